@@ -1,0 +1,159 @@
+/*
+ * opttree.h -- C ABI of the MI355X (gfx950) hot path of one OPT-Tree decoding
+ * step (arxiv 2406.17276): greedy adaptive draft-tree construction
+ * (Sec. 3, Eq. 1-3, Algorithm 1) and the tree-masked attention the target
+ * model runs to verify the drafted nodes (Sec. 3, Algorithm 2).
+ *
+ * Conventions
+ *   - every function returns an int status (OT_OK or a negative OT_ERR_*),
+ *     never throws, never allocates or frees device memory;
+ *   - every tensor argument is a DEVICE pointer owned by the caller; parameter
+ *     structs are HOST pointers, read before the call returns;
+ *   - all work is enqueued on the caller's hipStream_t (passed as void*, NULL =
+ *     the default stream); calls are asynchronous, results are valid after the
+ *     stream has been synchronised;
+ *   - the library keeps no global device state: scratch lives in a caller-owned
+ *     workspace sized by the *_workspace_bytes query.  Concurrent calls must use
+ *     distinct workspaces;
+ *   - device pointers must be 16-byte aligned;
+ *   - arguments are validated on the host before anything is launched; an
+ *     invalid call enqueues nothing.
+ */
+#ifndef OPTTREE_H
+#define OPTTREE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define OT_API __attribute__((visibility("default")))
+
+#define OT_OK                       0
+#define OT_ERR_INVALID_ARG        (-1)  /* null pointer, non-positive size, misaligned pointer, bad stride */
+#define OT_ERR_UNSUPPORTED        (-2)  /* outside the limits below */
+#define OT_ERR_WORKSPACE_TOO_SMALL (-3)
+#define OT_ERR_HIP                (-4)  /* a HIP runtime call failed; see ot_last_hip_error() */
+
+#define OT_F32   0   /* IEEE binary32 */
+#define OT_BF16  1   /* bfloat16 */
+
+/* limits of this build */
+#define OT_MAX_NODES     256   /* n  */
+#define OT_MAX_TOPK       16   /* k  */
+#define OT_MAX_DEPTH      32   /* d  */
+#define OT_MAX_HEAD_DIM  128
+#define OT_MASK_WORDS(n) (((n) + 63) / 64)
+
+OT_API int ot_version(void);                       /* 100*major + minor */
+OT_API const char* ot_status_string(int status);   /* static string, never NULL */
+OT_API int ot_last_hip_error(void);                /* hipError_t of the last failed HIP call on this thread */
+
+/* ------------------------------------------------------------------------
+ * Draft-tree construction (Sec. 3; Algorithm 1 with a fixed number of
+ * drafting steps `depth`).
+ *
+ * Input: for every sequence b, drafting step t (0-based; step 0 expands the
+ * root) and frontier slot j < F_t, one row of `vocab` next-token logits of the
+ * draft model, where F_0 = 1 and F_{t+1} = min(n, k*F_t).  Row (b,t,j) starts
+ * at  logits + b*stride_seq + t*stride_depth + j*stride_row  (strides in
+ * elements; rows j >= F_t are never read).  p_d = softmax(row).
+ *
+ * Per row: the k most probable tokens become the node's children (equal logits:
+ * smaller token id first); a child's score is log p^ = score(parent) + log p_d
+ * (Eq. 2, root excluded).  Per step the F_{t+1} best candidates are kept (equal
+ * scores: smaller parent slot, then smaller rank) and numbered by
+ * (parent slot, rank).  Finally the n_out = min(n, sum_t F_t) best nodes of the
+ * whole pool are selected (equal scores: shallower, then smaller slot) and
+ * emitted in (depth, slot) order, so parents precede children.
+ * ---------------------------------------------------------------------- */
+typedef struct ot_build_params {
+    int32_t batch;          /* sequences, >= 1 */
+    int32_t vocab;          /* >= k */
+    int32_t depth;          /* drafting steps d, 1..OT_MAX_DEPTH */
+    int32_t k;              /* children considered per node, 1..OT_MAX_TOPK */
+    int32_t n;              /* node budget, 1..OT_MAX_NODES */
+    int32_t logits_dtype;   /* OT_F32 | OT_BF16 */
+    int64_t stride_seq, stride_depth, stride_row;   /* elements; stride_row >= vocab */
+} ot_build_params;
+
+typedef struct ot_tree_out {      /* device pointers, caller-owned; rows >= n_out are filled as noted */
+    int32_t*  token;    /* [batch][n]  vocabulary id of node i            (-1) */
+    int32_t*  parent;   /* [batch][n]  output index of the parent, -1 = child of the root (-1) */
+    int32_t*  depth;    /* [batch][n]  1..d; position id = position of the root + depth    (0) */
+    float*    score;    /* [batch][n]  log p^                                               (-inf) */
+    uint64_t* mask;     /* [batch][n][OT_MASK_WORDS(n)] bit j of row i: j is i or an ancestor of i (0) */
+    int32_t*  n_out;    /* [batch] */
+    double*   expect;   /* [batch]  E(A) = sum_i p^_i  (Eq. 3) */
+} ot_tree_out;
+
+OT_API size_t ot_build_workspace_bytes(const ot_build_params* p);   /* 0 if p is invalid */
+
+/* One-shot: all `depth` steps' rows are already in memory. */
+OT_API int ot_build_tree(const ot_build_params* p, const void* logits,
+                  void* workspace, size_t workspace_bytes,
+                  const ot_tree_out* out, void* hip_stream);
+
+/* Streaming form of the same computation: what a decoder calls between the
+ * draft model's forwards (the loop of Algorithm 1).  The strides of `p` are
+ * ignored by begin; each expand call passes its own.
+ *   ot_tree_begin   resets the builder kept in `workspace`;
+ *   ot_tree_expand  consumes the F_t rows of step t (row (b,j) at
+ *                   rows + b*stride_seq + j*stride_row) and writes the next
+ *                   frontier: token and parent slot of its F_{t+1} slots
+ *                   ([batch][n] each, entries >= F_{t+1} untouched); steps must
+ *                   be fed in order t = 0,1,..;
+ *   ot_tree_finalize selects and emits the tree over the steps fed so far.
+ * The three calls of one tree must use the same workspace and stream order. */
+OT_API int ot_tree_begin(const ot_build_params* p, void* workspace, size_t workspace_bytes, void* hip_stream);
+OT_API int ot_tree_expand(const ot_build_params* p, int32_t step, const void* rows,
+                   int64_t stride_seq, int64_t stride_row,
+                   void* workspace, size_t workspace_bytes,
+                   int32_t* frontier_token, int32_t* frontier_parent_slot, void* hip_stream);
+OT_API int ot_tree_finalize(const ot_build_params* p, int32_t steps_done,
+                     void* workspace, size_t workspace_bytes,
+                     const ot_tree_out* out, void* hip_stream);
+
+/* ------------------------------------------------------------------------
+ * Tree-masked verification attention (Algorithm 2: the target model's forward
+ * over T_opt with "the corresponding tree attention mask").
+ *
+ * For sequence b, query head h, node i:
+ *   O[b,h,i,:] = sum_j softmax_j(scale * Q[b,h,i,:] . K[b,h/g,j,:]) V[b,h/g,j,:]
+ * over j in {prefix rows 0..prefix_len[b]-1} U {tree rows j : bit j of mask[b][i]},
+ * g = q_heads / kv_heads.  A node whose row has no visible key yields zeros.
+ * The root token's K/V is the last prefix row.  Q and K arrive already
+ * position-encoded.  bf16 inputs use bf16 MFMA with fp32 accumulation and fp32
+ * softmax; f32 inputs use fp32 arithmetic throughout.
+ *
+ * Element (b,h,r,c) of a tensor is at base + b*s[0] + h*s[1] + r*s[2] + c
+ * (strides in elements, multiples of 16 bytes; last dimension contiguous).
+ * prefix_len[b] is clamped to [0, max_prefix] on the device.
+ * ---------------------------------------------------------------------- */
+typedef struct ot_attn_params {
+    int32_t batch, q_heads, kv_heads;   /* q_heads % kv_heads == 0 */
+    int32_t head_dim;                   /* 64 or 128 */
+    int32_t n;                          /* query rows = tree nodes, 1..OT_MAX_NODES */
+    int32_t max_prefix;                 /* rows allocated per (b, kv head) in K_prefix / V_prefix, >= 0 */
+    int32_t dtype;                      /* OT_F32 | OT_BF16, of Q, K, V and O */
+    float   softmax_scale;              /* 0 => 1/sqrt(head_dim) */
+    int64_t q_strides[3], kp_strides[3], vp_strides[3], kt_strides[3], vt_strides[3], o_strides[3];
+} ot_attn_params;
+
+OT_API size_t ot_attn_workspace_bytes(const ot_attn_params* p);     /* 0 if p is invalid */
+
+OT_API int ot_tree_verify_attention(const ot_attn_params* p,
+                             const void* Q,                          /* [batch][q_heads][n][head_dim] */
+                             const void* K_prefix, const void* V_prefix, /* [batch][kv_heads][max_prefix][head_dim]; may be NULL if max_prefix == 0 */
+                             const void* K_tree, const void* V_tree,     /* [batch][kv_heads][n][head_dim] */
+                             const int32_t* prefix_len,              /* [batch] */
+                             const uint64_t* mask,                   /* [batch][n][OT_MASK_WORDS(n)] */
+                             void* O,                                /* [batch][q_heads][n][head_dim] */
+                             void* workspace, size_t workspace_bytes, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OPTTREE_H */

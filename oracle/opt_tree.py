@@ -228,7 +228,6 @@ def build_tree(logits: np.ndarray, k: int, n: int, depth: int):
     Only the first F_t rows of depth t are read.  Returns finalize()'s dict plus
     the per-layer frontiers ('layers').
     """
-    logits = np.asarray(logits)
     b = TreeBuilder(k, n)
     for t in range(depth):
         F = b.frontier_score.shape[0]

@@ -1,0 +1,231 @@
+"""ctypes binding of libopttree.so: argument marshalling only.
+
+Function names mirror include/opttree.h.  PyTorch is used for device memory
+(tensors in, tensors out) and for the current HIP stream; every step of the
+path runs in the library's kernels.  There is no CPU fallback: if the library
+is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+OT_F32, OT_BF16 = 0, 1
+OT_MAX_NODES, OT_MAX_TOPK, OT_MAX_DEPTH = 256, 16, 32
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libopttree.so")
+_lib = None
+
+
+class OptTreeError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = lib().ot_status_string(status).decode()
+        if status == -4:
+            msg += f" (hipError {lib().ot_last_hip_error()})"
+        super().__init__(f"{where}: {msg} [{status}]")
+
+
+class BuildParams(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("vocab", C.c_int32), ("depth", C.c_int32), ("k", C.c_int32),
+                ("n", C.c_int32), ("logits_dtype", C.c_int32),
+                ("stride_seq", C.c_int64), ("stride_depth", C.c_int64), ("stride_row", C.c_int64)]
+
+
+class TreeOut(C.Structure):
+    _fields_ = [("token", C.c_void_p), ("parent", C.c_void_p), ("depth", C.c_void_p), ("score", C.c_void_p),
+                ("mask", C.c_void_p), ("n_out", C.c_void_p), ("expect", C.c_void_p)]
+
+
+class AttnParams(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("q_heads", C.c_int32), ("kv_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("n", C.c_int32), ("max_prefix", C.c_int32), ("dtype", C.c_int32), ("softmax_scale", C.c_float),
+                ("q_strides", C.c_int64 * 3), ("kp_strides", C.c_int64 * 3), ("vp_strides", C.c_int64 * 3),
+                ("kt_strides", C.c_int64 * 3), ("vt_strides", C.c_int64 * 3), ("o_strides", C.c_int64 * 3)]
+
+
+def lib():
+    """Open libopttree.so (once).  Raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise FileNotFoundError(
+                f"{_LIB_PATH} is missing: build it with `python -m paper_2406_17276_amd.build` "
+                "(there is no fallback path)")
+        L = C.CDLL(_LIB_PATH)
+        L.ot_version.restype = C.c_int
+        L.ot_status_string.restype = C.c_char_p
+        L.ot_status_string.argtypes = [C.c_int]
+        L.ot_last_hip_error.restype = C.c_int
+        L.ot_build_workspace_bytes.restype = C.c_size_t
+        L.ot_build_workspace_bytes.argtypes = [C.POINTER(BuildParams)]
+        L.ot_build_tree.restype = C.c_int
+        L.ot_build_tree.argtypes = [C.POINTER(BuildParams), C.c_void_p, C.c_void_p, C.c_size_t,
+                                    C.POINTER(TreeOut), C.c_void_p]
+        L.ot_tree_begin.restype = C.c_int
+        L.ot_tree_begin.argtypes = [C.POINTER(BuildParams), C.c_void_p, C.c_size_t, C.c_void_p]
+        L.ot_tree_expand.restype = C.c_int
+        L.ot_tree_expand.argtypes = [C.POINTER(BuildParams), C.c_int32, C.c_void_p, C.c_int64, C.c_int64,
+                                     C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.ot_tree_finalize.restype = C.c_int
+        L.ot_tree_finalize.argtypes = [C.POINTER(BuildParams), C.c_int32, C.c_void_p, C.c_size_t,
+                                       C.POINTER(TreeOut), C.c_void_p]
+        L.ot_attn_workspace_bytes.restype = C.c_size_t
+        L.ot_attn_workspace_bytes.argtypes = [C.POINTER(AttnParams)]
+        L.ot_tree_verify_attention.restype = C.c_int
+        L.ot_tree_verify_attention.argtypes = [C.POINTER(AttnParams)] + [C.c_void_p] * 9 + [C.c_size_t, C.c_void_p]
+        _lib = L
+    return _lib
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        raise OptTreeError(status, where)
+
+
+def _dtype_code(t) -> int:
+    import torch
+    if t.dtype == torch.float32:
+        return OT_F32
+    if t.dtype == torch.bfloat16:
+        return OT_BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _stream() -> int:
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+@dataclass
+class Tree:
+    token: "object"     # int32 [B, n]
+    parent: "object"    # int32 [B, n]
+    depth: "object"     # int32 [B, n]
+    score: "object"     # float32 [B, n]
+    mask: "object"      # int64 [B, n, W] (bit pattern of the uint64 words)
+    n_out: "object"     # int32 [B]
+    expect: "object"    # float64 [B]
+
+    def c_struct(self) -> TreeOut:
+        return TreeOut(self.token.data_ptr(), self.parent.data_ptr(), self.depth.data_ptr(), self.score.data_ptr(),
+                       self.mask.data_ptr(), self.n_out.data_ptr(), self.expect.data_ptr())
+
+
+def alloc_tree(batch: int, n: int, device="cuda") -> Tree:
+    import torch
+    W = (n + 63) // 64
+    return Tree(token=torch.empty((batch, n), dtype=torch.int32, device=device),
+                parent=torch.empty((batch, n), dtype=torch.int32, device=device),
+                depth=torch.empty((batch, n), dtype=torch.int32, device=device),
+                score=torch.empty((batch, n), dtype=torch.float32, device=device),
+                mask=torch.empty((batch, n, W), dtype=torch.int64, device=device),
+                n_out=torch.empty((batch,), dtype=torch.int32, device=device),
+                expect=torch.empty((batch,), dtype=torch.float64, device=device))
+
+
+def build_params(logits, k: int, n: int, depth: int) -> BuildParams:
+    """logits: [B, depth, n, V] (any strides with a contiguous last dimension)."""
+    if logits.dim() != 4 or logits.stride(3) != 1:
+        raise ValueError("logits must be [B, depth, n, V] with a contiguous last dimension")
+    B, d, nn, V = logits.shape
+    if d < depth or nn < min(n, max(1, nn)):
+        raise ValueError("logits tensor smaller than (depth, n)")
+    return BuildParams(B, V, depth, k, n, _dtype_code(logits), logits.stride(0), logits.stride(1), logits.stride(2))
+
+
+def build_workspace_bytes(p: BuildParams) -> int:
+    return int(lib().ot_build_workspace_bytes(C.byref(p)))
+
+
+def build_tree(logits, k: int, n: int, depth: int, out: Tree | None = None, workspace=None) -> Tree:
+    """ot_build_tree: one-shot draft-tree construction on the current stream."""
+    import torch
+    p = build_params(logits, k, n, depth)
+    need = build_workspace_bytes(p)
+    if need == 0:
+        _check(lib().ot_build_tree(C.byref(p), logits.data_ptr(), None, 0, None, None), "ot_build_tree")
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=logits.device)
+    if out is None:
+        out = alloc_tree(p.batch, n, logits.device)
+    o = out.c_struct()
+    _check(lib().ot_build_tree(C.byref(p), logits.data_ptr(), workspace.data_ptr(), workspace.numel(),
+                               C.byref(o), _stream()), "ot_build_tree")
+    return out
+
+
+class TreeStream:
+    """ot_tree_begin / ot_tree_expand / ot_tree_finalize for one batch of trees."""
+
+    def __init__(self, batch: int, vocab: int, k: int, n: int, depth: int, dtype_code: int, device="cuda"):
+        import torch
+        self.p = BuildParams(batch, vocab, depth, k, n, dtype_code, 0, 0, vocab)
+        need = build_workspace_bytes(self.p)
+        if need == 0:
+            _check(lib().ot_tree_begin(C.byref(self.p), None, 0, None), "ot_tree_begin")
+        self.ws = torch.empty(need, dtype=torch.uint8, device=device)
+        self.frontier_token = torch.full((batch, n), -1, dtype=torch.int32, device=device)
+        self.frontier_parent = torch.full((batch, n), -1, dtype=torch.int32, device=device)
+        self.step = 0
+        _check(lib().ot_tree_begin(C.byref(self.p), self.ws.data_ptr(), self.ws.numel(), _stream()), "ot_tree_begin")
+
+    def expand(self, rows):
+        """rows: [B, >=F_t, V]; returns (tokens, parent_slots) views of the next frontier [B, n]."""
+        if rows.dim() != 3 or rows.stride(2) != 1:
+            raise ValueError("rows must be [B, F, V] with a contiguous last dimension")
+        _check(lib().ot_tree_expand(C.byref(self.p), self.step, rows.data_ptr(), rows.stride(0), rows.stride(1),
+                                    self.ws.data_ptr(), self.ws.numel(), self.frontier_token.data_ptr(),
+                                    self.frontier_parent.data_ptr(), _stream()), "ot_tree_expand")
+        self.step += 1
+        return self.frontier_token, self.frontier_parent
+
+    def finalize(self, out: Tree | None = None) -> Tree:
+        if out is None:
+            out = alloc_tree(self.p.batch, self.p.n, self.ws.device)
+        o = out.c_struct()
+        _check(lib().ot_tree_finalize(C.byref(self.p), self.step, self.ws.data_ptr(), self.ws.numel(),
+                                      C.byref(o), _stream()), "ot_tree_finalize")
+        return out
+
+
+def attn_params(Q, K_prefix, V_prefix, K_tree, V_tree, max_prefix=None, softmax_scale: float = 0.0) -> AttnParams:
+    B, Hq, n, D = Q.shape
+    Hkv = K_tree.shape[1]
+    if max_prefix is None:
+        max_prefix = 0 if K_prefix is None else K_prefix.shape[2]
+
+    def st(t):
+        if t is None:
+            return (C.c_int64 * 3)(0, 0, D)
+        if t.stride(3) != 1:
+            raise ValueError("last dimension must be contiguous")
+        return (C.c_int64 * 3)(t.stride(0), t.stride(1), t.stride(2))
+
+    return AttnParams(B, Hq, Hkv, D, n, max_prefix, _dtype_code(Q), float(softmax_scale),
+                      st(Q), st(K_prefix), st(V_prefix), st(K_tree), st(V_tree), st(Q))
+
+
+def attn_workspace_bytes(p: AttnParams) -> int:
+    return int(lib().ot_attn_workspace_bytes(C.byref(p)))
+
+
+def tree_verify_attention(Q, K_prefix, V_prefix, K_tree, V_tree, prefix_len, mask, out=None, workspace=None,
+                          softmax_scale: float = 0.0):
+    """ot_tree_verify_attention on the current stream.  Q [B,Hq,n,D]; K/V_prefix [B,Hkv,Lmax,D] (or None);
+    K/V_tree [B,Hkv,n,D]; prefix_len int32 [B]; mask int64 [B,n,W]."""
+    import torch
+    p = attn_params(Q, K_prefix, V_prefix, K_tree, V_tree, softmax_scale=softmax_scale)
+    if out is None:
+        out = torch.empty_like(Q)
+    p.o_strides = (C.c_int64 * 3)(out.stride(0), out.stride(1), out.stride(2))
+    need = attn_workspace_bytes(p)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=Q.device)
+    ptr = lambda t: None if t is None else t.data_ptr()
+    _check(lib().ot_tree_verify_attention(
+        C.byref(p), ptr(Q), ptr(K_prefix), ptr(V_prefix), ptr(K_tree), ptr(V_tree), ptr(prefix_len), ptr(mask),
+        ptr(out), ptr(workspace), 0 if workspace is None else workspace.numel(), _stream()),
+        "ot_tree_verify_attention")
+    return out

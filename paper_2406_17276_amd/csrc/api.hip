@@ -1,0 +1,192 @@
+// C ABI of libopttree: argument validation, workspace carving and kernel sequencing.
+// No arithmetic of the method lives here.
+#include <string.h>
+
+#include "common.hpp"
+
+namespace ot {
+
+static thread_local int g_last_hip_error = 0;
+void set_last_hip_error(int e) { g_last_hip_error = e; }
+
+Frontier make_frontier(int k, int n, int depth) {
+    Frontier f;
+    memset(&f, 0, sizeof(f));
+    f.F[0] = 1;
+    f.row_start[0] = 0;
+    long long rows = 0, pool = 0;
+    for (int t = 0; t < depth; ++t) {
+        rows += f.F[t];
+        f.row_start[t + 1] = (int)rows;
+        const long long next = (long long)k * f.F[t];
+        f.F[t + 1] = (int)(next < n ? next : n);
+        pool += f.F[t + 1];
+    }
+    f.rows = (int)rows;
+    f.pool = (int)pool;
+    return f;
+}
+
+static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+static int validate_build(const ot_build_params* p, bool check_strides) {
+    if (!p) return OT_ERR_INVALID_ARG;
+    if (p->batch < 1 || p->vocab < 1 || p->depth < 1 || p->k < 1 || p->n < 1) return OT_ERR_INVALID_ARG;
+    if (p->k > p->vocab) return OT_ERR_INVALID_ARG;
+    if (p->logits_dtype != OT_F32 && p->logits_dtype != OT_BF16) return OT_ERR_INVALID_ARG;
+    if (p->k > OT_MAX_TOPK || p->n > OT_MAX_NODES || p->depth > OT_MAX_DEPTH) return OT_ERR_UNSUPPORTED;
+    if (scan_parts(p->vocab) > 8) return OT_ERR_UNSUPPORTED;
+    if (check_strides) {
+        if (p->stride_row < p->vocab || p->stride_depth < 0 || p->stride_seq < 0) return OT_ERR_INVALID_ARG;
+    }
+    return OT_OK;
+}
+
+BuildWorkspace carve_build_workspace(const ot_build_params& p, void* base) {
+    const Frontier f = make_frontier(p.k, p.n, p.depth);
+    const size_t rows = (size_t)p.batch * (size_t)(f.rows > p.n ? f.rows : p.n);
+    const size_t parts = (size_t)scan_parts(p.vocab);
+    const size_t k = (size_t)p.k;
+    const size_t pool = (size_t)p.batch * p.depth * p.n;
+    BuildWorkspace w;
+    memset(&w, 0, sizeof(w));
+    size_t off = 0;
+    char* b = (char*)base;
+    auto take = [&](size_t bytes) { char* q = b + off; off = align_up(off + bytes, 256); return (void*)q; };
+    w.row_lse = (double*)take(rows * 8);
+    w.row_topv = (float*)take(rows * k * 4);
+    w.row_topi = (int32_t*)take(rows * k * 4);
+    if (parts > 1) {
+        w.part_m = (float*)take(rows * parts * 4);
+        w.part_s = (double*)take(rows * parts * 8);
+        w.part_topv = (float*)take(rows * parts * k * 4);
+        w.part_topi = (int32_t*)take(rows * parts * k * 4);
+    }
+    w.pool_key = (unsigned long long*)take(pool * 8);
+    w.pool_tok = (int32_t*)take(pool * 4);
+    w.pool_par = (int32_t*)take(pool * 4);
+    w.bytes = off;
+    return w;
+}
+
+static int check_tree_out(const ot_tree_out* o) {
+    if (!o || !o->token || !o->parent || !o->depth || !o->score || !o->mask || !o->n_out || !o->expect)
+        return OT_ERR_INVALID_ARG;
+    if (((uintptr_t)o->mask % 8) || ((uintptr_t)o->expect % 8)) return OT_ERR_INVALID_ARG;
+    return OT_OK;
+}
+
+static SelectGeometry select_geometry(const ot_build_params& p, const Frontier& f) {
+    SelectGeometry g;
+    g.batch = p.batch; g.k = p.k; g.n = p.n; g.depth = p.depth;
+    g.rows_per_seq = f.rows;
+    for (int i = 0; i < OT_MAX_DEPTH + 2; ++i) { g.F[i] = f.F[i]; g.row_start[i] = f.row_start[i]; }
+    return g;
+}
+
+}  // namespace ot
+
+using namespace ot;
+
+extern "C" {
+
+int ot_version(void) { return 100; }
+
+const char* ot_status_string(int status) {
+    switch (status) {
+        case OT_OK: return "ok";
+        case OT_ERR_INVALID_ARG: return "invalid argument";
+        case OT_ERR_UNSUPPORTED: return "unsupported size or type";
+        case OT_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+        case OT_ERR_HIP: return "HIP runtime error";
+        default: return "unknown status";
+    }
+}
+
+int ot_last_hip_error(void) { return g_last_hip_error; }
+
+size_t ot_build_workspace_bytes(const ot_build_params* p) {
+    if (validate_build(p, false) != OT_OK) return 0;
+    return carve_build_workspace(*p, nullptr).bytes;
+}
+
+int ot_build_tree(const ot_build_params* p, const void* logits, void* workspace, size_t workspace_bytes,
+                  const ot_tree_out* out, void* hip_stream) {
+    int st = validate_build(p, true);
+    if (st != OT_OK) return st;
+    if (!logits || !workspace) return OT_ERR_INVALID_ARG;
+    if ((uintptr_t)workspace % 16) return OT_ERR_INVALID_ARG;
+    const int esize = p->logits_dtype == OT_BF16 ? 2 : 4;
+    if ((uintptr_t)logits % esize) return OT_ERR_INVALID_ARG;
+    st = check_tree_out(out);
+    if (st != OT_OK) return st;
+    const BuildWorkspace ws = carve_build_workspace(*p, workspace);
+    if (workspace_bytes < ws.bytes) return OT_ERR_WORKSPACE_TOO_SMALL;
+    const Frontier f = make_frontier(p->k, p->n, p->depth);
+    hipStream_t s = (hipStream_t)hip_stream;
+
+    ScanGeometry sg;
+    sg.batch = p->batch; sg.vocab = p->vocab; sg.k = p->k; sg.dtype = p->logits_dtype;
+    sg.nsteps = p->depth; sg.rows_per_seq = f.rows;
+    for (int i = 0; i < OT_MAX_DEPTH + 2; ++i) sg.row_start[i] = f.row_start[i];
+    sg.stride_seq = p->stride_seq; sg.stride_depth = p->stride_depth; sg.stride_row = p->stride_row;
+    st = launch_row_scan(sg, logits, ws, s);
+    if (st != OT_OK) return st;
+    return launch_tree_oneshot(select_geometry(*p, f), ws, *out, s);
+}
+
+int ot_tree_begin(const ot_build_params* p, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    (void)hip_stream;
+    int st = validate_build(p, false);
+    if (st != OT_OK) return st;
+    if (!workspace || (uintptr_t)workspace % 16) return OT_ERR_INVALID_ARG;
+    if (workspace_bytes < carve_build_workspace(*p, workspace).bytes) return OT_ERR_WORKSPACE_TOO_SMALL;
+    return OT_OK;   // every step overwrites the state it owns; nothing to clear
+}
+
+int ot_tree_expand(const ot_build_params* p, int32_t step, const void* rows, int64_t stride_seq, int64_t stride_row,
+                   void* workspace, size_t workspace_bytes, int32_t* frontier_token, int32_t* frontier_parent_slot,
+                   void* hip_stream) {
+    int st = validate_build(p, false);
+    if (st != OT_OK) return st;
+    if (step < 0 || step >= p->depth) return OT_ERR_INVALID_ARG;
+    if (!rows || !workspace || !frontier_token || !frontier_parent_slot) return OT_ERR_INVALID_ARG;
+    if ((uintptr_t)workspace % 16) return OT_ERR_INVALID_ARG;
+    const int esize = p->logits_dtype == OT_BF16 ? 2 : 4;
+    if ((uintptr_t)rows % esize) return OT_ERR_INVALID_ARG;
+    if (stride_row < p->vocab || stride_seq < 0) return OT_ERR_INVALID_ARG;
+    const BuildWorkspace ws = carve_build_workspace(*p, workspace);
+    if (workspace_bytes < ws.bytes) return OT_ERR_WORKSPACE_TOO_SMALL;
+    const Frontier f = make_frontier(p->k, p->n, p->depth);
+    hipStream_t s = (hipStream_t)hip_stream;
+
+    ScanGeometry sg;
+    sg.batch = p->batch; sg.vocab = p->vocab; sg.k = p->k; sg.dtype = p->logits_dtype;
+    sg.nsteps = 1; sg.rows_per_seq = f.F[step];
+    memset(sg.row_start, 0, sizeof(sg.row_start));
+    sg.row_start[1] = f.F[step];
+    sg.stride_seq = stride_seq; sg.stride_depth = 0; sg.stride_row = stride_row;
+    st = launch_row_scan(sg, rows, ws, s);
+    if (st != OT_OK) return st;
+    SelectGeometry g = select_geometry(*p, f);
+    g.rows_per_seq = f.F[step];
+    return launch_tree_step(g, step, ws, frontier_token, frontier_parent_slot, s);
+}
+
+int ot_tree_finalize(const ot_build_params* p, int32_t steps_done, void* workspace, size_t workspace_bytes,
+                     const ot_tree_out* out, void* hip_stream) {
+    int st = validate_build(p, false);
+    if (st != OT_OK) return st;
+    if (steps_done < 1 || steps_done > p->depth) return OT_ERR_INVALID_ARG;
+    if (!workspace || (uintptr_t)workspace % 16) return OT_ERR_INVALID_ARG;
+    st = check_tree_out(out);
+    if (st != OT_OK) return st;
+    const BuildWorkspace ws = carve_build_workspace(*p, workspace);
+    if (workspace_bytes < ws.bytes) return OT_ERR_WORKSPACE_TOO_SMALL;
+    const Frontier f = make_frontier(p->k, p->n, p->depth);
+    return launch_tree_finalize(select_geometry(*p, f), steps_done, ws, *out, (hipStream_t)hip_stream);
+}
+
+
+
+}  // extern "C"

@@ -1,0 +1,324 @@
+// Row scan: for every logits row of the draft model, one pass over the row yields
+//   lse  = log sum_v exp(x_v)            (normaliser of p_d = softmax(row), Sec. 2 "Inference")
+//   top-k tokens by logit, equal logits -> smaller token id   (children of a node, Sec. 3 after Eq. 2)
+// This is the HBM-bound part of tree construction: every element is read exactly once,
+// 16 bytes per lane per load, and held in registers for both the maximum and the exp-sum.
+//
+// One workgroup handles one "part" (<= 32768 elements) of one row.  Inside a workgroup:
+//   1. every lane loads its 32 elements (all loads are issued before the first use),
+//   2. lane max -> 16 group maxima (one per 1/16th of the workgroup) -> LDS;
+//      M = max of them is the exp reference, tau = min of them is a lower bound of the
+//      16th largest element (each group holds an element >= tau), hence of the k-th (k <= 16),
+//   3. one sweep over the registers: s += exp(x - M); elements >= tau go to an LDS candidate list,
+//   4. the k best candidates are ranked by counting (value desc, token asc),
+//   5. part results are written; rows split over several parts are merged by merge_parts_kernel.
+// If the candidate list overflows (massive ties), a slow exact path extracts the k best
+// by k rounds of a workgroup-wide arg-max over the registers.
+#include "common.hpp"
+
+namespace ot {
+namespace {
+
+constexpr int kCandCap = 2048;
+constexpr float kLog2e = 1.4426950408889634f;
+
+struct ScanKArgs {
+    const void* logits;
+    int vocab, k, parts, part_elems;
+    int nsteps, rows_per_seq;
+    int row_start[OT_MAX_DEPTH + 2];
+    long long stride_seq, stride_depth, stride_row;
+    // P == 1: final row results; P > 1: per-part results
+    double* row_lse; float* row_topv; int32_t* row_topi;
+    float* part_m; double* part_s; float* part_topv; int32_t* part_topi;
+};
+
+__device__ __forceinline__ unsigned int f32_key(float v) {
+    unsigned int u = __float_as_uint(v);
+    return (u >> 31) ? ~u : (u | 0x80000000u);
+}
+
+template <int DT, int NT, bool VECLOAD>
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu((NT == 1024 && VECLOAD) ? 8 : 4, 8))) void row_scan_kernel(const ScanKArgs a) {
+    constexpr int VEC = (DT == OT_BF16) ? 8 : 4;
+    constexpr int EPL = 32;             // elements per lane
+    constexpr int VPL = EPL / VEC;      // 16-byte vectors per lane
+    constexpr int NW = NT / 64;
+
+    __shared__ float s_gmax[16];
+    __shared__ double s_wsum[16];
+    __shared__ float s_cv[kCandCap];
+    __shared__ int s_ci[kCandCap];
+    __shared__ int s_rank[kCandCap];
+    __shared__ int s_count;
+    __shared__ unsigned long long s_best[16];
+
+    const int tid = threadIdx.x;
+    const int wg = blockIdx.x;
+    const int rid = wg / a.parts;
+    const int part = wg - rid * a.parts;
+    const int b = rid / a.rows_per_seq;
+    const int r = rid - b * a.rows_per_seq;
+    int t = 0;
+    while (t + 1 < a.nsteps && r >= a.row_start[t + 1]) ++t;
+    const int j = r - a.row_start[t];
+    const long long row_off = (long long)b * a.stride_seq + (long long)t * a.stride_depth + (long long)j * a.stride_row;
+    const int e_begin = part * a.part_elems;
+    const int e_end = min(a.vocab, e_begin + a.part_elems);
+
+    if (tid == 0) s_count = 0;
+    for (int i = tid; i < kCandCap; i += NT) s_rank[i] = 0;
+
+    // ---- 1. load ----------------------------------------------------------
+    // VECLOAD: the host guarantees 16-byte aligned rows and vocab % VEC == 0, so a vector is
+    // either wholly inside the part or wholly outside.  Otherwise: guarded scalar loads.
+    float x[EPL];
+    if (DT == OT_BF16) {
+        const unsigned short* row = (const unsigned short*)a.logits + row_off;
+#pragma unroll
+        for (int i = 0; i < VPL; ++i) {
+            const int e0 = e_begin + (i * NT + tid) * VEC;
+            if (VECLOAD) {
+                u32x4 w = {0xff80ff80u, 0xff80ff80u, 0xff80ff80u, 0xff80ff80u};   // -inf pairs
+                if (e0 < e_end) w = __builtin_nontemporal_load((const u32x4*)(row + e0));
+                x[i * 8 + 0] = bf16_lo(w.x); x[i * 8 + 1] = bf16_hi(w.x);
+                x[i * 8 + 2] = bf16_lo(w.y); x[i * 8 + 3] = bf16_hi(w.y);
+                x[i * 8 + 4] = bf16_lo(w.z); x[i * 8 + 5] = bf16_hi(w.z);
+                x[i * 8 + 6] = bf16_lo(w.w); x[i * 8 + 7] = bf16_hi(w.w);
+            } else {
+#pragma unroll
+                for (int c = 0; c < VEC; ++c)
+                    x[i * 8 + c] = (e0 + c < e_end) ? __uint_as_float((unsigned)row[e0 + c] << 16) : -INFINITY;
+            }
+        }
+    } else {
+        const float* row = (const float*)a.logits + row_off;
+#pragma unroll
+        for (int i = 0; i < VPL; ++i) {
+            const int e0 = e_begin + (i * NT + tid) * VEC;
+            if (VECLOAD) {
+                f32x4 w = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+                if (e0 < e_end) w = __builtin_nontemporal_load((const f32x4*)(row + e0));
+                x[i * 4 + 0] = w.x; x[i * 4 + 1] = w.y; x[i * 4 + 2] = w.z; x[i * 4 + 3] = w.w;
+            } else {
+#pragma unroll
+                for (int c = 0; c < VEC; ++c) x[i * 4 + c] = (e0 + c < e_end) ? row[e0 + c] : -INFINITY;
+            }
+        }
+    }
+
+    // ---- 2. maxima --------------------------------------------------------
+    float m = x[0];
+#pragma unroll
+    for (int i = 1; i < EPL; ++i) m = fmaxf(m, x[i]);
+    if (NT == 1024) {
+        const float g = wave_max(m);
+        if ((tid & 63) == 0) s_gmax[tid >> 6] = g;
+    } else {
+        const float g = row16_max(m);
+        if ((tid & 15) == 0) s_gmax[tid >> 4] = g;
+    }
+    __syncthreads();
+    float M = s_gmax[0], tau = s_gmax[0];
+#pragma unroll
+    for (int i = 1; i < 16; ++i) {
+        M = fmaxf(M, s_gmax[i]);
+        tau = fminf(tau, s_gmax[i]);
+    }
+
+    // ---- 3. exp-sum and candidates ---------------------------------------
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int i = 0; i < VPL; ++i) {
+#pragma unroll
+        for (int c = 0; c < VEC; ++c) {
+            const float v = x[i * VEC + c];
+            acc[c & 3] += __builtin_amdgcn_exp2f((v - M) * kLog2e);
+            if (v >= tau) {
+                const int e = e_begin + (i * NT + tid) * VEC + c;
+                if (e < e_end) {
+                    const int p = atomicAdd(&s_count, 1);
+                    if (p < kCandCap) { s_cv[p] = v; s_ci[p] = e; }
+                }
+            }
+        }
+    }
+    double s = (double)(acc[0] + acc[1]) + (double)(acc[2] + acc[3]);
+    s = wave_sum(s);
+    if ((tid & 63) == 0) s_wsum[tid >> 6] = s;
+    __syncthreads();
+    const int ncand = s_count;
+
+    // where the k winners of this part go
+    float* outv; int32_t* outi;
+    if (a.parts == 1) {
+        outv = a.row_topv + (size_t)rid * a.k;
+        outi = a.row_topi + (size_t)rid * a.k;
+    } else {
+        outv = a.part_topv + (size_t)wg * a.k;
+        outi = a.part_topi + (size_t)wg * a.k;
+    }
+    if (tid == 0) {
+        double tot = 0.0;
+        for (int w = 0; w < NW; ++w) tot += s_wsum[w];
+        if (a.parts == 1) {
+            a.row_lse[rid] = (double)M + log(tot);
+        } else {
+            a.part_m[wg] = M;
+            a.part_s[wg] = tot;
+        }
+    }
+
+    // ---- 4. rank the candidates ------------------------------------------
+    if (ncand <= kCandCap) {
+        int cp = 64;
+        while (cp < ncand) cp <<= 1;
+        const int q_cnt = (NT / cp) > 0 ? (NT / cp) : 1;   // slices of the inner loop per candidate
+        if (cp <= NT) {
+            const int i = tid & (cp - 1);
+            const int q = tid / cp;
+            if (i < ncand) {
+                const float v = s_cv[i];
+                const int id = s_ci[i];
+                int rank = 0;
+                for (int jj = q; jj < ncand; jj += q_cnt) {
+                    const float u = s_cv[jj];
+                    const int ui = s_ci[jj];
+                    rank += (u > v || (u == v && ui < id)) ? 1 : 0;
+                }
+                if (q_cnt > 1) atomicAdd(&s_rank[i], rank); else s_rank[i] = rank;
+            }
+        } else {
+            for (int i = tid; i < ncand; i += NT) {
+                const float v = s_cv[i];
+                const int id = s_ci[i];
+                int rank = 0;
+                for (int jj = 0; jj < ncand; ++jj) {
+                    const float u = s_cv[jj];
+                    const int ui = s_ci[jj];
+                    rank += (u > v || (u == v && ui < id)) ? 1 : 0;
+                }
+                s_rank[i] = rank;
+            }
+        }
+        __syncthreads();
+        for (int i = tid; i < ncand; i += NT) {
+            const int rank = s_rank[i];
+            if (rank < a.k) { outv[rank] = s_cv[i]; outi[rank] = s_ci[i]; }
+        }
+        return;
+    }
+
+    // ---- slow exact path: k rounds of arg-max, re-reading the part from memory ----
+    float prev_v = INFINITY;
+    int prev_i = -1;
+    for (int round = 0; round < a.k; ++round) {
+        unsigned long long best = 0ull;
+        for (int e = e_begin + tid; e < e_end; e += NT) {
+            float v;
+            if (DT == OT_BF16) v = __uint_as_float((unsigned)((const unsigned short*)a.logits + row_off)[e] << 16);
+            else v = ((const float*)a.logits + row_off)[e];
+            const bool after = (v < prev_v) || (v == prev_v && e > prev_i);
+            if (after) {
+                const unsigned long long key =
+                    ((unsigned long long)f32_key(v) << 32) | (unsigned long long)(0xffffffffu - (unsigned)e);
+                best = key > best ? key : best;
+            }
+        }
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const unsigned long long other = __shfl_xor(best, o);
+            best = other > best ? other : best;
+        }
+        __syncthreads();
+        if ((tid & 63) == 0) s_best[tid >> 6] = best;
+        __syncthreads();
+        best = s_best[0];
+        for (int w = 1; w < NW; ++w) best = s_best[w] > best ? s_best[w] : best;
+        if (best == 0ull) break;      // fewer than k valid elements in this part
+        const unsigned int fk = (unsigned int)(best >> 32);
+        const unsigned int fu = (fk >> 31) ? (fk & 0x7fffffffu) : ~fk;
+        prev_v = __uint_as_float(fu);
+        prev_i = (int)(0xffffffffu - (unsigned)(best & 0xffffffffu));
+        if (tid == 0) { outv[round] = prev_v; outi[round] = prev_i; }
+    }
+}
+
+// Rows that span several parts: combine the per-part (max, sum) pairs and merge the
+// per-part sorted top-k lists.  One thread per row.
+__global__ void merge_parts_kernel(int rows, int parts, int k, const float* part_m, const double* part_s,
+                                   const float* part_topv, const int32_t* part_topi, double* row_lse,
+                                   float* row_topv, int32_t* row_topi) {
+    const int rid = blockIdx.x * blockDim.x + threadIdx.x;
+    if (rid >= rows) return;
+    const size_t base = (size_t)rid * parts;
+    float M = part_m[base];
+    for (int p = 1; p < parts; ++p) M = fmaxf(M, part_m[base + p]);
+    double s = 0.0;
+    for (int p = 0; p < parts; ++p) s += part_s[base + p] * exp((double)part_m[base + p] - (double)M);
+    row_lse[rid] = (double)M + log(s);
+    // k-way merge of sorted lists; heads[] are positions inside each part's list
+    int head[8];
+    for (int p = 0; p < 8; ++p) head[p] = 0;
+    for (int r = 0; r < k; ++r) {
+        int bp = -1; float bv = 0.f; int bi = 0;
+        for (int p = 0; p < parts; ++p) {
+            if (head[p] >= k) continue;
+            const float v = part_topv[(base + p) * k + head[p]];
+            const int id = part_topi[(base + p) * k + head[p]];
+            if (bp < 0 || v > bv || (v == bv && id < bi)) { bp = p; bv = v; bi = id; }
+        }
+        row_topv[(size_t)rid * k + r] = bv;
+        row_topi[(size_t)rid * k + r] = bi;
+        head[bp]++;
+    }
+}
+
+}  // namespace
+
+int launch_row_scan(const ScanGeometry& g, const void* logits, const BuildWorkspace& ws, hipStream_t s) {
+    const int parts = scan_parts(g.vocab);
+    if (parts > 8) return OT_ERR_UNSUPPORTED;
+    const int esize = g.dtype == OT_BF16 ? 2 : 4;
+    const int vec = 16 / esize;
+    ScanKArgs a;
+    a.logits = logits;
+    a.vocab = g.vocab; a.k = g.k; a.parts = parts;
+    const int per = (g.vocab + parts - 1) / parts;
+    a.part_elems = (per + vec - 1) / vec * vec;
+    a.nsteps = g.nsteps; a.rows_per_seq = g.rows_per_seq;
+    for (int i = 0; i < OT_MAX_DEPTH + 2; ++i) a.row_start[i] = g.row_start[i];
+    a.stride_seq = g.stride_seq; a.stride_depth = g.stride_depth; a.stride_row = g.stride_row;
+    a.row_lse = ws.row_lse; a.row_topv = ws.row_topv; a.row_topi = ws.row_topi;
+    a.part_m = ws.part_m; a.part_s = ws.part_s; a.part_topv = ws.part_topv; a.part_topi = ws.part_topi;
+
+    const bool aligned = ((uintptr_t)logits % 16 == 0) && (g.stride_seq % vec == 0) && (g.stride_depth % vec == 0) &&
+                         (g.stride_row % vec == 0) && (g.vocab % vec == 0);
+    const bool small = a.part_elems <= 256 * 32;
+    const long long rows = (long long)g.batch * g.rows_per_seq;
+    const long long grid = rows * parts;
+    if (grid <= 0 || grid > 0x7fffffffLL) return OT_ERR_UNSUPPORTED;
+    const dim3 gd((unsigned)grid);
+
+#define OT_SCAN_LAUNCH(DT, NT, VL) \
+    hipLaunchKernelGGL((row_scan_kernel<DT, NT, VL>), gd, dim3(NT), 0, s, a)
+    if (g.dtype == OT_BF16) {
+        if (small) { if (aligned) OT_SCAN_LAUNCH(OT_BF16, 256, true); else OT_SCAN_LAUNCH(OT_BF16, 256, false); }
+        else       { if (aligned) OT_SCAN_LAUNCH(OT_BF16, 1024, true); else OT_SCAN_LAUNCH(OT_BF16, 1024, false); }
+    } else {
+        if (small) { if (aligned) OT_SCAN_LAUNCH(OT_F32, 256, true); else OT_SCAN_LAUNCH(OT_F32, 256, false); }
+        else       { if (aligned) OT_SCAN_LAUNCH(OT_F32, 1024, true); else OT_SCAN_LAUNCH(OT_F32, 1024, false); }
+    }
+#undef OT_SCAN_LAUNCH
+    OT_HIP_CHECK(hipGetLastError());
+    if (parts > 1) {
+        const int threads = 128;
+        hipLaunchKernelGGL(merge_parts_kernel, dim3((unsigned)((rows + threads - 1) / threads)), dim3(threads), 0, s,
+                           (int)rows, parts, g.k, ws.part_m, ws.part_s, ws.part_topv, ws.part_topi, ws.row_lse,
+                           ws.row_topv, ws.row_topi);
+        OT_HIP_CHECK(hipGetLastError());
+    }
+    return OT_OK;
+}
+
+}  // namespace ot

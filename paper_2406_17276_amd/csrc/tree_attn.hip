@@ -1,0 +1,556 @@
+// Tree-masked verification attention (Algorithm 2: the target model's forward over the
+// drafted nodes with the tree attention mask).  For node i of sequence b and query head h:
+//   O[i] = sum_j softmax_j(scale q_i.k_j) v_j,  j over the cached prefix and the tree rows
+//   that are i itself or an ancestor of i (bit j of mask[b][i]).
+//
+// The keys of one (sequence, KV head) are cut into 64-key tiles: ceil(L_b/64) prefix tiles,
+// then ceil(n/64) tree tiles.  Contiguous tile ranges ("splits") go to different workgroups so
+// that a single small sequence still fills the chip; every split leaves an un-normalised
+// partial (running max m in log2 units, sum l, O) that attn_combine_kernel merges.
+//
+// bf16 path (attn_mfma_kernel): one workgroup = 64 packed query rows of one KV head (GQA: the
+// g = q_heads/kv_heads query heads that share the KV head are stacked, row = head*n + node)
+// and 4 wavefronts = 2 query blocks of 32 rows x 2 halves of each 64-key tile.  Each wavefront
+//   S^T = K Q^T   v_mfma_f32_32x32x16_bf16, A = K rows from LDS, B = Q held in registers;
+//                 the accumulator leaves every lane with 16 scores of ONE query, so the
+//                 online-softmax statistics and the rescale factor are per-lane scalars;
+//   O^T += V^T P^T  same instruction, B = P straight from the S^T accumulators (the key order
+//                 inside a 16-key slab is whatever the accumulator layout gives; V is read in
+//                 the same order), A = V gathered from LDS.
+// K/V tiles are fetched 16 bytes per lane into registers one tile ahead and staged through LDS.
+// The ancestor mask is applied as a bit test on tree tiles only; prefix tiles only mask the tail.
+//
+// f32 path (attn_f32_kernel): plain fp32 FMA arithmetic, 16 query rows x 32-key tiles.
+#include <math.h>
+
+#include "common.hpp"
+
+namespace ot {
+namespace {
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr int kMaxSplits = 32;
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+struct AttnKArgs {
+    const void *Q, *Kp, *Vp, *Kt, *Vt;
+    const int32_t* prefix_len;
+    const uint64_t* mask;
+    void* O;
+    float* part_o;      // [rows_total][splits][D]
+    float* part_ml;     // [rows_total][splits][2]
+    int batch, q_heads, kv_heads, g, n, D, max_prefix, splits, W, dtype;
+    float scale_log2;   // softmax scale * log2(e)
+    long long qs[3], kps[3], vps[3], kts[3], vts[3], os[3];
+};
+
+__device__ __forceinline__ int clamp_len(int L, int maxp) { return L < 0 ? 0 : (L > maxp ? maxp : L); }
+
+// Tile range of split s out of S over T tiles.
+__device__ __forceinline__ void split_range(int T, int S, int s, int& t0, int& t1) {
+    t0 = (int)(((long long)T * s) / S);
+    t1 = (int)(((long long)T * (s + 1)) / S);
+}
+
+// ---------------------------------------------------------------------------
+// bf16 MFMA kernel
+// ---------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(256) void attn_mfma_kernel(const AttnKArgs a) {
+    constexpr int TK = 64;                 // keys per tile
+    constexpr int KPAD = D + 8;            // bf16 elements per K row in LDS
+    constexpr int VPAD = D + 8;
+    constexpr int SLABS = D / 16;          // 16-wide d slabs of the QK^T contraction
+    constexpr int DB = D / 32;             // 32-wide d blocks of O^T
+    constexpr int CH = TK * D / 8 / 256;   // 16-byte chunks per thread per tile (K or V)
+
+    __shared__ __attribute__((aligned(16))) unsigned short s_buf[TK * (KPAD + VPAD)];
+    unsigned short* const s_k = s_buf;
+    unsigned short* const s_v = s_buf + TK * KPAD;
+    static_assert(sizeof(unsigned short) * TK * (KPAD + VPAD) >= 2 * 64 * (DB * 16 + 2) * 4, "merge buffer fits");
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int qb = wave & 1, kh = wave >> 1;
+    const int l32 = lane & 31, h = lane >> 5;
+    const int split = blockIdx.x, rb = blockIdx.y;
+    const int b = blockIdx.z / a.kv_heads, hk = blockIdx.z - b * a.kv_heads;
+    const int n = a.n;
+    const int L = clamp_len(a.prefix_len[b], a.max_prefix);
+    const int ptiles = (L + TK - 1) / TK, ttiles = (n + TK - 1) / TK;
+    int t0, t1;
+    split_range(ptiles + ttiles, a.splits, split, t0, t1);
+
+    // this lane's query row
+    const int rho = rb * 64 + qb * 32 + l32;           // packed row inside the KV head
+    const bool row_ok = rho < a.g * n;
+    const int hq = hk * a.g + (row_ok ? rho / n : 0);
+    const int node = row_ok ? rho % n : 0;
+
+    // Q fragments: B operand of S^T = K Q^T; lane holds Q[row][16 s + 8 h .. +7]
+    bf16x8 qf[SLABS];
+    {
+        const unsigned short* qrow =
+            (const unsigned short*)a.Q + (long long)b * a.qs[0] + (long long)hq * a.qs[1] + (long long)node * a.qs[2];
+#pragma unroll
+        for (int s = 0; s < SLABS; ++s) {
+            u32x4 w = {0u, 0u, 0u, 0u};
+            if (row_ok) w = *(const u32x4*)(qrow + 16 * s + 8 * h);
+            qf[s] = __builtin_bit_cast(bf16x8, w);
+        }
+    }
+    // this lane's ancestor mask row
+    uint64_t mrow[4] = {0ull, 0ull, 0ull, 0ull};
+    if (row_ok)
+        for (int w = 0; w < a.W; ++w) mrow[w] = a.mask[((long long)b * n + node) * a.W + w];
+
+    const unsigned short* kp = (const unsigned short*)a.Kp + (long long)b * a.kps[0] + (long long)hk * a.kps[1];
+    const unsigned short* vp = (const unsigned short*)a.Vp + (long long)b * a.vps[0] + (long long)hk * a.vps[1];
+    const unsigned short* kt = (const unsigned short*)a.Kt + (long long)b * a.kts[0] + (long long)hk * a.kts[1];
+    const unsigned short* vt = (const unsigned short*)a.Vt + (long long)b * a.vts[0] + (long long)hk * a.vts[1];
+
+    float m_run = -INFINITY, l_run = 0.f;
+    f32x16 oacc[DB];
+#pragma unroll
+    for (int d = 0; d < DB; ++d)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) oacc[d][v] = 0.f;
+
+    u32x4 kreg[CH], vreg[CH];
+    auto fetch = [&](int t) {
+        const bool tree = t >= ptiles;
+        const int key0 = tree ? (t - ptiles) * TK : t * TK;
+        const int kend = tree ? n : L;
+        const unsigned short* kb = tree ? kt : kp;
+        const unsigned short* vb = tree ? vt : vp;
+        const long long ks = tree ? a.kts[2] : a.kps[2];
+        const long long vs = tree ? a.vts[2] : a.vps[2];
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+            const int chunk = c * 256 + tid;
+            const int key = chunk / (D / 8), col = (chunk % (D / 8)) * 8;
+            u32x4 kw = {0u, 0u, 0u, 0u}, vw = {0u, 0u, 0u, 0u};
+            if (key0 + key < kend) {
+                kw = *(const u32x4*)(kb + (long long)(key0 + key) * ks + col);
+                vw = *(const u32x4*)(vb + (long long)(key0 + key) * vs + col);
+            }
+            kreg[c] = kw;
+            vreg[c] = vw;
+        }
+    };
+
+    if (t0 < t1) fetch(t0);
+    for (int t = t0; t < t1; ++t) {
+        // stage the fetched tile
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+            const int chunk = c * 256 + tid;
+            const int key = chunk / (D / 8), col = (chunk % (D / 8)) * 8;
+            *(u32x4*)(s_k + key * KPAD + col) = kreg[c];
+            *(u32x4*)(s_v + key * VPAD + col) = vreg[c];
+        }
+        __syncthreads();
+        if (t + 1 < t1) fetch(t + 1);
+
+        const bool tree = t >= ptiles;
+        const int key0 = tree ? (t - ptiles) * TK : t * TK;
+        const int kend = tree ? n : L;
+
+        // S^T block: 32 keys (this wave's half of the tile) x 32 queries
+        f32x16 sacc;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) sacc[v] = 0.f;
+#pragma unroll
+        for (int s = 0; s < SLABS; ++s) {
+            const u32x4 kw = *(const u32x4*)(s_k + (32 * kh + l32) * KPAD + 16 * s + 8 * h);
+            sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kw), qf[s], sacc, 0, 0, 0);
+        }
+        // mask and online softmax; accumulator element v is key 32 kh + 8 (v/4) + 4 h + v%4
+        float sc[16];
+        float tmax = -INFINITY;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int kl = 32 * kh + 8 * (v >> 2) + 4 * h + (v & 3);
+            const int key = key0 + kl;
+            bool ok = key < kend;
+            if (tree) ok = ok && ((mrow[key >> 6] >> (key & 63)) & 1ull);
+            sc[v] = ok ? sacc[v] * a.scale_log2 : -INFINITY;
+            tmax = fmaxf(tmax, sc[v]);
+        }
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+        const float m_new = fmaxf(m_run, tmax);
+        float alpha = 1.f;
+        bf16x8 pf[2];
+        if (m_new == -INFINITY) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) pf[v >> 3][v & 7] = (__bf16)0.f;
+        } else {
+            alpha = __builtin_amdgcn_exp2f(m_run - m_new);      // m_run = -inf gives 0
+            float psum = 0.f;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const float p = __builtin_amdgcn_exp2f(sc[v] - m_new);
+                psum += p;
+                pf[v >> 3][v & 7] = (__bf16)p;
+            }
+            l_run = l_run * alpha + psum;
+            m_run = m_new;
+        }
+#pragma unroll
+        for (int d = 0; d < DB; ++d)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) oacc[d][v] *= alpha;
+        // O^T += V^T P^T over the wave's 32 keys: two 16-key slabs
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+#pragma unroll
+            for (int d = 0; d < DB; ++d) {
+                bf16x8 vf;
+#pragma unroll
+                for (int p = 0; p < 8; ++p) {
+                    const int kl = 32 * kh + 16 * u + 8 * (p >> 2) + 4 * h + (p & 3);
+                    const unsigned short raw = s_v[kl * VPAD + 32 * d + l32];
+                    vf[p] = __builtin_bit_cast(__bf16, raw);
+                }
+                oacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[u], oacc[d], 0, 0, 0);
+            }
+        }
+        __syncthreads();
+    }
+
+    // merge the two key-half waves of each query block through LDS (tile buffers are free now)
+    l_run += __shfl_xor(l_run, 32);
+    float* s_merge = (float*)s_buf;          // [2 qb][64 lanes][DB*16 + 2]
+    constexpr int MST = DB * 16 + 2;
+    if (kh == 1) {
+        float* dst = s_merge + (qb * 64 + lane) * MST;
+#pragma unroll
+        for (int d = 0; d < DB; ++d)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) dst[d * 16 + v] = oacc[d][v];
+        dst[DB * 16] = m_run;
+        dst[DB * 16 + 1] = l_run;
+    }
+    __syncthreads();
+    if (kh == 0) {
+        const float* src = s_merge + (qb * 64 + lane) * MST;
+        const float m2 = src[DB * 16], l2 = src[DB * 16 + 1];
+        const float mm = fmaxf(m_run, m2);
+        float a1 = 0.f, a2 = 0.f;
+        if (mm != -INFINITY) {
+            a1 = __builtin_amdgcn_exp2f(m_run - mm);
+            a2 = __builtin_amdgcn_exp2f(m2 - mm);
+        }
+        const float lt = l_run * a1 + l2 * a2;
+        if (row_ok) {
+            const long long row = ((long long)b * a.q_heads + hq) * n + node;
+            if (a.splits == 1) {
+                const float inv = lt > 0.f ? 1.f / lt : 0.f;
+                unsigned short* orow =
+                    (unsigned short*)a.O + (long long)b * a.os[0] + (long long)hq * a.os[1] + (long long)node * a.os[2];
+#pragma unroll
+                for (int d = 0; d < DB; ++d)
+#pragma unroll
+                    for (int v4 = 0; v4 < 4; ++v4) {
+                        unsigned short o4[4];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const int v = v4 * 4 + e;
+                            const float val = (oacc[d][v] * a1 + src[d * 16 + v] * a2) * inv;
+                            o4[e] = __builtin_bit_cast(unsigned short, (__bf16)val);
+                        }
+                        uint2 pk;
+                        pk.x = (unsigned)o4[0] | ((unsigned)o4[1] << 16);
+                        pk.y = (unsigned)o4[2] | ((unsigned)o4[3] << 16);
+                        *(uint2*)(orow + 32 * d + 8 * v4 + 4 * h) = pk;
+                    }
+            } else {
+                float* po = a.part_o + (row * a.splits + split) * D;
+#pragma unroll
+                for (int d = 0; d < DB; ++d)
+#pragma unroll
+                    for (int v4 = 0; v4 < 4; ++v4) {
+                        f32x4 o4;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const int v = v4 * 4 + e;
+                            o4[e] = oacc[d][v] * a1 + src[d * 16 + v] * a2;
+                        }
+                        *(f32x4*)(po + 32 * d + 8 * v4 + 4 * h) = o4;
+                    }
+                if (h == 0) {
+                    a.part_ml[(row * a.splits + split) * 2] = mm;
+                    a.part_ml[(row * a.splits + split) * 2 + 1] = lt;
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// f32 kernel: 16 query rows of one query head x 32-key tiles, fp32 FMA arithmetic
+// ---------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(256) void attn_f32_kernel(const AttnKArgs a) {
+    constexpr int TK = 32, RB = 16;
+    constexpr int KPAD = D + 4;
+    constexpr int EPT = D / 16;            // output columns per thread
+    __shared__ __attribute__((aligned(16))) float s_q[RB * D];
+    __shared__ __attribute__((aligned(16))) float s_k[TK * KPAD];
+    __shared__ __attribute__((aligned(16))) float s_v[TK * D];
+    __shared__ float s_p[RB * TK];
+
+    const int tid = threadIdx.x, r = tid >> 4, c = tid & 15;
+    const int split = blockIdx.x, rb = blockIdx.y;
+    const int b = blockIdx.z / a.q_heads, hq = blockIdx.z - b * a.q_heads;
+    const int hk = hq / a.g;
+    const int n = a.n;
+    const int L = clamp_len(a.prefix_len[b], a.max_prefix);
+    const int ptiles = (L + TK - 1) / TK, ttiles = (n + TK - 1) / TK;
+    int t0, t1;
+    split_range(ptiles + ttiles, a.splits, split, t0, t1);
+    const int node = rb * RB + r;
+    const bool row_ok = node < n;
+
+    const float* qbase = (const float*)a.Q + (long long)b * a.qs[0] + (long long)hq * a.qs[1];
+    for (int i = tid; i < RB * D / 4; i += 256) {
+        const int rr = i / (D / 4), cc = (i % (D / 4)) * 4;
+        f32x4 w = {0.f, 0.f, 0.f, 0.f};
+        if (rb * RB + rr < n) w = *(const f32x4*)(qbase + (long long)(rb * RB + rr) * a.qs[2] + cc);
+        *(f32x4*)(s_q + rr * D + cc) = w;
+    }
+    uint64_t mrow[4] = {0ull, 0ull, 0ull, 0ull};
+    if (row_ok)
+        for (int w = 0; w < a.W; ++w) mrow[w] = a.mask[((long long)b * n + node) * a.W + w];
+
+    const float* kp = (const float*)a.Kp + (long long)b * a.kps[0] + (long long)hk * a.kps[1];
+    const float* vp = (const float*)a.Vp + (long long)b * a.vps[0] + (long long)hk * a.vps[1];
+    const float* kt = (const float*)a.Kt + (long long)b * a.kts[0] + (long long)hk * a.kts[1];
+    const float* vt = (const float*)a.Vt + (long long)b * a.vts[0] + (long long)hk * a.vts[1];
+
+    float m_run = -INFINITY, l_run = 0.f;
+    float o[EPT];
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) o[e] = 0.f;
+
+    for (int t = t0; t < t1; ++t) {
+        const bool tree = t >= ptiles;
+        const int key0 = tree ? (t - ptiles) * TK : t * TK;
+        const int kend = tree ? n : L;
+        const float* kb = tree ? kt : kp;
+        const float* vb = tree ? vt : vp;
+        const long long ks = tree ? a.kts[2] : a.kps[2];
+        const long long vs = tree ? a.vts[2] : a.vps[2];
+        __syncthreads();
+        for (int i = tid; i < TK * D / 4; i += 256) {
+            const int key = i / (D / 4), cc = (i % (D / 4)) * 4;
+            f32x4 kw = {0.f, 0.f, 0.f, 0.f}, vw = {0.f, 0.f, 0.f, 0.f};
+            if (key0 + key < kend) {
+                kw = *(const f32x4*)(kb + (long long)(key0 + key) * ks + cc);
+                vw = *(const f32x4*)(vb + (long long)(key0 + key) * vs + cc);
+            }
+            *(f32x4*)(s_k + key * KPAD + cc) = kw;
+            *(f32x4*)(s_v + key * D + cc) = vw;
+        }
+        __syncthreads();
+        float s2[2];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int kl = c + 16 * u;
+            float acc = 0.f;
+#pragma unroll 8
+            for (int d = 0; d < D; d += 4) {
+                const f32x4 qv = *(const f32x4*)(s_q + r * D + d);
+                const f32x4 kv = *(const f32x4*)(s_k + kl * KPAD + d);
+                acc = fmaf(qv.x, kv.x, acc); acc = fmaf(qv.y, kv.y, acc);
+                acc = fmaf(qv.z, kv.z, acc); acc = fmaf(qv.w, kv.w, acc);
+            }
+            const int key = key0 + kl;
+            bool ok = row_ok && key < kend;
+            if (tree) ok = ok && ((mrow[key >> 6] >> (key & 63)) & 1ull);
+            s2[u] = ok ? acc * a.scale_log2 : -INFINITY;
+        }
+        const float tmax = row16_max(fmaxf(s2[0], s2[1]));
+        const float m_new = fmaxf(m_run, tmax);
+        float alpha = 1.f, p0 = 0.f, p1 = 0.f;
+        if (m_new != -INFINITY) {
+            alpha = exp2f(m_run - m_new);
+            p0 = exp2f(s2[0] - m_new);
+            p1 = exp2f(s2[1] - m_new);
+            m_run = m_new;
+        }
+        s_p[r * TK + c] = p0;
+        s_p[r * TK + c + 16] = p1;
+        __syncthreads();
+        float psum = 0.f;
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) o[e] *= alpha;
+        for (int jj = 0; jj < TK; ++jj) {
+            const float p = s_p[r * TK + jj];
+            psum += p;
+#pragma unroll
+            for (int e = 0; e < EPT; ++e) o[e] = fmaf(p, s_v[jj * D + c + 16 * e], o[e]);
+        }
+        l_run = l_run * alpha + psum;
+    }
+    if (!row_ok) return;
+    const long long row = ((long long)b * a.q_heads + hq) * n + node;
+    if (a.splits == 1) {
+        const float inv = l_run > 0.f ? 1.f / l_run : 0.f;
+        float* orow = (float*)a.O + (long long)b * a.os[0] + (long long)hq * a.os[1] + (long long)node * a.os[2];
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) orow[c + 16 * e] = o[e] * inv;
+    } else {
+        float* po = a.part_o + (row * a.splits + split) * D;
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) po[c + 16 * e] = o[e];
+        if (c == 0) {
+            a.part_ml[(row * a.splits + split) * 2] = m_run;
+            a.part_ml[(row * a.splits + split) * 2 + 1] = l_run;
+        }
+    }
+}
+
+// Merge the per-split partials of one output row: O = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s.
+__global__ __launch_bounds__(128) void attn_combine_kernel(const AttnKArgs a) {
+    const long long row = blockIdx.x;
+    const int d = threadIdx.x;
+    if (d >= a.D) return;
+    const int n = a.n;
+    const int node = (int)(row % n);
+    const int hq = (int)((row / n) % a.q_heads);
+    const int b = (int)(row / ((long long)n * a.q_heads));
+    const float* ml = a.part_ml + row * a.splits * 2;
+    float M = -INFINITY;
+    for (int s = 0; s < a.splits; ++s) M = fmaxf(M, ml[2 * s]);
+    float acc = 0.f, l = 0.f;
+    if (M != -INFINITY) {
+        for (int s = 0; s < a.splits; ++s) {
+            const float m = ml[2 * s];
+            if (m == -INFINITY) continue;
+            const float w = exp2f(m - M);
+            l += w * ml[2 * s + 1];
+            acc += w * a.part_o[(row * a.splits + s) * a.D + d];
+        }
+    }
+    const float val = l > 0.f ? acc / l : 0.f;
+    const long long off = (long long)b * a.os[0] + (long long)hq * a.os[1] + (long long)node * a.os[2] + d;
+    if (a.dtype == OT_BF16) ((unsigned short*)a.O)[off] = __builtin_bit_cast(unsigned short, (__bf16)val);
+    else ((float*)a.O)[off] = val;
+}
+
+}  // namespace
+
+static size_t align_up(size_t v, size_t al) { return (v + al - 1) / al * al; }
+
+AttnPlan plan_attention(const ot_attn_params& p) {
+    AttnPlan pl;
+    const int g = p.q_heads / p.kv_heads;
+    int base, tile;
+    if (p.dtype == OT_BF16) {
+        pl.row_blocks = (g * p.n + 63) / 64;
+        base = p.batch * p.kv_heads * pl.row_blocks;
+        tile = 64;
+    } else {
+        pl.row_blocks = (p.n + 15) / 16;
+        base = p.batch * p.q_heads * pl.row_blocks;
+        tile = 32;
+    }
+    const int max_tiles = (p.max_prefix + tile - 1) / tile + (p.n + tile - 1) / tile;
+    int splits = (512 + base - 1) / base;
+    if (splits > max_tiles) splits = max_tiles;
+    if (splits > kMaxSplits) splits = kMaxSplits;
+    if (splits < 1) splits = 1;
+    pl.splits = splits;
+    const size_t rows = (size_t)p.batch * p.q_heads * p.n;
+    pl.part_o_bytes = splits > 1 ? align_up(rows * splits * p.head_dim * 4, 256) : 0;
+    pl.part_ml_bytes = splits > 1 ? align_up(rows * splits * 2 * 4, 256) : 0;
+    pl.bytes = pl.part_o_bytes + pl.part_ml_bytes + 256;
+    return pl;
+}
+
+int launch_tree_attention(const ot_attn_params& p, const AttnPlan& plan, const void* Q, const void* Kp, const void* Vp,
+                          const void* Kt, const void* Vt, const int32_t* prefix_len, const uint64_t* mask, void* O,
+                          void* workspace, hipStream_t s) {
+    AttnKArgs a;
+    a.Q = Q; a.Kp = Kp; a.Vp = Vp; a.Kt = Kt; a.Vt = Vt;
+    a.prefix_len = prefix_len; a.mask = mask; a.O = O;
+    a.part_o = (float*)workspace;
+    a.part_ml = (float*)((char*)workspace + plan.part_o_bytes);
+    a.batch = p.batch; a.q_heads = p.q_heads; a.kv_heads = p.kv_heads; a.g = p.q_heads / p.kv_heads;
+    a.n = p.n; a.D = p.head_dim; a.max_prefix = p.max_prefix; a.splits = plan.splits;
+    a.W = OT_MASK_WORDS(p.n); a.dtype = p.dtype;
+    const float scale = p.softmax_scale != 0.f ? p.softmax_scale : 1.0f / sqrtf((float)p.head_dim);
+    a.scale_log2 = scale * kLog2e;
+    for (int i = 0; i < 3; ++i) {
+        a.qs[i] = p.q_strides[i]; a.kps[i] = p.kp_strides[i]; a.vps[i] = p.vp_strides[i];
+        a.kts[i] = p.kt_strides[i]; a.vts[i] = p.vt_strides[i]; a.os[i] = p.o_strides[i];
+    }
+    if (p.dtype == OT_BF16) {
+        const dim3 grid(plan.splits, plan.row_blocks, p.batch * p.kv_heads);
+        if (p.head_dim == 128) hipLaunchKernelGGL(attn_mfma_kernel<128>, grid, dim3(256), 0, s, a);
+        else                   hipLaunchKernelGGL(attn_mfma_kernel<64>, grid, dim3(256), 0, s, a);
+    } else {
+        const dim3 grid(plan.splits, plan.row_blocks, p.batch * p.q_heads);
+        if (p.head_dim == 128) hipLaunchKernelGGL(attn_f32_kernel<128>, grid, dim3(256), 0, s, a);
+        else                   hipLaunchKernelGGL(attn_f32_kernel<64>, grid, dim3(256), 0, s, a);
+    }
+    OT_HIP_CHECK(hipGetLastError());
+    if (plan.splits > 1) {
+        const long long rows = (long long)p.batch * p.q_heads * p.n;
+        hipLaunchKernelGGL(attn_combine_kernel, dim3((unsigned)rows), dim3(128), 0, s, a);
+        OT_HIP_CHECK(hipGetLastError());
+    }
+    return OT_OK;
+}
+
+}  // namespace ot
+
+using namespace ot;
+
+static int validate_attn(const ot_attn_params* p) {
+    if (!p) return OT_ERR_INVALID_ARG;
+    if (p->batch < 1 || p->q_heads < 1 || p->kv_heads < 1 || p->n < 1 || p->max_prefix < 0) return OT_ERR_INVALID_ARG;
+    if (p->q_heads % p->kv_heads) return OT_ERR_INVALID_ARG;
+    if (p->dtype != OT_F32 && p->dtype != OT_BF16) return OT_ERR_INVALID_ARG;
+    if (!(p->softmax_scale >= 0.f)) return OT_ERR_INVALID_ARG;
+    if (p->head_dim != 64 && p->head_dim != 128) return OT_ERR_UNSUPPORTED;
+    if (p->n > OT_MAX_NODES) return OT_ERR_UNSUPPORTED;
+    if ((long long)p->batch * p->q_heads > 65535 || (long long)p->batch * p->q_heads * p->n > 0x7fffffffLL)
+        return OT_ERR_UNSUPPORTED;
+    const int vec = p->dtype == OT_BF16 ? 8 : 4;
+    const int64_t* st[6] = {p->q_strides, p->kp_strides, p->vp_strides, p->kt_strides, p->vt_strides, p->o_strides};
+    for (int t = 0; t < 6; ++t) {
+        for (int i = 0; i < 3; ++i)
+            if (st[t][i] < 0 || st[t][i] % vec) return OT_ERR_INVALID_ARG;
+        if (st[t][2] < p->head_dim) return OT_ERR_INVALID_ARG;
+    }
+    return OT_OK;
+}
+
+extern "C" {
+
+size_t ot_attn_workspace_bytes(const ot_attn_params* p) {
+    if (validate_attn(p) != OT_OK) return 0;
+    return plan_attention(*p).bytes;
+}
+
+int ot_tree_verify_attention(const ot_attn_params* p, const void* Q, const void* K_prefix, const void* V_prefix,
+                             const void* K_tree, const void* V_tree, const int32_t* prefix_len, const uint64_t* mask,
+                             void* O, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    int st = validate_attn(p);
+    if (st != OT_OK) return st;
+    if (!Q || !K_tree || !V_tree || !prefix_len || !mask || !O || !workspace) return OT_ERR_INVALID_ARG;
+    if (p->max_prefix > 0 && (!K_prefix || !V_prefix)) return OT_ERR_INVALID_ARG;
+    const void* ptrs[7] = {Q, K_prefix, V_prefix, K_tree, V_tree, O, workspace};
+    for (int i = 0; i < 7; ++i)
+        if (ptrs[i] && ((uintptr_t)ptrs[i] % 16)) return OT_ERR_INVALID_ARG;
+    if (((uintptr_t)prefix_len % 4) || ((uintptr_t)mask % 8)) return OT_ERR_INVALID_ARG;
+    const AttnPlan plan = plan_attention(*p);
+    if (workspace_bytes < plan.bytes) return OT_ERR_WORKSPACE_TOO_SMALL;
+    return launch_tree_attention(*p, plan, Q, K_prefix, V_prefix, K_tree, V_tree, prefix_len, mask, O, workspace,
+                                 (hipStream_t)hip_stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,69 @@
+"""Helpers shared by the GPU parity tests: host arrays <-> device tensors, oracle drivers."""
+import numpy as np
+
+from oracle import opt_tree as ot_oracle
+from paper_2406_17276_amd import workloads as wl
+
+GAP = 1e-5          # minimum cross-parent score gap (log p^) required of generated inputs
+
+
+def to_device(a: np.ndarray, dtype: str):
+    import torch
+    if dtype == "bf16":
+        return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).cuda().view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+
+
+def from_device_f64(t) -> np.ndarray:
+    import torch
+    return t.detach().to(torch.float64).cpu().numpy()
+
+
+def mask_to_device(mask_u64: np.ndarray):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(mask_u64).view(np.int64)).cuda()
+
+
+def oracle_trees(logits_stored: np.ndarray, dtype: str, k: int, n: int, depth: int):
+    """Run the fp64 oracle on every sequence of stored logits [B, depth, n, V]."""
+    out = []
+    for b in range(logits_stored.shape[0]):
+        out.append(ot_oracle.build_tree(LazyF64(logits_stored[b], dtype), k, n, depth))
+    return out
+
+
+class LazyF64:
+    """Indexable view that widens stored logits to float64 one step at a time (saves host memory)."""
+
+    def __init__(self, stored, dtype):
+        self.stored, self.dtype = stored, dtype
+
+    def __getitem__(self, idx):
+        return wl.to_f64(self.stored[idx], self.dtype)
+
+
+def gapped_logits(w: wl.Workload, seed0: int = 0, seqs=None, max_tries: int = 8):
+    """Logits of workload w whose every selection cut has a cross-parent gap > GAP (seed bumped until so)."""
+    for seed in range(seed0, seed0 + max_tries):
+        logits = wl.make_logits(w, seed, seqs)
+        trees = oracle_trees(logits, w.dtype, w.k, w.n, w.depth)
+        if min(t["min_gap"] for t in trees) > GAP:
+            return seed, logits, trees
+    raise RuntimeError("no seed with the required score gap")
+
+
+def assert_tree_equal(got, want_list, n, score_atol=1e-5):
+    """got: api.Tree on device; want_list: oracle dicts per sequence.  Structure must be bit-exact."""
+    tok = got.token.cpu().numpy(); par = got.parent.cpu().numpy(); dep = got.depth.cpu().numpy()
+    sc = got.score.cpu().numpy().astype(np.float64); msk = got.mask.cpu().numpy().view(np.uint64)
+    nout = got.n_out.cpu().numpy(); ex = got.expect.cpu().numpy()
+    for b, want in enumerate(want_list):
+        assert nout[b] == want["n_out"], f"seq {b}: n_out"
+        np.testing.assert_array_equal(tok[b], want["token"], err_msg=f"seq {b}: token")
+        np.testing.assert_array_equal(par[b], want["parent"], err_msg=f"seq {b}: parent")
+        np.testing.assert_array_equal(dep[b], want["depth"], err_msg=f"seq {b}: depth")
+        np.testing.assert_array_equal(msk[b], want["mask"], err_msg=f"seq {b}: mask")
+        m = want["n_out"]
+        np.testing.assert_allclose(sc[b, :m], want["score"][:m], rtol=0, atol=score_atol, err_msg=f"seq {b}: score")
+        assert np.all(np.isneginf(sc[b, m:]))
+        np.testing.assert_allclose(ex[b], want["expect"], rtol=1e-6, err_msg=f"seq {b}: E")

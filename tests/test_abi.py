@@ -1,0 +1,104 @@
+"""The C-ABI library loads, exports every symbol the header declares, and rejects bad arguments on the
+host before touching the GPU (no compute is launched by this file)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2406_17276_amd import api
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "opttree.h")).read()
+    return re.findall(r"OT_API\s+[\w\s\*]+?\b(ot_\w+)\s*\(", text)
+
+
+def test_header_declares_the_expected_entry_points():
+    names = declared_symbols()
+    for must in ["ot_build_tree", "ot_tree_verify_attention", "ot_tree_begin", "ot_tree_expand",
+                 "ot_tree_finalize", "ot_build_workspace_bytes", "ot_attn_workspace_bytes"]:
+        assert must in names
+
+
+def test_library_exports_every_declared_symbol():
+    L = api.lib()
+    for name in declared_symbols():
+        assert hasattr(L, name), name
+    assert L.ot_version() >= 100
+    assert L.ot_status_string(0) == b"ok"
+    assert L.ot_status_string(-3) == b"workspace too small"
+
+
+def _bp(**kw):
+    d = dict(batch=1, vocab=1000, depth=4, k=4, n=16, logits_dtype=0, stride_seq=64000, stride_depth=16000, stride_row=1000)
+    d.update(kw)
+    return api.BuildParams(**d)
+
+
+def test_build_workspace_query_and_limits():
+    assert api.build_workspace_bytes(_bp()) > 0
+    for bad in [dict(k=0), dict(n=0), dict(depth=0), dict(batch=0), dict(k=1001), dict(logits_dtype=7),
+                dict(k=17), dict(n=257), dict(depth=33), dict(vocab=300000)]:
+        assert api.build_workspace_bytes(_bp(**bad)) == 0, bad
+
+
+def test_build_tree_rejects_bad_arguments_without_launching():
+    L = api.lib()
+    fake = C.c_void_p(0x1000)          # never dereferenced: validation fails first
+    out = api.TreeOut(*([0x1000] * 7))
+    p = _bp()
+    need = api.build_workspace_bytes(p)
+    assert L.ot_build_tree(None, fake, fake, need, C.byref(out), None) == -1
+    assert L.ot_build_tree(C.byref(p), None, fake, need, C.byref(out), None) == -1
+    assert L.ot_build_tree(C.byref(p), fake, None, need, C.byref(out), None) == -1
+    assert L.ot_build_tree(C.byref(p), fake, fake, need, None, None) == -1
+    assert L.ot_build_tree(C.byref(p), fake, fake, need - 1, C.byref(out), None) == -3
+    assert L.ot_build_tree(C.byref(p), fake, C.c_void_p(0x1004), need, C.byref(out), None) == -1     # misaligned
+    assert L.ot_build_tree(C.byref(_bp(stride_row=999)), fake, fake, need, C.byref(out), None) == -1
+    assert L.ot_build_tree(C.byref(_bp(k=17)), fake, fake, need, C.byref(out), None) == -2
+    bad_out = api.TreeOut(0x1000, 0, 0x1000, 0x1000, 0x1000, 0x1000, 0x1000)
+    assert L.ot_build_tree(C.byref(p), fake, fake, need, C.byref(bad_out), None) == -1
+    assert L.ot_tree_expand(C.byref(p), 4, fake, 0, 1000, fake, need, fake, fake, None) == -1          # step out of range
+    assert L.ot_tree_finalize(C.byref(p), 0, fake, need, C.byref(out), None) == -1
+
+
+def _ap(**kw):
+    s = (C.c_int64 * 3)
+    d = dict(batch=1, q_heads=4, kv_heads=4, head_dim=64, n=16, max_prefix=128, dtype=0, softmax_scale=0.0,
+             q_strides=s(4096, 1024, 64), kp_strides=s(32768, 8192, 64), vp_strides=s(32768, 8192, 64),
+             kt_strides=s(4096, 1024, 64), vt_strides=s(4096, 1024, 64), o_strides=s(4096, 1024, 64))
+    d.update(kw)
+    return api.AttnParams(**d)
+
+
+def test_attention_rejects_bad_arguments_without_launching():
+    L = api.lib()
+    s = (C.c_int64 * 3)
+    assert api.attn_workspace_bytes(_ap()) > 0
+    assert api.attn_workspace_bytes(_ap(q_heads=6, kv_heads=4)) == 0
+    assert api.attn_workspace_bytes(_ap(head_dim=96)) == 0
+    assert api.attn_workspace_bytes(_ap(n=0)) == 0
+    assert api.attn_workspace_bytes(_ap(n=257)) == 0
+    assert api.attn_workspace_bytes(_ap(q_strides=s(4096, 1024, 62))) == 0
+    f = C.c_void_p(0x1000)
+    p = _ap()
+    need = api.attn_workspace_bytes(p)
+    args = [f] * 9
+    bad = list(args); bad[0] = None
+    assert L.ot_tree_verify_attention(C.byref(p), *bad, need, None) == -1
+    bad = list(args); bad[1] = None                                                  # K_prefix NULL with max_prefix > 0
+    assert L.ot_tree_verify_attention(C.byref(p), *bad, need, None) == -1
+    bad = list(args); bad[0] = C.c_void_p(0x1008)
+    assert L.ot_tree_verify_attention(C.byref(p), *bad, need, None) == -1
+    assert L.ot_tree_verify_attention(C.byref(p), *args, need - 1, None) == -3
+    assert L.ot_tree_verify_attention(C.byref(_ap(head_dim=96)), *args, need, None) == -2
+
+
+def test_binding_fails_loudly_when_library_is_missing(monkeypatch):
+    monkeypatch.setattr(api, "_lib", None)
+    monkeypatch.setattr(api, "_LIB_PATH", "/nonexistent/libopttree.so")
+    with pytest.raises(FileNotFoundError):
+        api.lib()

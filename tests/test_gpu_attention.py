@@ -1,0 +1,151 @@
+"""Parity of ot_tree_verify_attention with the fp64 oracle (needs an MI355X).
+Bars: max-abs 1e-5 for f32 inputs, 2e-2 for bf16 inputs, against fp64 on the stored (rounded) inputs."""
+import numpy as np
+import pytest
+
+from oracle import opt_tree as ot_oracle
+from oracle import tree_attention as ta_oracle
+from paper_2406_17276_amd import workloads as wl
+from tests import _util as U
+
+pytestmark = pytest.mark.gpu
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+
+
+def _gpu_attention(x, mask, dtype, scale=0.0):
+    import torch
+    from paper_2406_17276_amd import api
+    dev = {k: U.to_device(v, dtype) for k, v in x.items() if k != "prefix_len"}
+    plen = torch.from_numpy(x["prefix_len"].astype(np.int32)).cuda()
+    kp, vp = dev["K_prefix"], dev["V_prefix"]
+    out = api.tree_verify_attention(dev["Q"], kp, vp, dev["K_tree"], dev["V_tree"], plen, U.mask_to_device(mask),
+                                    softmax_scale=scale)
+    torch.cuda.synchronize()
+    return U.from_device_f64(out)
+
+
+def _oracle_attention(x, mask, dtype, scale=None):
+    f = {k: wl.to_f64(v, dtype) for k, v in x.items() if k != "prefix_len"}
+    return ta_oracle.tree_verify_attention(f["Q"], f["K_prefix"], f["V_prefix"], f["K_tree"], f["V_tree"],
+                                           x["prefix_len"], mask, scale)
+
+
+def _shape(dtype, B, Hq, Hkv, D, L, n, ragged=0.0, name="t"):
+    return wl.Workload(name, B, 8, 1, 1, n, dtype, "normal", 1.0, Hq, Hkv, D, L, ragged=ragged)
+
+
+def _random_masks(B, n, seed, shape="random"):
+    return np.stack([ot_oracle.ancestor_mask(wl.random_tree_parents(n, seed + b, shape)) for b in range(B)])
+
+
+@pytest.mark.parametrize("name", ["tiny", "7b"])
+def test_full_config_with_the_tree_built_by_the_oracle(name):
+    w = wl.WORKLOADS[name]
+    logits = wl.make_logits(w, 0)
+    tree = U.oracle_trees(logits, w.dtype, w.k, w.n, w.depth)[0]
+    mask = tree["mask"][None]
+    x = wl.make_attention_inputs(w, 0)
+    got = _gpu_attention(x, mask, w.dtype)
+    want = _oracle_attention(x, mask, w.dtype)
+    assert np.abs(got - want).max() < TOL[w.dtype]
+
+
+def test_13b_shape_sampled_heads():
+    # full shape on the GPU; the oracle checks 6 of the 40 heads
+    w = wl.WORKLOADS["13b"]
+    x = wl.make_attention_inputs(w, 1)
+    mask = _random_masks(1, w.n, 7)
+    got = _gpu_attention(x, mask, w.dtype)
+    heads = [0, 7, 13, 22, 31, 39]
+    sub = {k: (v[:, heads] if k != "prefix_len" else v) for k, v in x.items()}
+    want = _oracle_attention(sub, mask, w.dtype)
+    assert np.abs(got[:, heads] - want).max() < TOL[w.dtype]
+
+
+def test_70b_shape_gqa_ragged_sampled():
+    # GQA 64/8 heads, ragged prefixes around 4096, n=60; 3 sequences on the GPU, oracle on 2 KV groups of each
+    w = wl.WORKLOADS["70b"]
+    seqs = [0, 7, 12]
+    x = wl.make_attention_inputs(w, 2, seqs=seqs)
+    mask = _random_masks(len(seqs), w.n, 11)
+    got = _gpu_attention(x, mask, w.dtype)
+    g = w.q_heads // w.kv_heads
+    for kvh in (1, 6):
+        qh = list(range(kvh * g, kvh * g + g))
+        sub = dict(Q=x["Q"][:, qh], K_prefix=x["K_prefix"][:, [kvh]], V_prefix=x["V_prefix"][:, [kvh]],
+                   K_tree=x["K_tree"][:, [kvh]], V_tree=x["V_tree"][:, [kvh]], prefix_len=x["prefix_len"])
+        want = _oracle_attention(sub, mask, w.dtype)
+        assert np.abs(got[:, qh] - want).max() < TOL[w.dtype]
+
+
+def test_large_budget_shape_one_kv_group():
+    # n = 256 (4 mask words), 32/8 heads, prefix 8192: 1 sequence on the GPU, oracle on one KV group
+    w = wl.WORKLOADS["large"]
+    x = wl.make_attention_inputs(w, 3, seqs=[0])
+    mask = _random_masks(1, w.n, 5)
+    got = _gpu_attention(x, mask, w.dtype)
+    qh = [8, 9, 10, 11]
+    sub = dict(Q=x["Q"][:, qh], K_prefix=x["K_prefix"][:, [2]], V_prefix=x["V_prefix"][:, [2]],
+               K_tree=x["K_tree"][:, [2]], V_tree=x["V_tree"][:, [2]], prefix_len=x["prefix_len"])
+    want = _oracle_attention(sub, mask, w.dtype)
+    assert np.abs(got[:, qh] - want).max() < TOL[w.dtype]
+
+
+@pytest.mark.parametrize("dtype,B,Hq,Hkv,D,L,n,ragged,shape", [
+    ("f32", 2, 4, 4, 64, 128, 16, 0.0, "random"),
+    ("f32", 2, 6, 2, 128, 77, 37, 0.3, "random"),      # GQA, ragged, n not a multiple of 16
+    ("f32", 1, 2, 2, 64, 0, 20, 0.0, "random"),        # empty prefix
+    ("f32", 1, 2, 1, 64, 300, 130, 0.0, "chain"),      # three mask words, chain = causal
+    ("bf16", 2, 4, 4, 128, 200, 50, 0.2, "random"),
+    ("bf16", 1, 8, 2, 128, 1000, 60, 0.0, "random"),   # packed GQA rows span several 64-row blocks
+    ("bf16", 2, 4, 2, 64, 129, 33, 0.5, "random"),     # head_dim 64, ragged tails
+    ("bf16", 1, 2, 2, 128, 0, 70, 0.0, "star"),        # empty prefix, two tree tiles
+    ("bf16", 1, 4, 1, 128, 64, 256, 0.0, "random"),    # maximum n
+    ("bf16", 1, 1, 1, 128, 5000, 1, 0.0, "random"),    # a single node
+])
+def test_shapes_and_edges(dtype, B, Hq, Hkv, D, L, n, ragged, shape):
+    w = _shape(dtype, B, Hq, Hkv, D, L, n, ragged)
+    x = wl.make_attention_inputs(w, 4)
+    mask = _random_masks(B, n, 3, shape)
+    got = _gpu_attention(x, mask, dtype)
+    want = _oracle_attention(x, mask, dtype)
+    assert np.abs(got - want).max() < TOL[dtype]
+
+
+def test_softmax_scale_override_and_unnormalised_inputs():
+    w = _shape("f32", 1, 2, 2, 64, 90, 12)
+    x = wl.make_attention_inputs(w, 6)
+    x["Q"] = (x["Q"] * 4.0).astype(np.float32)          # large logits: exercises the running max
+    mask = _random_masks(1, 12, 1)
+    got = _gpu_attention(x, mask, "f32", scale=0.05)
+    want = _oracle_attention(x, mask, "f32", scale=0.05)
+    assert np.abs(got - want).max() < 1e-5
+
+
+def test_strided_kv_cache_views():
+    import torch
+    from paper_2406_17276_amd import api
+    w = _shape("bf16", 2, 4, 2, 128, 150, 24)
+    x = wl.make_attention_inputs(w, 8)
+    mask = _random_masks(2, 24, 2)
+    want = _oracle_attention(x, mask, "bf16")
+    dev = {k: U.to_device(v, "bf16") for k, v in x.items() if k != "prefix_len"}
+    Lmax = dev["K_prefix"].shape[2]
+    cache_k = torch.zeros((2, 2, Lmax + 40, 128 + 64), dtype=torch.bfloat16, device="cuda")
+    cache_v = torch.zeros_like(cache_k)
+    kview, vview = cache_k[:, :, 8:8 + Lmax, 64:], cache_v[:, :, 8:8 + Lmax, 64:]
+    kview.copy_(dev["K_prefix"]); vview.copy_(dev["V_prefix"])
+    plen = torch.from_numpy(x["prefix_len"]).cuda()
+    out = api.tree_verify_attention(dev["Q"], kview, vview, dev["K_tree"], dev["V_tree"], plen, U.mask_to_device(mask))
+    torch.cuda.synchronize()
+    assert np.abs(U.from_device_f64(out) - want).max() < 2e-2
+
+
+def test_prefix_length_is_clamped_on_device():
+    w = _shape("f32", 1, 2, 2, 64, 40, 8)
+    x = wl.make_attention_inputs(w, 9)
+    mask = _random_masks(1, 8, 4)
+    want = _oracle_attention(x, mask, "f32")
+    y = dict(x); y["prefix_len"] = np.array([10_000], dtype=np.int32)
+    got = _gpu_attention(y, mask, "f32")
+    assert np.abs(got - want).max() < 1e-5

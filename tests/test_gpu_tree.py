@@ -1,0 +1,178 @@
+"""Parity of ot_build_tree / ot_tree_expand / ot_tree_finalize with the fp64 oracle (needs an MI355X).
+
+Tree structure (tokens, parents, depths, masks, n_out) must be bit-exact; log p^ within 1e-5 absolute
+and E within 1e-6 relative (fp32 exp-sum with fp64 combination, error budget ~1e-7 per row).
+Inputs are regenerated with the next seed until every selection cut has a cross-parent gap > 1e-5."""
+import numpy as np
+import pytest
+
+from oracle import opt_tree as ot_oracle
+from paper_2406_17276_amd import workloads as wl
+from tests import _util as U
+
+pytestmark = pytest.mark.gpu
+
+
+def _run(logits_stored, dtype, k, n, depth):
+    from paper_2406_17276_amd import api
+    import torch
+    dev = U.to_device(logits_stored, dtype)
+    tree = api.build_tree(dev, k, n, depth)
+    torch.cuda.synchronize()
+    return tree
+
+
+@pytest.mark.parametrize("name", ["tiny", "7b", "13b"])
+def test_full_config_single_sequence(name):
+    w = wl.WORKLOADS[name]
+    seed, logits, want = U.gapped_logits(w, 0)
+    print(f"{name}: seed {seed}, min gap {min(t['min_gap'] for t in want):.3e}", flush=True)
+    got = _run(logits, w.dtype, w.k, w.n, w.depth)
+    U.assert_tree_equal(got, want, w.n)
+
+
+def test_70b_shape_batched_subset():
+    # full per-sequence shape (V=32000, d=10, k=8, n=60), 4 of the 16 sequences: the oracle stays in seconds
+    w = wl.WORKLOADS["70b"]
+    seed, logits, want = U.gapped_logits(w, 0, seqs=[0, 5, 10, 15])
+    got = _run(logits, w.dtype, w.k, w.n, w.depth)
+    U.assert_tree_equal(got, want, w.n)
+
+
+def test_large_budget_shape_reduced_depth():
+    # n=256 (4 mask words, 4 wavefronts), k=16, vocab 128256 split over 4 scan parts; 1 sequence, and
+    # 6 instead of 20 drafting steps so that the oracle finishes in ~20 s
+    import dataclasses
+    w = dataclasses.replace(wl.WORKLOADS["large"], depth=6)
+    seed, logits, want = U.gapped_logits(w, 0, seqs=[0])
+    got = _run(logits, w.dtype, w.k, w.n, w.depth)
+    U.assert_tree_equal(got, want, w.n)
+
+
+def _random_case(V, k, n, d, B, dtype, seed, scale=3.0):
+    g = np.random.default_rng(seed)
+    for s in range(seed, seed + 16):
+        x = (g.standard_normal((B, d, n, V)) * scale).astype(np.float32)
+        stored = wl.store(x, dtype)
+        want = U.oracle_trees(stored, dtype, k, n, d)
+        if min(t["min_gap"] for t in want) > U.GAP:
+            return stored, want
+    raise RuntimeError("no gapped input")
+
+
+@pytest.mark.parametrize("V,k,n,d,B,dtype", [
+    (1000, 4, 16, 4, 3, "f32"),        # Tiny shape, batched
+    (1001, 3, 7, 5, 2, "f32"),         # vocab not a multiple of the vector width -> scalar loads
+    (777, 5, 33, 3, 2, "bf16"),
+    (50, 16, 64, 3, 1, "f32"),         # k = 16, tiny vocab (most scan groups empty)
+    (9000, 10, 50, 6, 2, "bf16"),      # 1024-thread scan with a ragged tail
+    (40000, 6, 20, 4, 2, "bf16"),      # two scan parts + merge
+    (70001, 2, 100, 9, 1, "f32"),      # three parts, unaligned vocab, 2 waves of selection
+    (300, 1, 8, 5, 2, "f32"),          # k = 1: a chain, pool smaller than n
+    (300, 4, 1, 3, 2, "f32"),          # n = 1
+    (300, 2, 200, 4, 1, "f32"),        # n larger than the pool (2+4+8+16)
+    (2048, 12, 130, 3, 2, "bf16"),     # 3 waves
+    (512, 8, 256, 32, 1, "f32"),       # maximum n and depth
+])
+def test_random_shapes_and_edges(V, k, n, d, B, dtype):
+    stored, want = _random_case(V, k, n, d, B, dtype, seed=V + k + n)
+    got = _run(stored, dtype, k, n, d)
+    U.assert_tree_equal(got, want, n)
+
+
+def test_constant_rows_exercise_every_tie_rule():
+    # all logits equal: top-k ties by token id (candidate-list overflow path), layer cuts tie by
+    # (parent slot, rank), the final cut ties by (depth, slot)
+    for V, k, n, d, dtype in [(4096, 3, 10, 3, "f32"), (33000, 4, 9, 2, "bf16"), (64, 2, 5, 4, "f32")]:
+        stored = wl.store(np.zeros((1, d, n, V), dtype=np.float32), dtype)
+        want = U.oracle_trees(stored, dtype, k, n, d)
+        got = _run(stored, dtype, k, n, d)
+        U.assert_tree_equal(got, want, n)
+
+
+def test_quantised_rows_with_many_exact_ties():
+    g = np.random.default_rng(5)
+    V, k, n, d = 5000, 8, 24, 4
+    x = g.integers(-6, 7, size=(2, d, n, V)).astype(np.float32)      # 13 distinct values: huge tie groups
+    x += (g.standard_normal((2, d, n, 1)) * 0.37).astype(np.float32)  # rows differ, ties inside rows stay
+    stored = wl.store(x, "f32")
+    want = U.oracle_trees(stored, "f32", k, n, d)
+    assert min(t["min_gap"] for t in want) > U.GAP
+    got = _run(stored, "f32", k, n, d)
+    U.assert_tree_equal(got, want, n)
+
+
+def test_strided_logits_view():
+    import torch
+    from paper_2406_17276_amd import api
+    V, k, n, d, B = 1000, 4, 16, 4, 2
+    stored, want = _random_case(V, k, n, d, B, "f32", seed=99)
+    big = torch.zeros((B, d + 1, n + 3, V + 24), dtype=torch.float32, device="cuda")
+    view = big[:, :d, :n, 8:8 + V]          # 16-byte aligned start, padded strides
+    view.copy_(U.to_device(stored, "f32"))
+    got = api.build_tree(view, k, n, d)
+    torch.cuda.synchronize()
+    U.assert_tree_equal(got, want, n)
+    view2 = big[:, :d, :n, 3:3 + V]         # misaligned start: scalar-load path
+    view2.copy_(U.to_device(stored, "f32"))
+    got = api.build_tree(view2, k, n, d)
+    torch.cuda.synchronize()
+    U.assert_tree_equal(got, want, n)
+
+
+def test_streaming_matches_oracle_layer_by_layer():
+    """Drive expand() the way a decoder would: the rows of step t+1 depend on the frontier of step t."""
+    import torch
+    from paper_2406_17276_amd import api
+    V, k, n, d, B = 3000, 5, 40, 6, 2
+
+    def row_for(b, path):
+        h = np.random.SeedSequence([1234, b, len(path)] + [int(p) + 1 for p in path])
+        return (np.random.default_rng(h).standard_normal(V) * 3.0).astype(np.float32)
+
+    builders = [ot_oracle.TreeBuilder(k, n) for _ in range(B)]
+    paths = [[()] for _ in range(B)]
+    stream = api.TreeStream(B, V, k, n, d, api.OT_F32)
+    for t in range(d):
+        F = len(paths[0])
+        rows = np.zeros((B, n, V), dtype=np.float32)
+        for b in range(B):
+            for j, p in enumerate(paths[b]):
+                rows[b, j] = row_for(b, p)
+        ftok, fpar = stream.expand(torch.from_numpy(rows).cuda())
+        torch.cuda.synchronize()
+        ftok, fpar = ftok.cpu().numpy(), fpar.cpu().numpy()
+        for b in range(B):
+            tok, par = builders[b].expand(rows[b, :F].astype(np.float64))
+            Fn = len(tok)
+            np.testing.assert_array_equal(ftok[b, :Fn], tok)
+            np.testing.assert_array_equal(fpar[b, :Fn], par)
+            paths[b] = [paths[b][int(pj)] + (int(tk),) for tk, pj in zip(tok, par)]
+    want = [bld.finalize() for bld in builders]
+    assert min(wnt["min_gap"] for wnt in want) > U.GAP
+    got = stream.finalize()
+    torch.cuda.synchronize()
+    U.assert_tree_equal(got, want, n)
+
+
+def test_expected_length_grows_with_depth():
+    # Thm. 3.2 on the GPU path: E of the depth-t tree is non-decreasing in t
+    w = wl.WORKLOADS["tiny"]
+    logits = wl.make_logits(w, 3)
+    prev = 0.0
+    for d in range(1, w.depth + 1):
+        got = _run(logits, w.dtype, w.k, w.n, d)
+        e = float(got.expect.cpu()[0])
+        assert e >= prev - 1e-12
+        prev = e
+
+
+def test_repeated_calls_are_bit_identical():
+    import torch
+    w = wl.WORKLOADS["7b"]
+    logits = wl.make_logits(w, 1)
+    a = _run(logits, w.dtype, w.k, w.n, w.depth)
+    for _ in range(3):
+        b = _run(logits, w.dtype, w.k, w.n, w.depth)
+        for f in ("token", "parent", "depth", "mask", "score", "expect"):
+            assert torch.equal(getattr(a, f), getattr(b, f)), f
