@@ -100,7 +100,9 @@ __device__ void select_threshold(const u64 (&key)[M], int want, Group<SINGLE>& g
     int f_hi = 0;
     int tot_gt_lo = g.sum_i(bgt);
     int tot_ge_lo = 0x7fffffff;
-    while (true) {
+    // every round removes at least the pivot from the open interval, so M * blockDim rounds always
+    // suffice; the bound makes termination unconditional
+    for (int round = 0; round < M * 256 + 2; ++round) {
         const int in_range = tot_gt_lo - f_hi;
         if (in_range <= 0) break;
         const int cnt = bgt - a;
