@@ -1,0 +1,253 @@
+#!/usr/bin/env python3
+"""Benchmark of the OPT-Tree decoding-step hot path on one MI355X.
+
+One step = one ot_build_tree (row scan + tree selection) followed by one
+ot_tree_verify_attention (K/V streaming + split merge) on one batch of the
+synthetic workload, the attention mask being the one the tree builder just
+wrote.  Inputs are resident in HBM before the timed region; consecutive steps
+use different copies from a ring larger than the chip's caches, so the logits
+and the K/V cache are streamed from HBM every step.
+
+Prints ONE JSON line: steps/s, the roofline of the dominant kernel (the logits
+row scan, HBM-bound), the K/V-streaming attention kernel as a second roofline,
+and the CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes as C
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, published
+
+
+class Hip:
+    """The few HIP event calls the benchmark needs, straight from the runtime."""
+
+    def __init__(self):
+        self.lib = C.CDLL("libamdhip64.so")
+        self.lib.hipEventCreate.argtypes = [C.POINTER(C.c_void_p)]
+        self.lib.hipEventRecord.argtypes = [C.c_void_p, C.c_void_p]
+        self.lib.hipEventSynchronize.argtypes = [C.c_void_p]
+        self.lib.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
+
+    def event(self):
+        e = C.c_void_p()
+        assert self.lib.hipEventCreate(C.byref(e)) == 0
+        return e
+
+    def record(self, e, stream):
+        assert self.lib.hipEventRecord(e, C.c_void_p(stream)) == 0
+
+    def elapsed_ms(self, a, b) -> float:
+        ms = C.c_float()
+        assert self.lib.hipEventSynchronize(b) == 0
+        rc = self.lib.hipEventElapsedTime(C.byref(ms), a, b)
+        assert rc == 0, rc
+        return float(ms.value)
+
+
+def device_logits(w, seed: int, slot: int):
+    """Ring copy `slot` of the workload's logits, drawn on the device with the workload's recipe."""
+    import torch
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed * 1000003 + slot)
+    F = w.frontier()
+    dt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    out = torch.zeros((w.batch, w.depth, w.n, w.vocab), dtype=dt, device="cuda")
+    for t in range(w.depth):
+        z = torch.randn((w.batch, F[t], w.vocab), generator=g, device="cuda", dtype=torch.float32)
+        if w.logit_kind == "zipf":
+            rank = torch.argsort(torch.rand((w.batch, F[t], w.vocab), generator=g, device="cuda"), dim=-1).float() + 1.0
+            x = -1.1 * torch.log(rank) + 0.5 * z
+        else:
+            x = z * w.logit_scale
+            if w.logit_kind == "peak":
+                idx = torch.randint(0, w.vocab, (w.batch, F[t], 1), generator=g, device="cuda")
+                x.scatter_add_(2, idx, torch.full_like(idx, w.peak, dtype=torch.float32))
+        out[:, t, :F[t]] = x.to(dt)
+    return out
+
+
+def device_attention(w, seed: int, slot: int, plen):
+    import torch
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed * 7919 + slot + 17)
+    dt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    Lmax = max(1, w.max_prefix())
+    mk = lambda *s: torch.randn(s, generator=g, device="cuda", dtype=torch.float32).to(dt)
+    return dict(Q=mk(w.batch, w.q_heads, w.n, w.head_dim), K_prefix=mk(w.batch, w.kv_heads, Lmax, w.head_dim),
+                V_prefix=mk(w.batch, w.kv_heads, Lmax, w.head_dim), K_tree=mk(w.batch, w.kv_heads, w.n, w.head_dim),
+                V_tree=mk(w.batch, w.kv_heads, w.n, w.head_dim), prefix_len=plen)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--workload", default="7b", choices=["tiny", "7b", "13b", "70b"])
+    ap.add_argument("--mode", default="stream", choices=["stream", "graph"])
+    ap.add_argument("--ring", type=int, default=0, help="input copies cycled through (0: enough for 768 MB)")
+    ap.add_argument("--no-events", action="store_true", help="do not time individual kernels in the timed region")
+    ap.add_argument("--cpu-steps", type=int, default=4, help="oracle steps timed for cpu_baseline (0 = skip)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from oracle import tree_attention as ta_oracle
+    from paper_2406_17276_amd import api, workloads as wl
+    from tests import _util as U
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    w = wl.WORKLOADS[args.workload]
+    hip = Hip()
+    stream = torch.cuda.current_stream().cuda_stream
+
+    # ---- slot 0: the seeded host-generated workload, checked against the oracle -------------
+    t_cpu0 = time.perf_counter()
+    seed, logits_h, want = U.gapped_logits(w, 0)
+    attn_h = wl.make_attention_inputs(w, seed)
+    logit_bytes = w.batch * w.rows_per_seq() * w.vocab * w.elem_bytes()
+    plen_h = attn_h["prefix_len"]
+    S_tot = int(sum(int(l) + w.n for l in plen_h))
+    kv_bytes = 2 * w.kv_heads * S_tot * w.head_dim * w.elem_bytes()
+    qo_bytes = 2 * w.batch * w.q_heads * w.n * w.head_dim * w.elem_bytes()
+    attn_flops = 4.0 * w.n * S_tot * w.head_dim * w.q_heads
+    per_slot = logit_bytes + 2 * w.kv_heads * w.batch * (w.max_prefix() + w.n) * w.head_dim * w.elem_bytes() + qo_bytes
+    ring = args.ring or max(2, min(64, int(768e6 // per_slot) + 1))
+
+    builds, attns = [], []
+    plen_d = torch.from_numpy(plen_h).cuda()
+    for slot in range(ring):
+        if slot == 0:
+            lg = U.to_device(logits_h, w.dtype)
+            at = {k: U.to_device(v, w.dtype) for k, v in attn_h.items() if k != "prefix_len"}
+        else:
+            lg = device_logits(w, seed, slot)
+            at = device_attention(w, seed, slot, plen_d)
+        pb = api.PreparedBuild(lg, w.k, w.n, w.depth)
+        pa = api.PreparedAttention(at["Q"], at["K_prefix"], at["V_prefix"], at["K_tree"], at["V_tree"], plen_d,
+                                   pb.out.mask)
+        builds.append(pb)
+        attns.append(pa)
+    torch.cuda.synchronize()
+
+    # parity of slot 0 in the launch configuration that is timed
+    builds[0](stream)
+    attns[0](stream)
+    torch.cuda.synchronize()
+    U.assert_tree_equal(builds[0].out, want, w.n)
+    f64 = {k: wl.to_f64(v, w.dtype) for k, v in attn_h.items() if k != "prefix_len"}
+    chk_heads = list(range(0, w.q_heads, max(1, w.q_heads // 4)))[:4] if w.q_heads > 8 else list(range(w.q_heads))
+    g = w.q_heads // w.kv_heads
+    kvh = sorted({h // g for h in chk_heads})
+    qh = [h for h in range(w.q_heads) if h // g in kvh]
+    mask_h = np.stack([t["mask"] for t in want])
+    ref = ta_oracle.tree_verify_attention(f64["Q"][:, qh], f64["K_prefix"][:, kvh], f64["V_prefix"][:, kvh],
+                                          f64["K_tree"][:, kvh], f64["V_tree"][:, kvh], plen_h, mask_h)
+    err = float(np.abs(U.from_device_f64(attns[0].out)[:, qh] - ref).max())
+    tol = 2e-2 if w.dtype == "bf16" else 1e-5
+    assert err < tol, f"attention parity {err}"
+
+    # ---- warm-up ---------------------------------------------------------------------------
+    for i in range(args.warmup):
+        builds[i % ring](stream)
+        attns[i % ring](stream)
+    torch.cuda.synchronize()
+
+    K = args.steps
+    use_events = (not args.no_events) and args.mode == "stream"
+    ev = [[hip.event() for _ in range(4)] for _ in range(K)] if use_events else None
+
+    graph = None
+    if args.mode == "graph":
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            cs = side.cuda_stream
+            with torch.cuda.graph(graph, stream=side):
+                for i in range(K):
+                    builds[i % ring](cs)
+                    attns[i % ring](cs)
+        torch.cuda.synchronize()
+
+    # ---- timed region: exactly K steps -------------------------------------------------------
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    if graph is not None:
+        graph.replay()
+    elif use_events:
+        for i in range(K):
+            e = ev[i]
+            builds[i % ring].timed(stream, e[0], e[1])
+            attns[i % ring].timed(stream, e[2], e[3])
+    else:
+        for i in range(K):
+            builds[i % ring](stream)
+            attns[i % ring](stream)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt * 1e3 / K
+
+    scan_ms = attn_ms = None
+    if use_events:
+        scan_ms = float(np.mean([hip.elapsed_ms(e[0], e[1]) for e in ev]))
+        attn_ms = float(np.mean([hip.elapsed_ms(e[2], e[3]) for e in ev]))
+
+    result = {
+        "metric": "tree-build+verify-attention steps/sec", "value": K / dt, "unit": "steps/s",
+        "n_gpus": 1, "steps": K, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": f"{w.name}: batch {w.batch}, vocab {w.vocab}, depth {w.depth}, top-k {w.k}, n {w.n}; "
+                               f"attention {w.q_heads}q/{w.kv_heads}kv heads, head_dim {w.head_dim}, prefix {w.prefix}",
+                   "mode": args.mode, "ring_copies": ring, "seed": seed, "kernel_events": bool(use_events)},
+    }
+    if scan_ms is not None:
+        gbs = logit_bytes / (scan_ms * 1e-3) / 1e9
+        result["roofline"] = {"kernel": "row_scan_kernel", "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS,
+                              "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS, "traffic": None,
+                              "algorithmic_bytes": logit_bytes, "avg_kernel_us": scan_ms * 1e3}
+        agbs = (kv_bytes + qo_bytes) / (attn_ms * 1e-3) / 1e9
+        result["roofline_attention"] = {
+            "kernel": "attn_mfma_kernel" if w.dtype == "bf16" else "attn_f32_kernel", "bound": "hbm",
+            "achieved": agbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": agbs / HBM_PEAK_GBS, "traffic": None,
+            "algorithmic_bytes": kv_bytes + qo_bytes, "avg_kernel_us": attn_ms * 1e3,
+            "mfma_tflops": attn_flops / (attn_ms * 1e-3) / 1e12,
+            "mfma_frac_of_peak": attn_flops / (attn_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS}
+
+    # ---- CPU oracle on a bounded sample of the same workload ----------------------------------
+    if args.cpu_steps > 0:
+        from threadpoolctl import threadpool_limits
+        cpu_dt = 0.0
+        with threadpool_limits(limits=1):
+            for s in range(args.cpu_steps):
+                lg = wl.make_logits(w, seed + 100 + s) if s else logits_h      # generation is not timed
+                tc = time.perf_counter()
+                trees = U.oracle_trees(lg, w.dtype, w.k, w.n, w.depth)
+                m = np.stack([t["mask"] for t in trees])
+                ta_oracle.tree_verify_attention(f64["Q"], f64["K_prefix"], f64["V_prefix"], f64["K_tree"],
+                                                f64["V_tree"], plen_h, m)
+                cpu_dt += time.perf_counter() - tc
+        result["cpu_baseline"] = {"value": args.cpu_steps / cpu_dt, "unit": "steps/s", "cores": 1, "kind": "oracle",
+                                  "sample": f"{args.cpu_steps} full steps of the same workload (fp64 NumPy oracle: "
+                                            "tree build + tree attention; inputs pre-generated; 1 thread)"}
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

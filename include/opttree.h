@@ -96,6 +96,15 @@ OT_API int ot_build_tree(const ot_build_params* p, const void* logits,
                   void* workspace, size_t workspace_bytes,
                   const ot_tree_out* out, void* hip_stream);
 
+/* Measurement aid: ot_build_tree that also records, in two caller-created hipEvent_t (passed as
+ * void*, either may be NULL), the begin and the end of its row-scan kernel -- the HBM-bound pass over
+ * the logits (softmax normaliser and top-k of every row, Sec. 3).  hipEventElapsedTime between
+ * them, after the stream is synchronised, is that kernel's execution time.  Not capturable in a graph. */
+OT_API int ot_build_tree_timed(const ot_build_params* p, const void* logits,
+                  void* workspace, size_t workspace_bytes,
+                  const ot_tree_out* out, void* hip_stream,
+                  void* scan_begin_event, void* scan_end_event);
+
 /* Streaming form of the same computation: what a decoder calls between the
  * draft model's forwards (the loop of Algorithm 1).  The strides of `p` are
  * ignored by begin; each expand call passes its own.
@@ -152,6 +161,16 @@ OT_API int ot_tree_verify_attention(const ot_attn_params* p,
                              const uint64_t* mask,                   /* [batch][n][OT_MASK_WORDS(n)] */
                              void* O,                                /* [batch][q_heads][n][head_dim] */
                              void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Measurement aid: ot_tree_verify_attention that also records the begin and the end of its
+ * K/V-streaming kernel (Algorithm 2's tree-masked attention, without the split merge) in two
+ * caller-created hipEvent_t (void*, either may be NULL).  Not capturable in a graph. */
+OT_API int ot_tree_verify_attention_timed(const ot_attn_params* p,
+                             const void* Q, const void* K_prefix, const void* V_prefix,
+                             const void* K_tree, const void* V_tree,
+                             const int32_t* prefix_len, const uint64_t* mask,
+                             void* O, void* workspace, size_t workspace_bytes, void* hip_stream,
+                             void* kernel_begin_event, void* kernel_end_event);
 
 #ifdef __cplusplus
 }

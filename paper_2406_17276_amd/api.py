@@ -63,6 +63,9 @@ def lib():
         L.ot_build_tree.restype = C.c_int
         L.ot_build_tree.argtypes = [C.POINTER(BuildParams), C.c_void_p, C.c_void_p, C.c_size_t,
                                     C.POINTER(TreeOut), C.c_void_p]
+        L.ot_build_tree_timed.restype = C.c_int
+        L.ot_build_tree_timed.argtypes = [C.POINTER(BuildParams), C.c_void_p, C.c_void_p, C.c_size_t,
+                                          C.POINTER(TreeOut), C.c_void_p, C.c_void_p, C.c_void_p]
         L.ot_tree_begin.restype = C.c_int
         L.ot_tree_begin.argtypes = [C.POINTER(BuildParams), C.c_void_p, C.c_size_t, C.c_void_p]
         L.ot_tree_expand.restype = C.c_int
@@ -75,6 +78,9 @@ def lib():
         L.ot_attn_workspace_bytes.argtypes = [C.POINTER(AttnParams)]
         L.ot_tree_verify_attention.restype = C.c_int
         L.ot_tree_verify_attention.argtypes = [C.POINTER(AttnParams)] + [C.c_void_p] * 9 + [C.c_size_t, C.c_void_p]
+        L.ot_tree_verify_attention_timed.restype = C.c_int
+        L.ot_tree_verify_attention_timed.argtypes = ([C.POINTER(AttnParams)] + [C.c_void_p] * 9 +
+                                                     [C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p])
         _lib = L
     return _lib
 
@@ -229,3 +235,56 @@ def tree_verify_attention(Q, K_prefix, V_prefix, K_tree, V_tree, prefix_len, mas
         ptr(out), ptr(workspace), 0 if workspace is None else workspace.numel(), _stream()),
         "ot_tree_verify_attention")
     return out
+
+
+# ---------------------------------------------------------------------------
+# Prepared calls: everything marshalled once, so that a hot loop (or a HIP graph capture) pays one
+# foreign call per library call.  Used by bench.py.
+# ---------------------------------------------------------------------------
+class PreparedBuild:
+    def __init__(self, logits, k: int, n: int, depth: int):
+        import torch
+        self.logits = logits
+        self.p = build_params(logits, k, n, depth)
+        need = build_workspace_bytes(self.p)
+        if need == 0:
+            raise OptTreeError(-2, "ot_build_workspace_bytes")
+        self.ws = torch.empty(need, dtype=torch.uint8, device=logits.device)
+        self.out = alloc_tree(self.p.batch, n, logits.device)
+        self.o = self.out.c_struct()
+        self._args = (C.byref(self.p), logits.data_ptr(), self.ws.data_ptr(), self.ws.numel(), C.byref(self.o))
+
+    def __call__(self, stream: int):
+        st = lib().ot_build_tree(*self._args, stream)
+        if st:
+            raise OptTreeError(st, "ot_build_tree")
+
+    def timed(self, stream: int, ev0, ev1):
+        st = lib().ot_build_tree_timed(*self._args, stream, ev0, ev1)
+        if st:
+            raise OptTreeError(st, "ot_build_tree_timed")
+
+
+class PreparedAttention:
+    def __init__(self, Q, K_prefix, V_prefix, K_tree, V_tree, prefix_len, mask, softmax_scale: float = 0.0):
+        import torch
+        self.keep = (Q, K_prefix, V_prefix, K_tree, V_tree, prefix_len, mask)
+        self.p = attn_params(Q, K_prefix, V_prefix, K_tree, V_tree, softmax_scale=softmax_scale)
+        self.out = torch.empty_like(Q)
+        need = attn_workspace_bytes(self.p)
+        if need == 0:
+            raise OptTreeError(-2, "ot_attn_workspace_bytes")
+        self.ws = torch.empty(need, dtype=torch.uint8, device=Q.device)
+        ptr = lambda t: None if t is None else t.data_ptr()
+        self._args = (C.byref(self.p), ptr(Q), ptr(K_prefix), ptr(V_prefix), ptr(K_tree), ptr(V_tree),
+                      ptr(prefix_len), ptr(mask), ptr(self.out), self.ws.data_ptr(), self.ws.numel())
+
+    def __call__(self, stream: int):
+        st = lib().ot_tree_verify_attention(*self._args, stream)
+        if st:
+            raise OptTreeError(st, "ot_tree_verify_attention")
+
+    def timed(self, stream: int, ev0, ev1):
+        st = lib().ot_tree_verify_attention_timed(*self._args, stream, ev0, ev1)
+        if st:
+            raise OptTreeError(st, "ot_tree_verify_attention_timed")

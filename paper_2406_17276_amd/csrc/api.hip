@@ -110,8 +110,8 @@ size_t ot_build_workspace_bytes(const ot_build_params* p) {
     return carve_build_workspace(*p, nullptr).bytes;
 }
 
-int ot_build_tree(const ot_build_params* p, const void* logits, void* workspace, size_t workspace_bytes,
-                  const ot_tree_out* out, void* hip_stream) {
+static int build_entry(const ot_build_params* p, const void* logits, void* workspace, size_t workspace_bytes,
+                       const ot_tree_out* out, void* hip_stream, void* ev0, void* ev1) {
     int st = validate_build(p, true);
     if (st != OT_OK) return st;
     if (!logits || !workspace) return OT_ERR_INVALID_ARG;
@@ -130,9 +130,19 @@ int ot_build_tree(const ot_build_params* p, const void* logits, void* workspace,
     sg.nsteps = p->depth; sg.rows_per_seq = f.rows;
     for (int i = 0; i < OT_MAX_DEPTH + 2; ++i) sg.row_start[i] = f.row_start[i];
     sg.stride_seq = p->stride_seq; sg.stride_depth = p->stride_depth; sg.stride_row = p->stride_row;
-    st = launch_row_scan(sg, logits, ws, s);
+    st = launch_row_scan(sg, logits, ws, s, (hipEvent_t)ev0, (hipEvent_t)ev1);
     if (st != OT_OK) return st;
     return launch_tree_oneshot(select_geometry(*p, f), ws, *out, s);
+}
+
+int ot_build_tree(const ot_build_params* p, const void* logits, void* workspace, size_t workspace_bytes,
+                  const ot_tree_out* out, void* hip_stream) {
+    return build_entry(p, logits, workspace, workspace_bytes, out, hip_stream, nullptr, nullptr);
+}
+
+int ot_build_tree_timed(const ot_build_params* p, const void* logits, void* workspace, size_t workspace_bytes,
+                        const ot_tree_out* out, void* hip_stream, void* scan_begin_event, void* scan_end_event) {
+    return build_entry(p, logits, workspace, workspace_bytes, out, hip_stream, scan_begin_event, scan_end_event);
 }
 
 int ot_tree_begin(const ot_build_params* p, void* workspace, size_t workspace_bytes, void* hip_stream) {

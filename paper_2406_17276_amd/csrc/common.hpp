@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include "opttree.h"
@@ -62,7 +63,9 @@ struct ScanGeometry {
     long long stride_seq, stride_depth, stride_row;
 };
 
-int launch_row_scan(const ScanGeometry& g, const void* logits, const BuildWorkspace& ws, hipStream_t s);
+// ev0/ev1 (optional): events that receive the begin and end time stamps of the scan kernel itself
+int launch_row_scan(const ScanGeometry& g, const void* logits, const BuildWorkspace& ws, hipStream_t s,
+                    hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr);
 
 struct SelectGeometry {
     int batch, k, n, depth;
@@ -84,7 +87,7 @@ struct AttnPlan {
 AttnPlan plan_attention(const ot_attn_params& p);
 int launch_tree_attention(const ot_attn_params& p, const AttnPlan& plan, const void* Q, const void* Kp, const void* Vp,
                           const void* Kt, const void* Vt, const int32_t* prefix_len, const uint64_t* mask, void* O,
-                          void* workspace, hipStream_t s);
+                          void* workspace, hipStream_t s, hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr);
 
 }  // namespace ot
 

@@ -276,7 +276,8 @@ __global__ void merge_parts_kernel(int rows, int parts, int k, const float* part
 
 }  // namespace
 
-int launch_row_scan(const ScanGeometry& g, const void* logits, const BuildWorkspace& ws, hipStream_t s) {
+int launch_row_scan(const ScanGeometry& g, const void* logits, const BuildWorkspace& ws, hipStream_t s, hipEvent_t ev0,
+                    hipEvent_t ev1) {
     const int parts = scan_parts(g.vocab);
     if (parts > 8) return OT_ERR_UNSUPPORTED;
     const int esize = g.dtype == OT_BF16 ? 2 : 4;
@@ -300,8 +301,11 @@ int launch_row_scan(const ScanGeometry& g, const void* logits, const BuildWorksp
     if (grid <= 0 || grid > 0x7fffffffLL) return OT_ERR_UNSUPPORTED;
     const dim3 gd((unsigned)grid);
 
-#define OT_SCAN_LAUNCH(DT, NT, VL) \
-    hipLaunchKernelGGL((row_scan_kernel<DT, NT, VL>), gd, dim3(NT), 0, s, a)
+#define OT_SCAN_LAUNCH(DT, NT, VL)                                                                       \
+    do {                                                                                                 \
+        if (ev0 || ev1) hipExtLaunchKernelGGL((row_scan_kernel<DT, NT, VL>), gd, dim3(NT), 0, s, ev0, ev1, 0, a); \
+        else hipLaunchKernelGGL((row_scan_kernel<DT, NT, VL>), gd, dim3(NT), 0, s, a);                   \
+    } while (0)
     if (g.dtype == OT_BF16) {
         if (small) { if (aligned) OT_SCAN_LAUNCH(OT_BF16, 256, true); else OT_SCAN_LAUNCH(OT_BF16, 256, false); }
         else       { if (aligned) OT_SCAN_LAUNCH(OT_BF16, 1024, true); else OT_SCAN_LAUNCH(OT_BF16, 1024, false); }

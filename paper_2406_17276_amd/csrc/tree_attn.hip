@@ -472,7 +472,7 @@ AttnPlan plan_attention(const ot_attn_params& p) {
 
 int launch_tree_attention(const ot_attn_params& p, const AttnPlan& plan, const void* Q, const void* Kp, const void* Vp,
                           const void* Kt, const void* Vt, const int32_t* prefix_len, const uint64_t* mask, void* O,
-                          void* workspace, hipStream_t s) {
+                          void* workspace, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1) {
     AttnKArgs a;
     a.Q = Q; a.Kp = Kp; a.Vp = Vp; a.Kt = Kt; a.Vt = Vt;
     a.prefix_len = prefix_len; a.mask = mask; a.O = O;
@@ -489,12 +489,22 @@ int launch_tree_attention(const ot_attn_params& p, const AttnPlan& plan, const v
     }
     if (p.dtype == OT_BF16) {
         const dim3 grid(plan.splits, plan.row_blocks, p.batch * p.kv_heads);
-        if (p.head_dim == 128) hipLaunchKernelGGL(attn_mfma_kernel<128>, grid, dim3(256), 0, s, a);
-        else                   hipLaunchKernelGGL(attn_mfma_kernel<64>, grid, dim3(256), 0, s, a);
+        if (ev0 || ev1) {
+            if (p.head_dim == 128) hipExtLaunchKernelGGL(attn_mfma_kernel<128>, grid, dim3(256), 0, s, ev0, ev1, 0, a);
+            else                   hipExtLaunchKernelGGL(attn_mfma_kernel<64>, grid, dim3(256), 0, s, ev0, ev1, 0, a);
+        } else {
+            if (p.head_dim == 128) hipLaunchKernelGGL(attn_mfma_kernel<128>, grid, dim3(256), 0, s, a);
+            else                   hipLaunchKernelGGL(attn_mfma_kernel<64>, grid, dim3(256), 0, s, a);
+        }
     } else {
         const dim3 grid(plan.splits, plan.row_blocks, p.batch * p.q_heads);
-        if (p.head_dim == 128) hipLaunchKernelGGL(attn_f32_kernel<128>, grid, dim3(256), 0, s, a);
-        else                   hipLaunchKernelGGL(attn_f32_kernel<64>, grid, dim3(256), 0, s, a);
+        if (ev0 || ev1) {
+            if (p.head_dim == 128) hipExtLaunchKernelGGL(attn_f32_kernel<128>, grid, dim3(256), 0, s, ev0, ev1, 0, a);
+            else                   hipExtLaunchKernelGGL(attn_f32_kernel<64>, grid, dim3(256), 0, s, ev0, ev1, 0, a);
+        } else {
+            if (p.head_dim == 128) hipLaunchKernelGGL(attn_f32_kernel<128>, grid, dim3(256), 0, s, a);
+            else                   hipLaunchKernelGGL(attn_f32_kernel<64>, grid, dim3(256), 0, s, a);
+        }
     }
     OT_HIP_CHECK(hipGetLastError());
     if (plan.splits > 1) {
@@ -536,9 +546,9 @@ size_t ot_attn_workspace_bytes(const ot_attn_params* p) {
     return plan_attention(*p).bytes;
 }
 
-int ot_tree_verify_attention(const ot_attn_params* p, const void* Q, const void* K_prefix, const void* V_prefix,
-                             const void* K_tree, const void* V_tree, const int32_t* prefix_len, const uint64_t* mask,
-                             void* O, void* workspace, size_t workspace_bytes, void* hip_stream) {
+static int attention_entry(const ot_attn_params* p, const void* Q, const void* K_prefix, const void* V_prefix,
+                           const void* K_tree, const void* V_tree, const int32_t* prefix_len, const uint64_t* mask,
+                           void* O, void* workspace, size_t workspace_bytes, void* hip_stream, void* ev0, void* ev1) {
     int st = validate_attn(p);
     if (st != OT_OK) return st;
     if (!Q || !K_tree || !V_tree || !prefix_len || !mask || !O || !workspace) return OT_ERR_INVALID_ARG;
@@ -550,7 +560,22 @@ int ot_tree_verify_attention(const ot_attn_params* p, const void* Q, const void*
     const AttnPlan plan = plan_attention(*p);
     if (workspace_bytes < plan.bytes) return OT_ERR_WORKSPACE_TOO_SMALL;
     return launch_tree_attention(*p, plan, Q, K_prefix, V_prefix, K_tree, V_tree, prefix_len, mask, O, workspace,
-                                 (hipStream_t)hip_stream);
+                                 (hipStream_t)hip_stream, (hipEvent_t)ev0, (hipEvent_t)ev1);
+}
+
+int ot_tree_verify_attention(const ot_attn_params* p, const void* Q, const void* K_prefix, const void* V_prefix,
+                             const void* K_tree, const void* V_tree, const int32_t* prefix_len, const uint64_t* mask,
+                             void* O, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return attention_entry(p, Q, K_prefix, V_prefix, K_tree, V_tree, prefix_len, mask, O, workspace, workspace_bytes,
+                           hip_stream, nullptr, nullptr);
+}
+
+int ot_tree_verify_attention_timed(const ot_attn_params* p, const void* Q, const void* K_prefix, const void* V_prefix,
+                                   const void* K_tree, const void* V_tree, const int32_t* prefix_len,
+                                   const uint64_t* mask, void* O, void* workspace, size_t workspace_bytes,
+                                   void* hip_stream, void* kernel_begin_event, void* kernel_end_event) {
+    return attention_entry(p, Q, K_prefix, V_prefix, K_tree, V_tree, prefix_len, mask, O, workspace, workspace_bytes,
+                           hip_stream, kernel_begin_event, kernel_end_event);
 }
 
 }  // extern "C"
