@@ -62,7 +62,8 @@ BuildWorkspace carve_build_workspace(const ot_build_params& p, void* base) {
         w.part_topv = (float*)take(rows * parts * k * 4);
         w.part_topi = (int32_t*)take(rows * parts * k * 4);
     }
-    w.pool_key = (unsigned long long*)take(pool * 8);
+    w.pool_key = (double*)take(pool * 8);
+    w.step_tau = (double*)take((size_t)p.batch * p.depth * 8);
     w.pool_tok = (int32_t*)take(pool * 4);
     w.pool_par = (int32_t*)take(pool * 4);
     w.bytes = off;

@@ -46,7 +46,8 @@ struct BuildWorkspace {
     double* part_s;                 // [rows_total][P]
     float* part_topv;               // [rows_total][P][k]
     int32_t* part_topi;             // [rows_total][P][k]
-    unsigned long long* pool_key;   // [batch][depth][n]   streaming state
+    double* pool_key;               // [batch][depth][n]   streaming state: log p^ of every pool node
+    double* step_tau;               // [batch][depth]      streaming state: cut value of every step
     int32_t* pool_tok;              // [batch][depth][n]
     int32_t* pool_par;              // [batch][depth][n]
     size_t bytes;
@@ -153,6 +154,31 @@ __device__ __forceinline__ int wave_max_i(int v) {
     v = max(v, __shfl_xor(v, 16));
     v = max(v, __shfl_xor(v, 32));
     return v;
+}
+
+// ---- wavefront reductions that end in a scalar (DPP inside rows of 16, v_readlane across rows) ----
+__device__ __forceinline__ int rl(int v, int lane) { return __builtin_amdgcn_readlane(v, lane); }
+__device__ __forceinline__ float rl_f(float v, int lane) { return __int_as_float(rl(__float_as_int(v), lane)); }
+template <int CTRL>
+__device__ __forceinline__ double dpp_d(double v) {
+    const int lo = dpp_i<CTRL>(0, __double2loint(v));
+    const int hi = dpp_i<CTRL>(0, __double2hiint(v));
+    return __hiloint2double(hi, lo);
+}
+__device__ __forceinline__ double rl_d(double v, int lane) {
+    return __hiloint2double(rl(__double2hiint(v), lane), rl(__double2loint(v), lane));
+}
+__device__ __forceinline__ double wave_sum_d(double v) {
+    v += dpp_d<DPP_QUAD_XOR1>(v);
+    v += dpp_d<DPP_QUAD_XOR2>(v);
+    v += dpp_d<DPP_ROW_HALF_MIRROR>(v);
+    v += dpp_d<DPP_ROW_MIRROR>(v);
+    return (rl_d(v, 0) + rl_d(v, 16)) + (rl_d(v, 32) + rl_d(v, 48));
+}
+// max over the wavefront as a scalar
+__device__ __forceinline__ float wave_max_f(float v) {
+    v = row16_max(v);
+    return fmaxf(fmaxf(rl_f(v, 0), rl_f(v, 16)), fmaxf(rl_f(v, 32), rl_f(v, 48)));
 }
 
 }  // namespace ot

@@ -6,14 +6,18 @@
 //
 // One workgroup handles one "part" (<= 32768 elements) of one row.  Inside a workgroup:
 //   1. every lane loads its 32 elements (all loads are issued before the first use),
-//   2. lane max -> 16 group maxima (one per 1/16th of the workgroup) -> LDS;
-//      M = max of them is the exp reference, tau = min of them is a lower bound of the
-//      16th largest element (each group holds an element >= tau), hence of the k-th (k <= 16),
-//   3. one sweep over the registers: s += exp(x - M); elements >= tau go to an LDS candidate list,
-//   4. the k best candidates are ranked by counting (value desc, token asc),
-//   5. part results are written; rows split over several parts are merged by merge_parts_kernel.
+//   2. every wavefront, on its own: lane maxima -> wave maximum m_w, then s_w = sum exp(x - m_w)
+//      over its registers (no workgroup barrier before this, so wavefronts whose data arrived
+//      early do their arithmetic while the others still wait for memory),
+//   3. barrier; tau = the k-th largest of 16 group maxima (one per 1/16th of the workgroup): each
+//      group holds an element >= its maximum, so at least k elements are >= tau,
+//   4. sweep over the registers: elements >= tau go to an LDS candidate list (a 16-byte vector is
+//      skipped when its own maximum is below tau),
+//   5. the k best candidates are ranked by counting (value desc, token asc); the wave partials are
+//      combined in fp64: M = max m_w, s = sum s_w exp(m_w - M), lse = M + log s,
+//   6. part results are written; rows split over several parts are merged by merge_parts_kernel.
 // If the candidate list overflows (massive ties), a slow exact path extracts the k best
-// by k rounds of a workgroup-wide arg-max over the registers.
+// by k rounds of a workgroup-wide arg-max over the part, re-read from memory.
 #include "common.hpp"
 
 namespace ot {
@@ -46,7 +50,9 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu((NT == 1024 
     constexpr int NW = NT / 64;
 
     __shared__ float s_gmax[16];
-    __shared__ double s_wsum[16];
+    __shared__ float s_wm[16];
+    __shared__ double s_ws[16];
+    __shared__ float s_tau;
     __shared__ float s_cv[kCandCap];
     __shared__ int s_ci[kCandCap];
     __shared__ int s_rank[kCandCap];
@@ -67,7 +73,6 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu((NT == 1024 
     const int e_end = min(a.vocab, e_begin + a.part_elems);
 
     if (tid == 0) s_count = 0;
-    for (int i = tid; i < kCandCap; i += NT) s_rank[i] = 0;
 
     // ---- 1. load ----------------------------------------------------------
     // VECLOAD: the host guarantees 16-byte aligned rows and vocab % VEC == 0, so a vector is
@@ -107,45 +112,62 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu((NT == 1024 
         }
     }
 
-    // ---- 2. maxima --------------------------------------------------------
-    float m = x[0];
-#pragma unroll
-    for (int i = 1; i < EPL; ++i) m = fmaxf(m, x[i]);
-    if (NT == 1024) {
-        const float g = wave_max(m);
-        if ((tid & 63) == 0) s_gmax[tid >> 6] = g;
-    } else {
-        const float g = row16_max(m);
-        if ((tid & 15) == 0) s_gmax[tid >> 4] = g;
-    }
-    __syncthreads();
-    float M = s_gmax[0], tau = s_gmax[0];
-#pragma unroll
-    for (int i = 1; i < 16; ++i) {
-        M = fmaxf(M, s_gmax[i]);
-        tau = fminf(tau, s_gmax[i]);
-    }
-
-    // ---- 3. exp-sum and candidates ---------------------------------------
-    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    // ---- 2. per-wavefront statistics -------------------------------------
+    float vmax[VPL];
 #pragma unroll
     for (int i = 0; i < VPL; ++i) {
+        float v = x[i * VEC];
 #pragma unroll
-        for (int c = 0; c < VEC; ++c) {
-            const float v = x[i * VEC + c];
-            acc[c & 3] += __builtin_amdgcn_exp2f((v - M) * kLog2e);
-            if (v >= tau) {
+        for (int c = 1; c < VEC; ++c) v = fmaxf(v, x[i * VEC + c]);
+        vmax[i] = v;
+    }
+    float m = vmax[0];
+#pragma unroll
+    for (int i = 1; i < VPL; ++i) m = fmaxf(m, vmax[i]);
+    const float rmax = row16_max(m);                  // max of this lane's row of 16 lanes
+    const float m_w = fmaxf(fmaxf(rl_f(rmax, 0), rl_f(rmax, 16)), fmaxf(rl_f(rmax, 32), rl_f(rmax, 48)));
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    if (m_w > -INFINITY) {
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) acc[i & 3] += __builtin_amdgcn_exp2f((x[i] - m_w) * kLog2e);
+    }
+    const double s_w = wave_sum_d((double)(acc[0] + acc[1]) + (double)(acc[2] + acc[3]));
+    const int lane = tid & 63, wave = tid >> 6;
+    if (lane == 0) { s_wm[wave] = m_w; s_ws[wave] = s_w; }
+    if (NT == 1024) { if (lane == 0) s_gmax[wave] = m_w; }
+    else            { if ((lane & 15) == 0) s_gmax[tid >> 4] = rmax; }
+    __syncthreads();
+
+    // ---- 3. tau: the kk-th largest of the 16 group maxima ------------------
+    if (tid < 16) {
+        const float v = s_gmax[tid];
+        int rank = 0;
+#pragma unroll
+        for (int jj = 0; jj < 16; ++jj) {
+            const float u = s_gmax[jj];
+            rank += (u > v || (u == v && jj < tid)) ? 1 : 0;
+        }
+        const int kk = a.k < 16 ? a.k : 16;
+        if (rank == kk - 1) s_tau = v;
+    }
+    __syncthreads();
+    const float tau = s_tau;
+
+    // ---- 4. candidates -----------------------------------------------------
+#pragma unroll
+    for (int i = 0; i < VPL; ++i) {
+        if (vmax[i] >= tau) {
+#pragma unroll
+            for (int c = 0; c < VEC; ++c) {
+                const float v = x[i * VEC + c];
                 const int e = e_begin + (i * NT + tid) * VEC + c;
-                if (e < e_end) {
+                if (v >= tau && e < e_end) {
                     const int p = atomicAdd(&s_count, 1);
                     if (p < kCandCap) { s_cv[p] = v; s_ci[p] = e; }
                 }
             }
         }
     }
-    double s = (double)(acc[0] + acc[1]) + (double)(acc[2] + acc[3]);
-    s = wave_sum(s);
-    if ((tid & 63) == 0) s_wsum[tid >> 6] = s;
     __syncthreads();
     const int ncand = s_count;
 
@@ -158,19 +180,48 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu((NT == 1024 
         outv = a.part_topv + (size_t)wg * a.k;
         outi = a.part_topi + (size_t)wg * a.k;
     }
-    if (tid == 0) {
-        double tot = 0.0;
-        for (int w = 0; w < NW; ++w) tot += s_wsum[w];
-        if (a.parts == 1) {
-            a.row_lse[rid] = (double)M + log(tot);
-        } else {
-            a.part_m[wg] = M;
-            a.part_s[wg] = tot;
+    // ---- 5a. combine the wave partials in fp64 (last wavefront, 16 lanes) --
+    if (wave == NW - 1 && lane < 16) {
+        const bool have = lane < NW;
+        const float mw = have ? s_wm[lane] : -INFINITY;
+        float M = mw;
+        M = fmaxf(M, __int_as_float(dpp_i<DPP_QUAD_XOR1>(__float_as_int(M), __float_as_int(M))));
+        M = fmaxf(M, __int_as_float(dpp_i<DPP_QUAD_XOR2>(__float_as_int(M), __float_as_int(M))));
+        M = fmaxf(M, __int_as_float(dpp_i<DPP_ROW_HALF_MIRROR>(__float_as_int(M), __float_as_int(M))));
+        M = fmaxf(M, __int_as_float(dpp_i<DPP_ROW_MIRROR>(__float_as_int(M), __float_as_int(M))));
+        double part_sum = (have && mw > -INFINITY) ? s_ws[lane] * exp((double)mw - (double)M) : 0.0;
+        part_sum += dpp_d<DPP_QUAD_XOR1>(part_sum);
+        part_sum += dpp_d<DPP_QUAD_XOR2>(part_sum);
+        part_sum += dpp_d<DPP_ROW_HALF_MIRROR>(part_sum);
+        part_sum += dpp_d<DPP_ROW_MIRROR>(part_sum);
+        if (lane == 0) {
+            if (a.parts == 1) {
+                a.row_lse[rid] = (double)M + log(part_sum);
+            } else {
+                a.part_m[wg] = M;
+                a.part_s[wg] = part_sum;
+            }
         }
     }
 
-    // ---- 4. rank the candidates ------------------------------------------
+    // ---- 5b. rank the candidates -------------------------------------------
     if (ncand <= kCandCap) {
+        if (ncand <= 64) {
+            if (tid < ncand) {
+                const float v = s_cv[tid];
+                const int id = s_ci[tid];
+                int rank = 0;
+                for (int jj = 0; jj < ncand; ++jj) {
+                    const float u = s_cv[jj];
+                    const int ui = s_ci[jj];
+                    rank += (u > v || (u == v && ui < id)) ? 1 : 0;
+                }
+                if (rank < a.k) { outv[rank] = v; outi[rank] = id; }
+            }
+            return;
+        }
+        for (int i = tid; i < kCandCap; i += NT) s_rank[i] = 0;
+        __syncthreads();
         int cp = 64;
         while (cp < ncand) cp <<= 1;
         const int q_cnt = (NT / cp) > 0 ? (NT / cp) : 1;   // slices of the inner loop per candidate

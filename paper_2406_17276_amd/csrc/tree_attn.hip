@@ -18,6 +18,10 @@
 //                 inside a 16-key slab is whatever the accumulator layout gives; V is read in
 //                 the same order), A = V gathered from LDS.
 // K/V tiles are fetched 16 bytes per lane into registers one tile ahead and staged through LDS.
+// K sits row-major (16-byte row padding keeps the 16-byte operand reads conflict-free).  V is the
+// transposed operand: it is stored as dwords that pair the SAME column of two adjacent keys
+// (built with one DPP exchange between neighbouring lanes and byte permutes), so that the eight
+// keys a lane needs for one column are four dword reads, conflict-free across the wavefront.
 // The ancestor mask is applied as a bit test on tree tiles only; prefix tiles only mask the tail.
 //
 // f32 path (attn_f32_kernel): plain fp32 FMA arithmetic, 16 query rows x 32-key tiles.
@@ -58,18 +62,18 @@ __device__ __forceinline__ void split_range(int T, int S, int s, int& t0, int& t
 // bf16 MFMA kernel
 // ---------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(256) void attn_mfma_kernel(const AttnKArgs a) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_mfma_kernel(const AttnKArgs a) {
     constexpr int TK = 64;                 // keys per tile
     constexpr int KPAD = D + 8;            // bf16 elements per K row in LDS
-    constexpr int VPAD = D + 8;
+    constexpr int VDP = D + 16;            // dwords per key-pair row of V in LDS (2 VDP % 64 == 32)
     constexpr int SLABS = D / 16;          // 16-wide d slabs of the QK^T contraction
     constexpr int DB = D / 32;             // 32-wide d blocks of O^T
     constexpr int CH = TK * D / 8 / 256;   // 16-byte chunks per thread per tile (K or V)
 
-    __shared__ __attribute__((aligned(16))) unsigned short s_buf[TK * (KPAD + VPAD)];
-    unsigned short* const s_k = s_buf;
-    unsigned short* const s_v = s_buf + TK * KPAD;
-    static_assert(sizeof(unsigned short) * TK * (KPAD + VPAD) >= 2 * 64 * (DB * 16 + 2) * 4, "merge buffer fits");
+    __shared__ __attribute__((aligned(16))) unsigned int s_buf[TK * KPAD / 2 + (TK / 2) * VDP];
+    unsigned short* const s_k = (unsigned short*)s_buf;
+    unsigned int* const s_v = s_buf + TK * KPAD / 2;
+    static_assert(sizeof(unsigned int) * (TK * KPAD / 2 + (TK / 2) * VDP) >= 2 * 64 * (DB * 16 + 2) * 4, "merge buffer fits");
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int qb = wave & 1, kh = wave >> 1;
@@ -130,12 +134,13 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const AttnKArgs a) {
         for (int c = 0; c < CH; ++c) {
             const int chunk = c * 256 + tid;
             const int key = chunk / (D / 8), col = (chunk % (D / 8)) * 8;
-            u32x4 kw = {0u, 0u, 0u, 0u}, vw = {0u, 0u, 0u, 0u};
-            if (key0 + key < kend) {
-                kw = *(const u32x4*)(kb + (long long)(key0 + key) * ks + col);
-                vw = *(const u32x4*)(vb + (long long)(key0 + key) * vs + col);
-            }
+            u32x4 kw = {0u, 0u, 0u, 0u};
+            if (key0 + key < kend) kw = *(const u32x4*)(kb + (long long)(key0 + key) * ks + col);
             kreg[c] = kw;
+            // V: neighbouring lanes fetch the same 8 columns of two adjacent keys
+            const int vkey = 2 * ((chunk >> 1) / (D / 8)) + (chunk & 1), vcol = ((chunk >> 1) % (D / 8)) * 8;
+            u32x4 vw = {0u, 0u, 0u, 0u};
+            if (key0 + vkey < kend) vw = *(const u32x4*)(vb + (long long)(key0 + vkey) * vs + vcol);
             vreg[c] = vw;
         }
     };
@@ -148,7 +153,23 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const AttnKArgs a) {
             const int chunk = c * 256 + tid;
             const int key = chunk / (D / 8), col = (chunk % (D / 8)) * 8;
             *(u32x4*)(s_k + key * KPAD + col) = kreg[c];
-            *(u32x4*)(s_v + key * VPAD + col) = vreg[c];
+            // pair the columns of keys 2kp (even lane) and 2kp+1 (odd lane): the even lane builds
+            // columns vcol..vcol+3, the odd lane vcol+4..vcol+7
+            const int odd = chunk & 1;
+            const int kp = (chunk >> 1) / (D / 8), vcol = ((chunk >> 1) % (D / 8)) * 8;
+            const u32x4 mine = vreg[c];
+            const unsigned give0 = odd ? mine.x : mine.z, give1 = odd ? mine.y : mine.w;
+            const unsigned got0 = (unsigned)dpp_i<DPP_QUAD_XOR1>(0, (int)give0);
+            const unsigned got1 = (unsigned)dpp_i<DPP_QUAD_XOR1>(0, (int)give1);
+            const unsigned own0 = odd ? mine.z : mine.x, own1 = odd ? mine.w : mine.y;
+            const unsigned ev0 = odd ? got0 : own0, od0 = odd ? own0 : got0;     // even key / odd key dwords
+            const unsigned ev1 = odd ? got1 : own1, od1 = odd ? own1 : got1;
+            u32x4 out;
+            out.x = __builtin_amdgcn_perm(od0, ev0, 0x05040100u);   // column +0: lo16(even) | lo16(odd) << 16
+            out.y = __builtin_amdgcn_perm(od0, ev0, 0x07060302u);   // column +1: hi16(even) | hi16(odd) << 16
+            out.z = __builtin_amdgcn_perm(od1, ev1, 0x05040100u);
+            out.w = __builtin_amdgcn_perm(od1, ev1, 0x07060302u);
+            *(u32x4*)(s_v + kp * VDP + vcol + 4 * odd) = out;
         }
         __syncthreads();
         if (t + 1 < t1) fetch(t + 1);
@@ -206,14 +227,12 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const AttnKArgs a) {
         for (int u = 0; u < 2; ++u) {
 #pragma unroll
             for (int d = 0; d < DB; ++d) {
-                bf16x8 vf;
-#pragma unroll
-                for (int p = 0; p < 8; ++p) {
-                    const int kl = 32 * kh + 16 * u + 8 * (p >> 2) + 4 * h + (p & 3);
-                    const unsigned short raw = s_v[kl * VPAD + 32 * d + l32];
-                    vf[p] = __builtin_bit_cast(__bf16, raw);
-                }
-                oacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[u], oacc[d], 0, 0, 0);
+                // keys 32kh+16u+4h+{0..3} and +8: key pairs kp0, kp0+1, kp0+4, kp0+5 of column 32d+l32
+                const int kp0 = 16 * kh + 8 * u + 2 * h;
+                const unsigned int* vcolp = s_v + kp0 * VDP + 32 * d + l32;
+                u32x4 vw;
+                vw.x = vcolp[0]; vw.y = vcolp[VDP]; vw.z = vcolp[4 * VDP]; vw.w = vcolp[5 * VDP];
+                oacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vw), pf[u], oacc[d], 0, 0, 0);
             }
         }
         __syncthreads();
@@ -462,6 +481,9 @@ AttnPlan plan_attention(const ot_attn_params& p) {
     if (splits > max_tiles) splits = max_tiles;
     if (splits > kMaxSplits) splits = kMaxSplits;
     if (splits < 1) splits = 1;
+    // even out: every split gets the same number of tiles (the last one possibly fewer)
+    const int per = (max_tiles + splits - 1) / splits;
+    splits = (max_tiles + per - 1) / per;
     pl.splits = splits;
     const size_t rows = (size_t)p.batch * p.q_heads * p.n;
     pl.part_o_bytes = splits > 1 ? align_up(rows * splits * p.head_dim * 4, 256) : 0;

@@ -25,150 +25,328 @@ struct SelKArgs {
     int k, n, depth, rows_per_seq;
     int F[OT_MAX_DEPTH + 2];
     int row_start[OT_MAX_DEPTH + 2];
-    u64* pool_key; int32_t* pool_tok; int32_t* pool_par;      // [batch][depth][n]  (streaming state)
+    int r0[OT_MAX_DEPTH + 2];      // rank whose per-lane minimum is a lower bound of step t's cut
+    double* pool_key; int32_t* pool_tok; int32_t* pool_par;   // [batch][depth][n]  (streaming state)
+    double* step_tau;                                         // [batch][depth]     (streaming state)
     ot_tree_out out;
     int32_t* frontier_token; int32_t* frontier_parent;        // [batch][n]         (streaming step)
     int step;
 };
 
-__device__ __forceinline__ int wave_sum_i(int v) {
+__device__ __forceinline__ double nan_d() { return __longlong_as_double(0x7ff8000000000000ll); }   // "absent"
+
+// ---- integer wavefront reductions that end in a scalar ----
+__device__ __forceinline__ int wave_max_u(int v) {
+    v = max(v, dpp_i<DPP_QUAD_XOR1>(v, v));
+    v = max(v, dpp_i<DPP_QUAD_XOR2>(v, v));
+    v = max(v, dpp_i<DPP_ROW_HALF_MIRROR>(v, v));
+    v = max(v, dpp_i<DPP_ROW_MIRROR>(v, v));
+    return max(max(rl(v, 0), rl(v, 16)), max(rl(v, 32), rl(v, 48)));
+}
+__device__ __forceinline__ int wave_sum_u(int v) {
     v += dpp_i<DPP_QUAD_XOR1>(v, v);
     v += dpp_i<DPP_QUAD_XOR2>(v, v);
     v += dpp_i<DPP_ROW_HALF_MIRROR>(v, v);
     v += dpp_i<DPP_ROW_MIRROR>(v, v);
-    v += __shfl_xor(v, 16);
-    v += __shfl_xor(v, 32);
-    return v;
+    return (rl(v, 0) + rl(v, 16)) + (rl(v, 32) + rl(v, 48));
+}
+// fmin/fmax ignore NaN operands, NaN marks "absent"
+__device__ __forceinline__ double wave_min_d(double v) {
+    v = fmin(v, dpp_d<DPP_QUAD_XOR1>(v));
+    v = fmin(v, dpp_d<DPP_QUAD_XOR2>(v));
+    v = fmin(v, dpp_d<DPP_ROW_HALF_MIRROR>(v));
+    v = fmin(v, dpp_d<DPP_ROW_MIRROR>(v));
+    return fmin(fmin(rl_d(v, 0), rl_d(v, 16)), fmin(rl_d(v, 32), rl_d(v, 48)));
+}
+// inclusive prefix sum inside the wavefront: Kogge-Stone inside rows (row_shr, zero fill), then row totals
+__device__ __forceinline__ int wave_incl_scan(int v, int lane) {
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, false);   // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, false);   // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, false);   // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, false);   // row_shr:8
+    const int t0 = rl(v, 15), t1 = rl(v, 31), t2 = rl(v, 47);
+    const int row = lane >> 4;
+    return v + (row > 0 ? t0 : 0) + (row > 1 ? t1 : 0) + (row > 2 ? t2 : 0);
+}
+
+// Barrier that orders LDS traffic only.  __syncthreads() would also wait for the global loads that
+// prefetch the next step's row statistics; nothing here communicates through global memory.
+template <bool SINGLE>
+__device__ __forceinline__ void lds_sync() {
+    if (SINGLE) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    else        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
 // Workgroup collectives.  SINGLE: the workgroup is one wavefront, no LDS and no barrier needed.
 template <bool SINGLE>
 struct Group {
     int* red;        // LDS int[2][4]
-    u64* bc;         // LDS u64[2]
-    int* scan;       // LDS int[2][4]
-    int phase, bphase, sphase;
-    int tid, wave, nw;
+    double* bc;      // LDS double[2]
+    double* redd;    // LDS double[2][4]
+    int phase, bphase, dphase;
+    int tid, lane, wave, nw;
 
-    __device__ int combine(int v, bool is_max) {
+    __device__ __forceinline__ int combine(int v, bool is_max) {
         if (SINGLE) return v;
-        if ((tid & 63) == 0) red[phase * 4 + wave] = v;
-        __syncthreads();
+        if (lane == 0) red[phase * 4 + wave] = v;
+        lds_sync<false>();
         int r = red[phase * 4];
         for (int w = 1; w < nw; ++w) r = is_max ? max(r, red[phase * 4 + w]) : r + red[phase * 4 + w];
         phase ^= 1;
         return r;
     }
-    __device__ int max_i(int v) { return combine(wave_max_i(v), true); }
-    __device__ int sum_i(int v) { return combine(wave_sum_i(v), false); }
-    __device__ u64 bcast(u64 v, int src) {
-        if (SINGLE) return __shfl(v, src);
+    __device__ __forceinline__ int max_i(int v) { return combine(wave_max_u(v), true); }
+    __device__ __forceinline__ int sum_i(int v) { return combine(wave_sum_u(v), false); }
+    __device__ __forceinline__ double min_d(double v) {
+        v = wave_min_d(v);
+        if (SINGLE) return v;
+        if (lane == 0) redd[dphase * 4 + wave] = v;
+        lds_sync<false>();
+        double r = redd[dphase * 4];
+        for (int w = 1; w < nw; ++w) r = fmin(r, redd[dphase * 4 + w]);
+        dphase ^= 1;
+        return r;
+    }
+    __device__ __forceinline__ double sum_d(double v) {
+        v = wave_sum_d(v);
+        if (SINGLE) return v;
+        if (lane == 0) redd[dphase * 4 + wave] = v;
+        lds_sync<false>();
+        double r = redd[dphase * 4];
+        for (int w = 1; w < nw; ++w) r += redd[dphase * 4 + w];
+        dphase ^= 1;
+        return r;
+    }
+    // value of thread `src` (uniform) for everybody
+    __device__ __forceinline__ double bcast(double v, int src) {
+        if (SINGLE) return rl_d(v, src);
         if (tid == src) bc[bphase] = v;
-        __syncthreads();
-        const u64 r = bc[bphase];
+        lds_sync<false>();
+        const double r = bc[bphase];
         bphase ^= 1;
         return r;
     }
     // exclusive prefix sum over the workgroup in thread order
-    __device__ int excl_scan(int v) {
-        const int lane = tid & 63;
-        int inc = v;
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-            const int up = __shfl_up(inc, o);
-            if (lane >= o) inc += up;
-        }
+    __device__ __forceinline__ int excl_scan(int v) {
+        const int inc = wave_incl_scan(v, lane);
         if (SINGLE) return inc - v;
-        if (lane == 63) scan[sphase * 4 + wave] = inc;
-        __syncthreads();
+        if (lane == 63) red[phase * 4 + wave] = inc;
+        lds_sync<false>();
         int off = 0;
-        for (int w = 0; w < wave; ++w) off += scan[sphase * 4 + w];
-        sphase ^= 1;
+        for (int w = 0; w < wave; ++w) off += red[phase * 4 + w];
+        phase ^= 1;
         return inc - v + off;
     }
 };
 
-// tau = the `want`-th largest of the workgroup's keys (M per lane; key 0 = absent).
-// Returns per lane the number of its keys > tau and == tau, and the workgroup totals.
-template <int M, bool SINGLE>
-__device__ void select_threshold(const u64 (&key)[M], int want, Group<SINGLE>& g, u64& tau, int& lane_gt, int& lane_eq,
-                                 int& total_gt, int& total_eq) {
-    u64 lo = 0ull, hi = ~0ull;
-    int a = 0, bgt = 0, bge = M;
+constexpr int kBuckets = 256;
+
+// next double above v (v finite)
+__device__ __forceinline__ double next_up(double v) {
+    if (v == 0.0) return __longlong_as_double(1ll);
+    const long long bits = __double_as_longlong(v);
+    return __longlong_as_double(v > 0.0 ? bits + 1 : bits - 1);
+}
+
+// Sort M doubles in registers, descending, NaN last (Batcher's odd-even merge network).
+template <int M>
+__device__ __forceinline__ void sort_desc(double (&x)[M]) {
 #pragma unroll
-    for (int r = 0; r < M; ++r) bgt += key[r] > 0ull ? 1 : 0;
-    int f_hi = 0;
-    int tot_gt_lo = g.sum_i(bgt);
-    int tot_ge_lo = 0x7fffffff;
-    // every round removes at least the pivot from the open interval, so M * blockDim rounds always
-    // suffice; the bound makes termination unconditional
-    for (int round = 0; round < M * 256 + 2; ++round) {
-        const int in_range = tot_gt_lo - f_hi;
-        if (in_range <= 0) break;
-        const int cnt = bgt - a;
-        const int target = want - f_hi;
-        int q = 0;
-        if (cnt > 0) {
-            q = (int)(((long long)cnt * (2 * target - 1)) / (2 * in_range));
-            q = q > cnt - 1 ? cnt - 1 : q;
-        }
-        u64 prop = 0ull;
-        int ord = 0;
+    for (int p = 1; p < M; p *= 2)
 #pragma unroll
-        for (int r = 0; r < M; ++r) {
-            const bool inr = key[r] > lo && key[r] < hi;
-            if (inr && ord == q) prop = key[r];
-            ord += inr ? 1 : 0;
-        }
-        const int packed = cnt > 0 ? ((cnt << 16) | (0xffff - g.tid)) : 0;
-        const int win = g.max_i(packed);
-        const int src = 0xffff - (win & 0xffff);
-        const u64 p = g.bcast(prop, src);
-        int gge = 0, ggt = 0;
+        for (int k = p; k >= 1; k /= 2)
 #pragma unroll
-        for (int r = 0; r < M; ++r) {
-            gge += key[r] >= p ? 1 : 0;
-            ggt += key[r] > p ? 1 : 0;
+            for (int j = k % p; j <= M - 1 - k; j += 2 * k)
+#pragma unroll
+                for (int i = 0; i < k; ++i)
+                    if (i + j + k <= M - 1 && (i + j) / (2 * p) == (i + j + k) / (2 * p)) {
+                        const double u = x[i + j], w = x[i + j + k];
+                        const bool swap = !(u >= w) && (w == w);
+                        x[i + j] = swap ? w : u;
+                        x[i + j + k] = swap ? u : w;
+                    }
+}
+
+// Result of "keep the `want` largest keys of the workgroup".
+struct Cut {
+    unsigned keep;     // bit r: this lane's key[r] is kept for certain
+    double tau;        // every kept key is >= tau, at least `want` keys are >= tau
+    int need;          // > 0: besides `keep`, `need` of the `total_eq` keys == tau are kept, in the caller's tie order
+    int total_eq;
+};
+
+// Every lane holds M keys (NaN = absent); SORTED: in descending order with NaN last.
+// kt is an LDS table [M][blockDim] (used only by phase 2), hist an LDS scratch of kBuckets + 4 ints.
+//   phase 1  [lo, hi) = [caller's lower bound (or the smallest key), just above the largest key).
+//            The keys inside are binned into 256 equal-width buckets (LDS atomics); a suffix scan of
+//            the histogram finds the bucket that holds the cut; the same is repeated once inside
+//            that bucket (65536 cells overall).  If the cut falls between two cells the kept set is
+//            known exactly and the search is over.  Needs no order inside a lane.
+//   phase 2  (ties or near-ties at the cut) on sorted keys: pivots are keys strictly inside the
+//            remaining range, proposed by the lane with most keys in range; per lane a = #keys
+//            above the range, b = #keys above or in it.  Ends when no key lies strictly inside, so
+//            that every key left in range equals tau.
+template <int M, bool SINGLE, bool SORTED>
+__device__ Cut select_keys(const double (&key)[M], double* kt, int* hist, int want, bool have_first,
+                           double first_pivot, Group<SINGLE>& g) {
+    const int NT = blockDim.x, tid = g.tid;
+    Cut cut;
+    cut.keep = 0u; cut.need = 0; cut.total_eq = 0;
+    double lmin = nan_d(), lmax = nan_d();
+#pragma unroll
+    for (int r = 0; r < M; ++r) { lmin = fmin(lmin, key[r]); lmax = fmax(lmax, key[r]); }
+    double lo = have_first ? first_pivot : g.min_d(lmin);
+    const double gmax = -g.min_d(-lmax);
+    unsigned in = 0u;                              // keys inside [lo, hi)
+#pragma unroll
+    for (int r = 0; r < M; ++r) in |= (key[r] >= lo ? 1u : 0u) << r;
+    int f_hi = 0, f_lo = 0;
+    bool exact = false;
+    if (gmax > lo) {
+        const double hi = next_up(gmax);
+        double u[M];
+        const double scale = (double)kBuckets / (hi - lo);
+#pragma unroll
+        for (int r = 0; r < M; ++r) u[r] = (key[r] - lo) * scale;
+        for (int level = 0; level < 2; ++level) {
+            int bk[M];
+#pragma unroll
+            for (int r = 0; r < M; ++r) {
+                int q = (int)u[r];
+                bk[r] = q < 0 ? 0 : (q > kBuckets - 1 ? kBuckets - 1 : q);
+            }
+            for (int i = tid; i < kBuckets; i += NT) hist[i] = 0;
+            lds_sync<SINGLE>();
+#pragma unroll
+            for (int r = 0; r < M; ++r)
+                if ((in >> r) & 1u) atomicAdd(&hist[bk[r]], 1);
+            lds_sync<SINGLE>();
+            const int T = want - f_hi;            // rank of the cut among the keys in range
+            if (g.wave == 0) {
+                const int L = g.lane;
+                const int c0 = hist[4 * L], c1 = hist[4 * L + 1], c2 = hist[4 * L + 2], c3 = hist[4 * L + 3];
+                const int sum = c0 + c1 + c2 + c3;
+                const int P = wave_incl_scan(sum, L);
+                const int total = rl(P, 63);
+                const int above_lane = total - P;                 // keys in higher lanes' buckets
+                const bool has = above_lane < T && above_lane + sum >= T;
+                int B = 4 * L + 3, above = above_lane, inb = c3;
+                if (above + c3 < T) { above += c3; B = 4 * L + 2; inb = c2;
+                    if (above + c2 < T) { above += c2; B = 4 * L + 1; inb = c1;
+                        if (above + c1 < T) { above += c1; B = 4 * L; inb = c0; } } }
+                const u64 bal = __ballot(has);
+                if (bal != 0ull) {
+                    const int src = __ffsll((long long)bal) - 1;
+                    if (L == src) { hist[kBuckets] = B; hist[kBuckets + 1] = above; hist[kBuckets + 2] = inb; }
+                } else if (L == 0) {
+                    hist[kBuckets] = -1;
+                }
+                if (L == 0) hist[kBuckets + 3] = total;
+            }
+            lds_sync<SINGLE>();
+            const int B = hist[kBuckets], above = hist[kBuckets + 1], inb = hist[kBuckets + 2];
+            const int total = hist[kBuckets + 3];
+            if (level == 0) f_lo = f_hi + total;
+            if (B < 0) break;                     // cannot happen while count(key >= lo) >= want; be safe
+            unsigned gt = 0u, eq = 0u;
+#pragma unroll
+            for (int r = 0; r < M; ++r) {
+                gt |= (bk[r] > B ? 1u : 0u) << r;
+                eq |= (bk[r] == B ? 1u : 0u) << r;
+            }
+            cut.keep |= in & gt;
+            if (above + inb == T) { exact = true; cut.keep |= in & eq; break; }
+            in &= eq;
+            f_hi += above; f_lo = f_hi + inb;
+#pragma unroll
+            for (int r = 0; r < M; ++r) u[r] = (u[r] - (double)B) * (double)kBuckets;
         }
-        const int both = g.sum_i(gge | (ggt << 16));
-        const int f_p = both & 0xffff, gt_p = both >> 16;
-        if (f_p >= want) { lo = p; bgt = ggt; bge = gge; tot_gt_lo = gt_p; tot_ge_lo = f_p; }
-        else             { hi = p; a = gge; f_hi = f_p; }
+    } else {
+        f_lo = g.sum_i(__popc(in));
     }
-    tau = lo;
-    lane_gt = a;
-    lane_eq = bge - a;
-    total_gt = f_hi;
-    total_eq = tot_ge_lo - f_hi;
+    if (exact) {
+        double kmin = nan_d();
+#pragma unroll
+        for (int r = 0; r < M; ++r) kmin = fmin(kmin, ((cut.keep >> r) & 1u) ? key[r] : nan_d());
+        cut.tau = g.min_d(kmin);
+        return cut;
+    }
+
+    // ---- phase 2 -----------------------------------------------------------------------------
+    double ks[M];
+#pragma unroll
+    for (int r = 0; r < M; ++r) ks[r] = key[r];
+    if (!SORTED) sort_desc<M>(ks);
+#pragma unroll
+    for (int r = 0; r < M; ++r) kt[r * NT + tid] = ks[r];
+    int a = __popc(cut.keep), b = a + __popc(in);
+    // every round moves lo up or the upper end down to a key strictly inside, so M * blockDim rounds
+    // always suffice; the bound makes termination unconditional
+    for (int round = 0; round < M * 256 + 2; ++round) {
+        const int cnt = b - a;
+        double prop = nan_d();
+        if (cnt > 0) {
+            const int T = want - f_hi, R = f_lo - f_hi;
+            int q = (int)((float)cnt * (float)(2 * T - 1) * __frcp_rn((float)(2 * R)));
+            q = q > cnt - 1 ? cnt - 1 : (q < 0 ? 0 : q);
+            const double top = kt[a * NT + tid];
+            prop = kt[(a + q) * NT + tid];
+            if (!(prop > lo)) prop = top;
+        }
+        const bool valid = prop > lo;
+        const int win = g.max_i(valid ? ((cnt << 16) | (0xffff - tid)) : 0);
+        if (win == 0) break;
+        const double p = g.bcast(prop, 0xffff - (win & 0xffff));
+        int ge = 0;
+#pragma unroll
+        for (int r = 0; r < M; ++r) ge += ks[r] >= p ? 1 : 0;
+        const int f_p = g.sum_i(ge);
+        if (f_p >= want) { lo = p; b = ge; f_lo = f_p; }
+        else             { a = ge; f_hi = f_p; }
+    }
+    cut.tau = lo;
+    cut.keep = 0u;
+#pragma unroll
+    for (int r = 0; r < M; ++r) cut.keep |= (key[r] > lo ? 1u : 0u) << r;
+    cut.need = want - f_hi;
+    cut.total_eq = f_lo - f_hi;
+    return cut;
 }
 
 // One drafting step's cut: how many of this lane's (rank-sorted) candidates survive, and the
-// first slot they occupy in the next layer.
+// first slot they occupy in the next layer.  tau_out: a value reached by at least `want`
+// candidates (NaN when nothing was cut).
 template <int KMAX, bool SINGLE>
-__device__ void layer_cut(const u64 (&ck)[KMAX], bool active, int k, int F, int want, Group<SINGLE>& g, int& cnt,
-                          int& off) {
+__device__ void layer_cut(const double (&ck)[KMAX], double* kt, int* hist, bool active, int k, int F, int want,
+                          int r0, Group<SINGLE>& g, int& cnt, int& off, double& tau_out) {
+    tau_out = nan_d();
     if (k * F <= want) {
         cnt = active ? k : 0;
     } else {
-        u64 tau; int lane_gt, lane_eq, total_gt, total_eq;
-        select_threshold<KMAX, SINGLE>(ck, want, g, tau, lane_gt, lane_eq, total_gt, total_eq);
-        const int need = want - total_gt;
-        int take = lane_eq;
-        if (total_eq != need) {           // ties at the cut: smaller parent slot first (ranks are contiguous per lane)
-            const int before = g.excl_scan(lane_eq);
-            take = need - before;
-            take = take < 0 ? 0 : (take > lane_eq ? lane_eq : take);
+        // every lane holds at least r0+1 candidates and (r0+1) F >= want, so the smallest rank-r0
+        // candidate is a lower bound of the cut: it discards most candidates at once
+        double c0 = nan_d();
+#pragma unroll
+        for (int r = 0; r < KMAX; ++r) c0 = (r == r0) ? ck[r] : c0;
+        const double m0 = g.min_d(c0);
+        const Cut cut = select_keys<KMAX, SINGLE, true>(ck, kt, hist, want, true, m0, g);
+        cnt = __popc(cut.keep);               // sorted candidates: the kept ones are a prefix
+        if (cut.need > 0) {                   // ties at the cut: smaller parent slot first, then smaller rank
+            int lane_eq = 0;
+#pragma unroll
+            for (int r = 0; r < KMAX; ++r) lane_eq += ck[r] == cut.tau ? 1 : 0;
+            int take = lane_eq;
+            if (cut.total_eq != cut.need) {
+                const int before = g.excl_scan(lane_eq);
+                take = cut.need - before;
+                take = take < 0 ? 0 : (take > lane_eq ? lane_eq : take);
+            }
+            cnt += take;
         }
-        cnt = lane_gt + take;
+        tau_out = cut.tau;
     }
     off = g.excl_scan(cnt);
 }
-
-struct RowData {
-    double lse;
-    float v[OT_MAX_TOPK];
-    int i[OT_MAX_TOPK];
-};
 
 template <int KMAX>
 __device__ __forceinline__ void load_row(const SelKArgs& a, long long rid, bool active, double& lse, float (&v)[KMAX],
@@ -184,58 +362,72 @@ __device__ __forceinline__ void load_row(const SelKArgs& a, long long rid, bool 
     }
 }
 
-// LDS carve-up shared by the kernels below.
+// candidate scores of one frontier slot: log p^(child) = log p^(parent) + (x - lse)   (Eq. 2)
+template <int KMAX>
+__device__ __forceinline__ void candidate_scores(double S, double lse, const float (&v)[KMAX], bool active, int k,
+                                                 double (&ck)[KMAX]) {
+#pragma unroll
+    for (int r = 0; r < KMAX; ++r)
+        ck[r] = (active && r < k) ? S + ((double)v[r] - lse) : __longlong_as_double(0x7ff8000000000000ll);
+}
+
+// LDS carve-up shared by the kernels below.  DK = rows of the key region (>= depth, and >= DMAX so
+// that the final selection can reuse the region as its key table once the keys sit in registers).
 struct Pool {
-    u64* key;               // [D][NT]   key of pool node (layer t+1, slot)
+    double* key;            // [DK][NT]  log p^ of pool node (layer t+1, slot)
+    double* kt;             // [KMAX][NT] per-lane key table of the per-step selection
     int* tok;               // [D][NT]
-    unsigned short* par;    // [D][NT]   parent slot in the previous layer
-    unsigned short* oidx;   // [D][NT]   output index of a selected node
+    unsigned char* par;     // [D][NT]   parent slot in the previous layer (< 256)
+    unsigned char* oidx;    // [D][NT]   output index of a selected node (< 256)
     u64* mrow;              // [NT][4]   ancestor bitmask rows by output index
 };
-__device__ __forceinline__ Pool carve_pool(void* smem, int D, int NT) {
+__device__ __forceinline__ Pool carve_pool(void* smem, int D, int NT, int DK, int KM) {
     Pool p;
-    p.key = (u64*)smem;
-    p.tok = (int*)(p.key + (size_t)D * NT);
-    p.par = (unsigned short*)(p.tok + (size_t)D * NT);
+    p.key = (double*)smem;
+    p.kt = p.key + (size_t)DK * NT;
+    p.mrow = (u64*)(p.kt + (size_t)KM * NT);
+    p.tok = (int*)(p.mrow + (size_t)NT * 4);
+    p.par = (unsigned char*)(p.tok + (size_t)D * NT);
     p.oidx = p.par + (size_t)D * NT;
-    p.mrow = (u64*)(p.oidx + (size_t)D * NT);
     return p;
 }
-inline size_t pool_lds_bytes(int D, int NT) { return (size_t)D * NT * (8 + 4 + 2 + 2) + (size_t)NT * 4 * 8; }
+inline size_t pool_lds_bytes(int D, int NT, int DK, int KM) {
+    return (size_t)DK * NT * 8 + (size_t)KM * NT * 8 + (size_t)NT * 4 * 8 + (size_t)D * NT * (4 + 1 + 1);
+}
 
-// Last line of Algorithm 1 and the outputs.  `steps` layers are in the pool.
+// Last line of Algorithm 1 and the outputs.  `steps` layers are in the pool; lo0 (or NaN) is a
+// value that at least n pool nodes reach (the largest cut value of the steps that cut to n).
 template <int DMAX, bool SINGLE>
-__device__ void finalize_tree(const SelKArgs& a, const Pool& P, int steps, int b, Group<SINGLE>& g, int* s_cntw /*[OT_MAX_DEPTH][4]*/,
-                              double* s_dsum /*[4]*/) {
+__device__ void finalize_tree(const SelKArgs& a, const Pool& P, int steps, int b, double lo0, Group<SINGLE>& g,
+                              int* s_cntw /*[OT_MAX_DEPTH][4]*/, int* s_hist) {
     const int NT = blockDim.x, tid = threadIdx.x, n = a.n;
     const int W = OT_MASK_WORDS(n);
     int pool_nodes = 0;
     for (int t = 0; t < steps; ++t) pool_nodes += a.F[t + 1];
     const int n_out = pool_nodes < n ? pool_nodes : n;
 
-    u64 pk[DMAX];
+    double pk[DMAX];
 #pragma unroll
-    for (int t = 0; t < DMAX; ++t) pk[t] = (t < steps && tid < a.F[t + 1]) ? P.key[t * NT + tid] : 0ull;
+    for (int t = 0; t < DMAX; ++t) pk[t] = (t < steps && tid < a.F[t + 1]) ? P.key[t * NT + tid] : nan_d();
 
     unsigned int sel = 0;           // bit t: pool node (layer t+1, slot tid) is in the tree
     if (pool_nodes <= n) {
 #pragma unroll
-        for (int t = 0; t < DMAX; ++t) sel |= (pk[t] != 0ull ? 1u : 0u) << t;
+        for (int t = 0; t < DMAX; ++t) sel |= (pk[t] == pk[t] ? 1u : 0u) << t;
     } else {
-        u64 tau; int lane_gt, lane_eq, total_gt, total_eq;
-        select_threshold<DMAX, SINGLE>(pk, n, g, tau, lane_gt, lane_eq, total_gt, total_eq);
+        lds_sync<SINGLE>();         // every lane has its pool keys in registers: the key region becomes the table
+        const Cut cut = select_keys<DMAX, SINGLE, false>(pk, P.key, s_hist, n, lo0 == lo0, lo0, g);
+        sel = cut.keep;
+        int need = cut.need;
+        if (need > 0 && cut.total_eq == need) {
 #pragma unroll
-        for (int t = 0; t < DMAX; ++t) sel |= (pk[t] > tau ? 1u : 0u) << t;
-        int need = n - total_gt;
-        if (total_eq == need) {
-#pragma unroll
-            for (int t = 0; t < DMAX; ++t) sel |= (pk[t] == tau ? 1u : 0u) << t;
-        } else {                     // ties at the cut: shallower first, then smaller slot
+            for (int t = 0; t < DMAX; ++t) sel |= (pk[t] == cut.tau ? 1u : 0u) << t;
+        } else if (need > 0) {       // ties at the cut: shallower first, then smaller slot
             for (int t = 0; t < steps; ++t) {
-                u64 kt = 0ull;
+                double kt = nan_d();
 #pragma unroll
                 for (int tt = 0; tt < DMAX; ++tt) kt = (tt == t) ? pk[tt] : kt;
-                const int eq = kt == tau ? 1 : 0;
+                const int eq = kt == cut.tau ? 1 : 0;
                 const int before = g.excl_scan(eq);
                 const int layer_eq = g.sum_i(eq);
                 if (eq && before < need) sel |= 1u << t;
@@ -246,15 +438,23 @@ __device__ void finalize_tree(const SelKArgs& a, const Pool& P, int steps, int b
 
     // output index = rank in (depth, slot) order among the selected nodes
     const int lane = tid & 63;
-    int my_prefix[DMAX];
+    if (SINGLE) {
+        int base = 0;               // wave-uniform: nodes selected in shallower layers
 #pragma unroll
-    for (int t = 0; t < DMAX; ++t) {
-        const u64 bal = __ballot((sel >> t) & 1u);
-        my_prefix[t] = __popcll(bal & ((1ull << lane) - 1ull));
-        if (lane == 0 && t < steps) s_cntw[t * 4 + g.wave] = __popcll(bal);
-    }
-    __syncthreads();
-    {
+        for (int t = 0; t < DMAX; ++t) {
+            const u64 bal = __ballot((sel >> t) & 1u);
+            if ((sel >> t) & 1u) P.oidx[t * NT + tid] = (unsigned char)(base + __popcll(bal & ((1ull << lane) - 1ull)));
+            base += __popcll(bal);
+        }
+    } else {
+        int my_prefix[DMAX];
+#pragma unroll
+        for (int t = 0; t < DMAX; ++t) {
+            const u64 bal = __ballot((sel >> t) & 1u);
+            my_prefix[t] = __popcll(bal & ((1ull << lane) - 1ull));
+            if (lane == 0 && t < steps) s_cntw[t * 4 + g.wave] = __popcll(bal);
+        }
+        lds_sync<SINGLE>();
         int base = 0;
 #pragma unroll
         for (int t = 0; t < DMAX; ++t) {
@@ -265,42 +465,50 @@ __device__ void finalize_tree(const SelKArgs& a, const Pool& P, int steps, int b
                     if (w < g.wave) mine += c;
                     base += c;
                 }
-                if ((sel >> t) & 1u) P.oidx[t * NT + tid] = (unsigned short)(mine + my_prefix[t]);
+                if ((sel >> t) & 1u) P.oidx[t * NT + tid] = (unsigned char)(mine + my_prefix[t]);
             }
         }
     }
-    __syncthreads();
+    lds_sync<SINGLE>();
 
-    // ancestor masks, layer by layer (a parent's row is complete before its children read it)
-    for (int t = 0; t < steps; ++t) {
-        if ((sel >> t) & 1u) {
-            const int i = P.oidx[t * NT + tid];
-            u64 row[4] = {0ull, 0ull, 0ull, 0ull};
-            if (t > 0) {
-                const int pi = P.oidx[(t - 1) * NT + P.par[t * NT + tid]];
+    // output index of every selected node of this lane and of its parent (independent LDS reads)
+    int my_i[DMAX], my_pi[DMAX];
 #pragma unroll
-                for (int w = 0; w < 4; ++w) row[w] = P.mrow[pi * 4 + w];
-            }
-            row[i >> 6] |= 1ull << (i & 63);
-#pragma unroll
-            for (int w = 0; w < 4; ++w) P.mrow[i * 4 + w] = row[w];
+    for (int t = 0; t < DMAX; ++t) {
+        my_i[t] = 0; my_pi[t] = -1;
+        if (t < steps && ((sel >> t) & 1u)) {
+            my_i[t] = P.oidx[t * NT + tid];
+            if (t > 0) my_pi[t] = P.oidx[(t - 1) * NT + P.par[t * NT + tid]];
         }
-        __syncthreads();
     }
-
-    // emit
+    // ancestor masks, layer by layer (a parent's row is complete before its children read it), and
+    // the per-node outputs.  The key region is free again: it collects log p^ by output index.
     const size_t ob = (size_t)b * n;
-    double e_sum = 0.0;
-    for (int t = 0; t < steps; ++t) {
-        if ((sel >> t) & 1u) {
-            const int i = P.oidx[t * NT + tid];
-            const double sc = key_f64(P.key[t * NT + tid]);
-            a.out.token[ob + i] = P.tok[t * NT + tid];
-            a.out.parent[ob + i] = t == 0 ? -1 : (int)P.oidx[(t - 1) * NT + P.par[t * NT + tid]];
-            a.out.depth[ob + i] = t + 1;
-            a.out.score[ob + i] = (float)sc;
-            for (int w = 0; w < W; ++w) a.out.mask[(ob + i) * W + w] = P.mrow[i * 4 + w];
-            e_sum += exp(sc);
+    double* sc_by_index = P.key;
+#pragma unroll
+    for (int t = 0; t < DMAX; ++t) {
+        if (t < steps) {
+            if ((sel >> t) & 1u) {
+                const int i = my_i[t], pi = my_pi[t];
+                u64 row[4] = {0ull, 0ull, 0ull, 0ull};
+                if (t > 0) {
+#pragma unroll
+                    for (int w = 0; w < 4; ++w) row[w] = P.mrow[pi * 4 + w];
+                }
+#pragma unroll
+                for (int w = 0; w < 4; ++w) row[w] |= (w == (i >> 6)) ? (1ull << (i & 63)) : 0ull;
+#pragma unroll
+                for (int w = 0; w < 4; ++w) P.mrow[i * 4 + w] = row[w];
+                sc_by_index[i] = pk[t];
+                a.out.token[ob + i] = P.tok[t * NT + tid];
+                a.out.parent[ob + i] = pi;
+                a.out.depth[ob + i] = t + 1;
+                a.out.score[ob + i] = (float)pk[t];
+#pragma unroll
+                for (int w = 0; w < 4; ++w)
+                    if (w < W) a.out.mask[(ob + i) * W + w] = row[w];
+            }
+            lds_sync<SINGLE>();
         }
     }
     for (int i = n_out + tid; i < n; i += NT) {
@@ -310,13 +518,11 @@ __device__ void finalize_tree(const SelKArgs& a, const Pool& P, int steps, int b
         a.out.score[ob + i] = -INFINITY;
         for (int w = 0; w < W; ++w) a.out.mask[(ob + i) * W + w] = 0ull;
     }
-    e_sum = wave_sum(e_sum);
-    if (lane == 0) s_dsum[g.wave] = e_sum;
-    __syncthreads();
+    // E = sum of p^ (Eq. 3): one exp per lane, node i on lane i
+    double e_sum = tid < n_out ? exp(sc_by_index[tid]) : 0.0;
+    e_sum = g.sum_d(e_sum);
     if (tid == 0) {
-        double e = 0.0;
-        for (int w = 0; w < g.nw; ++w) e += s_dsum[w];
-        a.out.expect[b] = e;
+        a.out.expect[b] = e_sum;
         a.out.n_out[b] = n_out;
     }
 }
@@ -324,25 +530,27 @@ __device__ void finalize_tree(const SelKArgs& a, const Pool& P, int steps, int b
 #define OT_SELECT_SHARED                                   \
     extern __shared__ u64 smem[];                          \
     __shared__ int s_red[8];                               \
-    __shared__ u64 s_bc[2];                                \
-    __shared__ int s_scan[8];                              \
+    __shared__ double s_bc[2];                             \
+    __shared__ double s_redd[8];                           \
     __shared__ int s_cntw[OT_MAX_DEPTH * 4];               \
-    __shared__ double s_dsum[4];                           \
+    __shared__ int s_hist[kBuckets + 4];                   \
     Group<SINGLE> g;                                       \
-    g.red = s_red; g.bc = s_bc; g.scan = s_scan;           \
-    g.phase = g.bphase = g.sphase = 0;                     \
-    g.tid = threadIdx.x; g.wave = threadIdx.x >> 6; g.nw = blockDim.x >> 6;
+    g.red = s_red; g.bc = s_bc; g.redd = s_redd;           \
+    g.phase = g.bphase = g.dphase = 0;                     \
+    g.tid = threadIdx.x; g.lane = threadIdx.x & 63;        \
+    g.wave = threadIdx.x >> 6; g.nw = blockDim.x >> 6;
 
 // One-shot: all steps in one launch, pool resident in LDS.
 template <int KMAX, int DMAX, bool SINGLE>
 __global__ __launch_bounds__(256) void tree_oneshot_kernel(const SelKArgs a) {
     OT_SELECT_SHARED
     const int NT = blockDim.x, tid = threadIdx.x, b = blockIdx.x, D = a.depth;
-    const Pool P = carve_pool(smem, D, NT);
+    const Pool P = carve_pool(smem, D, NT, DMAX, KMAX);
 
     double lse, nlse;
     float v[KMAX], nv[KMAX];
     int id[KMAX], nid[KMAX];
+    double lo0 = nan_d();
     load_row<KMAX>(a, (long long)b * a.rows_per_seq + tid, tid < a.F[0], nlse, nv, nid);
     for (int t = 0; t < D; ++t) {
         const int F = a.F[t], Fn = a.F[t + 1];
@@ -352,31 +560,31 @@ __global__ __launch_bounds__(256) void tree_oneshot_kernel(const SelKArgs a) {
         for (int r = 0; r < KMAX; ++r) { v[r] = nv[r]; id[r] = nid[r]; }
         if (t + 1 < D)   // next step's row: its address does not depend on the tree, fetch it now
             load_row<KMAX>(a, (long long)b * a.rows_per_seq + a.row_start[t + 1] + tid, tid < Fn, nlse, nv, nid);
-        const double S = (t == 0 || !active) ? 0.0 : key_f64(P.key[(t - 1) * NT + tid]);
-        u64 ck[KMAX];
-#pragma unroll
-        for (int r = 0; r < KMAX; ++r)
-            ck[r] = (active && r < a.k) ? f64_key(S + ((double)v[r] - lse)) : 0ull;
+        const double S = (t == 0 || !active) ? 0.0 : P.key[(t - 1) * NT + tid];
+        double ck[KMAX];
+        candidate_scores<KMAX>(S, lse, v, active, a.k, ck);
         int cnt, off;
-        layer_cut<KMAX, SINGLE>(ck, active, a.k, F, Fn, g, cnt, off);
+        double tau;
+        layer_cut<KMAX, SINGLE>(ck, P.kt, s_hist, active, a.k, F, Fn, a.r0[t], g, cnt, off, tau);
+        if (tau == tau) lo0 = (lo0 == lo0) ? fmax(lo0, tau) : tau;
 #pragma unroll
         for (int r = 0; r < KMAX; ++r) {
             if (r < cnt) {
                 P.key[t * NT + off + r] = ck[r];
                 P.tok[t * NT + off + r] = id[r];
-                P.par[t * NT + off + r] = (unsigned short)tid;
+                P.par[t * NT + off + r] = (unsigned char)tid;
             }
         }
-        __syncthreads();
+        lds_sync<SINGLE>();
     }
-    finalize_tree<DMAX, SINGLE>(a, P, D, b, g, s_cntw, s_dsum);
+    finalize_tree<DMAX, SINGLE>(a, P, D, b, lo0, g, s_cntw, s_hist);
 }
 
 // Streaming: one drafting step; the pool lives in the caller's workspace between launches.
 template <int KMAX, bool SINGLE>
 __global__ __launch_bounds__(256) void tree_step_kernel(const SelKArgs a) {
     OT_SELECT_SHARED
-    (void)smem; (void)s_cntw; (void)s_dsum;
+    (void)s_cntw;
     const int tid = threadIdx.x, b = blockIdx.x, t = a.step, n = a.n;
     const int F = a.F[t], Fn = a.F[t + 1];
     const bool active = tid < F;
@@ -385,12 +593,13 @@ __global__ __launch_bounds__(256) void tree_step_kernel(const SelKArgs a) {
     float v[KMAX];
     int id[KMAX];
     load_row<KMAX>(a, (long long)b * a.rows_per_seq + tid, active, lse, v, id);
-    const double S = (t == 0 || !active) ? 0.0 : key_f64(a.pool_key[pb + (size_t)(t - 1) * n + tid]);
-    u64 ck[KMAX];
-#pragma unroll
-    for (int r = 0; r < KMAX; ++r) ck[r] = (active && r < a.k) ? f64_key(S + ((double)v[r] - lse)) : 0ull;
+    const double S = (t == 0 || !active) ? 0.0 : a.pool_key[pb + (size_t)(t - 1) * n + tid];
+    double ck[KMAX];
+    candidate_scores<KMAX>(S, lse, v, active, a.k, ck);
     int cnt, off;
-    layer_cut<KMAX, SINGLE>(ck, active, a.k, F, Fn, g, cnt, off);
+    double tau;
+    layer_cut<KMAX, SINGLE>(ck, (double*)smem, s_hist, active, a.k, F, Fn, a.r0[t], g, cnt, off, tau);
+    if (tid == 0) a.step_tau[(size_t)b * a.depth + t] = tau;
 #pragma unroll
     for (int r = 0; r < KMAX; ++r) {
         if (r < cnt) {
@@ -408,26 +617,37 @@ template <int DMAX, bool SINGLE>
 __global__ __launch_bounds__(256) void tree_finalize_kernel(const SelKArgs a) {
     OT_SELECT_SHARED
     const int NT = blockDim.x, tid = threadIdx.x, b = blockIdx.x, n = a.n, steps = a.step;
-    const Pool P = carve_pool(smem, a.depth, NT);
+    const Pool P = carve_pool(smem, a.depth, NT, DMAX, 0);
     const size_t pb = (size_t)b * a.depth * n;
+    double lo0 = nan_d();
     for (int t = 0; t < steps; ++t) {
         if (tid < a.F[t + 1]) {
             const size_t o = pb + (size_t)t * n + tid;
             P.key[t * NT + tid] = a.pool_key[o];
             P.tok[t * NT + tid] = a.pool_tok[o];
-            P.par[t * NT + tid] = (unsigned short)a.pool_par[o];
+            P.par[t * NT + tid] = (unsigned char)a.pool_par[o];
         }
+        const double tau = a.step_tau[(size_t)b * a.depth + t];
+        if (tau == tau) lo0 = (lo0 == lo0) ? fmax(lo0, tau) : tau;
     }
     __syncthreads();
-    finalize_tree<DMAX, SINGLE>(a, P, steps, b, g, s_cntw, s_dsum);
+    finalize_tree<DMAX, SINGLE>(a, P, steps, b, lo0, g, s_cntw, s_hist);
 }
 
 SelKArgs make_args(const SelectGeometry& g, const BuildWorkspace& ws) {
     SelKArgs a;
     a.row_lse = ws.row_lse; a.row_topv = ws.row_topv; a.row_topi = ws.row_topi;
     a.k = g.k; a.n = g.n; a.depth = g.depth; a.rows_per_seq = g.rows_per_seq;
-    for (int i = 0; i < OT_MAX_DEPTH + 2; ++i) { a.F[i] = g.F[i]; a.row_start[i] = g.row_start[i]; }
-    a.pool_key = ws.pool_key; a.pool_tok = ws.pool_tok; a.pool_par = ws.pool_par;
+    for (int i = 0; i < OT_MAX_DEPTH + 2; ++i) {
+        a.F[i] = g.F[i];
+        a.row_start[i] = g.row_start[i];
+        a.r0[i] = 0;
+    }
+    for (int t = 0; t < g.depth; ++t) {
+        const int want = g.F[t + 1], F = g.F[t];
+        a.r0[t] = F > 0 ? (want + F - 1) / F - 1 : 0;
+    }
+    a.pool_key = ws.pool_key; a.pool_tok = ws.pool_tok; a.pool_par = ws.pool_par; a.step_tau = ws.step_tau;
     a.out = ot_tree_out{nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
     a.frontier_token = nullptr; a.frontier_parent = nullptr;
     a.step = 0;
@@ -446,7 +666,8 @@ int set_lds(K kernel, size_t bytes) {
 }
 
 template <int KMAX, int DMAX, bool SINGLE>
-int launch_oneshot_t(const SelKArgs& a, int batch, int NT, size_t lds, hipStream_t s) {
+int launch_oneshot_t(const SelKArgs& a, int batch, int NT, hipStream_t s) {
+    const size_t lds = pool_lds_bytes(a.depth, NT, DMAX, KMAX);
     int st = set_lds(tree_oneshot_kernel<KMAX, DMAX, SINGLE>, lds);
     if (st != OT_OK) return st;
     hipLaunchKernelGGL((tree_oneshot_kernel<KMAX, DMAX, SINGLE>), dim3(batch), dim3(NT), lds, s, a);
@@ -454,21 +675,40 @@ int launch_oneshot_t(const SelKArgs& a, int batch, int NT, size_t lds, hipStream
     return OT_OK;
 }
 template <int KMAX, bool SINGLE>
-int launch_oneshot_k(const SelKArgs& a, int batch, int NT, size_t lds, hipStream_t s) {
-    if (a.depth <= 8) return launch_oneshot_t<KMAX, 8, SINGLE>(a, batch, NT, lds, s);
-    if (a.depth <= 16) return launch_oneshot_t<KMAX, 16, SINGLE>(a, batch, NT, lds, s);
-    return launch_oneshot_t<KMAX, 32, SINGLE>(a, batch, NT, lds, s);
+int launch_oneshot_k(const SelKArgs& a, int batch, int NT, hipStream_t s) {
+    if (a.depth <= 8) return launch_oneshot_t<KMAX, 8, SINGLE>(a, batch, NT, s);
+    if (a.depth <= 10) return launch_oneshot_t<KMAX, 10, SINGLE>(a, batch, NT, s);
+    if (a.depth <= 12) return launch_oneshot_t<KMAX, 12, SINGLE>(a, batch, NT, s);
+    if (a.depth <= 16) return launch_oneshot_t<KMAX, 16, SINGLE>(a, batch, NT, s);
+    if (a.depth <= 20) return launch_oneshot_t<KMAX, 20, SINGLE>(a, batch, NT, s);
+    return launch_oneshot_t<KMAX, 32, SINGLE>(a, batch, NT, s);
 }
 template <bool SINGLE>
-int launch_oneshot_s(const SelKArgs& a, int batch, int NT, size_t lds, hipStream_t s) {
-    if (a.k <= 4) return launch_oneshot_k<4, SINGLE>(a, batch, NT, lds, s);
-    if (a.k <= 8) return launch_oneshot_k<8, SINGLE>(a, batch, NT, lds, s);
-    if (a.k <= 12) return launch_oneshot_k<12, SINGLE>(a, batch, NT, lds, s);
-    return launch_oneshot_k<16, SINGLE>(a, batch, NT, lds, s);
+int launch_oneshot_s(const SelKArgs& a, int batch, int NT, hipStream_t s) {
+    if (a.k <= 4) return launch_oneshot_k<4, SINGLE>(a, batch, NT, s);
+    if (a.k <= 8) return launch_oneshot_k<8, SINGLE>(a, batch, NT, s);
+    if (a.k <= 10) return launch_oneshot_k<10, SINGLE>(a, batch, NT, s);
+    return launch_oneshot_k<16, SINGLE>(a, batch, NT, s);
+}
+
+template <int KMAX, bool SINGLE>
+int launch_step_t(const SelKArgs& a, int batch, int NT, hipStream_t s) {
+    const size_t lds = (size_t)KMAX * NT * 8;
+    hipLaunchKernelGGL((tree_step_kernel<KMAX, SINGLE>), dim3(batch), dim3(NT), lds, s, a);
+    OT_HIP_CHECK(hipGetLastError());
+    return OT_OK;
+}
+template <bool SINGLE>
+int launch_step_s(const SelKArgs& a, int batch, int NT, hipStream_t s) {
+    if (a.k <= 4) return launch_step_t<4, SINGLE>(a, batch, NT, s);
+    if (a.k <= 8) return launch_step_t<8, SINGLE>(a, batch, NT, s);
+    if (a.k <= 10) return launch_step_t<10, SINGLE>(a, batch, NT, s);
+    return launch_step_t<16, SINGLE>(a, batch, NT, s);
 }
 
 template <int DMAX, bool SINGLE>
-int launch_finalize_t(const SelKArgs& a, int batch, int NT, size_t lds, hipStream_t s) {
+int launch_finalize_t(const SelKArgs& a, int batch, int NT, hipStream_t s) {
+    const size_t lds = pool_lds_bytes(a.depth, NT, DMAX, 0);
     int st = set_lds(tree_finalize_kernel<DMAX, SINGLE>, lds);
     if (st != OT_OK) return st;
     hipLaunchKernelGGL((tree_finalize_kernel<DMAX, SINGLE>), dim3(batch), dim3(NT), lds, s, a);
@@ -482,8 +722,7 @@ int launch_tree_oneshot(const SelectGeometry& g, const BuildWorkspace& ws, const
     SelKArgs a = make_args(g, ws);
     a.out = out;
     const int NT = threads_for(g.n);
-    const size_t lds = pool_lds_bytes(g.depth, NT);
-    return NT == 64 ? launch_oneshot_s<true>(a, g.batch, NT, lds, s) : launch_oneshot_s<false>(a, g.batch, NT, lds, s);
+    return NT == 64 ? launch_oneshot_s<true>(a, g.batch, NT, s) : launch_oneshot_s<false>(a, g.batch, NT, s);
 }
 
 int launch_tree_step(const SelectGeometry& g, int step, const BuildWorkspace& ws, int32_t* frontier_token,
@@ -492,15 +731,7 @@ int launch_tree_step(const SelectGeometry& g, int step, const BuildWorkspace& ws
     a.step = step;
     a.frontier_token = frontier_token; a.frontier_parent = frontier_parent;
     const int NT = threads_for(g.n);
-#define OT_STEP(KM)                                                                                         \
-    do {                                                                                                    \
-        if (NT == 64) hipLaunchKernelGGL((tree_step_kernel<KM, true>), dim3(g.batch), dim3(NT), 0, s, a);   \
-        else          hipLaunchKernelGGL((tree_step_kernel<KM, false>), dim3(g.batch), dim3(NT), 0, s, a);  \
-    } while (0)
-    if (g.k <= 4) OT_STEP(4); else if (g.k <= 8) OT_STEP(8); else if (g.k <= 12) OT_STEP(12); else OT_STEP(16);
-#undef OT_STEP
-    OT_HIP_CHECK(hipGetLastError());
-    return OT_OK;
+    return NT == 64 ? launch_step_s<true>(a, g.batch, NT, s) : launch_step_s<false>(a, g.batch, NT, s);
 }
 
 int launch_tree_finalize(const SelectGeometry& g, int steps_done, const BuildWorkspace& ws, const ot_tree_out& out,
@@ -509,15 +740,14 @@ int launch_tree_finalize(const SelectGeometry& g, int steps_done, const BuildWor
     a.out = out;
     a.step = steps_done;
     const int NT = threads_for(g.n);
-    const size_t lds = pool_lds_bytes(g.depth, NT);
     if (NT == 64) {
-        if (steps_done <= 8) return launch_finalize_t<8, true>(a, g.batch, NT, lds, s);
-        if (steps_done <= 16) return launch_finalize_t<16, true>(a, g.batch, NT, lds, s);
-        return launch_finalize_t<32, true>(a, g.batch, NT, lds, s);
+        if (steps_done <= 8) return launch_finalize_t<8, true>(a, g.batch, NT, s);
+        if (steps_done <= 16) return launch_finalize_t<16, true>(a, g.batch, NT, s);
+        return launch_finalize_t<32, true>(a, g.batch, NT, s);
     }
-    if (steps_done <= 8) return launch_finalize_t<8, false>(a, g.batch, NT, lds, s);
-    if (steps_done <= 16) return launch_finalize_t<16, false>(a, g.batch, NT, lds, s);
-    return launch_finalize_t<32, false>(a, g.batch, NT, lds, s);
+    if (steps_done <= 8) return launch_finalize_t<8, false>(a, g.batch, NT, s);
+    if (steps_done <= 16) return launch_finalize_t<16, false>(a, g.batch, NT, s);
+    return launch_finalize_t<32, false>(a, g.batch, NT, s);
 }
 
 }  // namespace ot
