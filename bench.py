@@ -27,6 +27,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published
+# HBM bytes one row-scan launch moves (rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, scaled by the same
+# counters' readings for a plain 256 MiB copy); see profiles/bench_7b_hbm_traffic_pmc.txt
+SCAN_TRAFFIC_BYTES = {"7b": 26.58e6}
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, published
 
 
@@ -100,6 +103,9 @@ def main():
     ap.add_argument("--ring", type=int, default=0, help="input copies cycled through (0: enough for 768 MB)")
     ap.add_argument("--no-events", action="store_true", help="do not time individual kernels in the timed region")
     ap.add_argument("--cpu-steps", type=int, default=4, help="oracle steps timed for cpu_baseline (0 = skip)")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain 256 MiB device copy (reference dispatch for scaling rocprofv3 "
+                         "FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); run with --gpus 1",
@@ -163,6 +169,13 @@ def main():
     tol = 2e-2 if w.dtype == "bf16" else 1e-5
     assert err < tol, f"attention parity {err}"
 
+    if args.calibration_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").random_(0, 255)
+        dst = torch.empty_like(src)
+        dst.copy_(src)           # reads 256 MiB and writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
+
     # ---- warm-up ---------------------------------------------------------------------------
     for i in range(args.warmup):
         builds[i % ring](stream)
@@ -220,7 +233,8 @@ def main():
     if scan_ms is not None:
         gbs = logit_bytes / (scan_ms * 1e-3) / 1e9
         result["roofline"] = {"kernel": "row_scan_kernel", "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS,
-                              "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS, "traffic": None,
+                              "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
+                              "traffic": SCAN_TRAFFIC_BYTES.get(w.name),
                               "algorithmic_bytes": logit_bytes, "avg_kernel_us": scan_ms * 1e3}
         agbs = (kv_bytes + qo_bytes) / (attn_ms * 1e-3) / 1e9
         result["roofline_attention"] = {
