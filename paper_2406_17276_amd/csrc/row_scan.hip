@@ -42,10 +42,9 @@ __device__ __forceinline__ unsigned int f32_key(float v) {
     return (u >> 31) ? ~u : (u | 0x80000000u);
 }
 
-template <int DT, int NT, bool VECLOAD>
+template <int DT, int NT, int EPL, bool VECLOAD>
 __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu((NT == 1024 && VECLOAD) ? 8 : 4, 8))) void row_scan_kernel(const ScanKArgs a) {
-    constexpr int VEC = (DT == OT_BF16) ? 8 : 4;
-    constexpr int EPL = 32;             // elements per lane
+    constexpr int VEC = (DT == OT_BF16) ? 8 : 4;   // elements per 16-byte vector; EPL = elements per lane
     constexpr int VPL = EPL / VEC;      // 16-byte vectors per lane
     constexpr int NW = NT / 64;
 
@@ -134,8 +133,11 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu((NT == 1024 
     const double s_w = wave_sum_d((double)(acc[0] + acc[1]) + (double)(acc[2] + acc[3]));
     const int lane = tid & 63, wave = tid >> 6;
     if (lane == 0) { s_wm[wave] = m_w; s_ws[wave] = s_w; }
-    if (NT == 1024) { if (lane == 0) s_gmax[wave] = m_w; }
-    else            { if ((lane & 15) == 0) s_gmax[tid >> 4] = rmax; }
+    // 16 group maxima: a group is 1/16th of the workgroup (a wavefront, half of one, or a row of 16 lanes)
+    if (NT == 1024)     { if (lane == 0) s_gmax[wave] = m_w; }
+    else if (NT == 512) { if (lane == 0) { s_gmax[2 * wave] = fmaxf(rl_f(rmax, 0), rl_f(rmax, 16));
+                                           s_gmax[2 * wave + 1] = fmaxf(rl_f(rmax, 32), rl_f(rmax, 48)); } }
+    else                { if ((lane & 15) == 0) s_gmax[tid >> 4] = rmax; }
     __syncthreads();
 
     // ---- 3. tau: the kk-th largest of the 16 group maxima ------------------
@@ -189,7 +191,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu((NT == 1024 
         M = fmaxf(M, __int_as_float(dpp_i<DPP_QUAD_XOR2>(__float_as_int(M), __float_as_int(M))));
         M = fmaxf(M, __int_as_float(dpp_i<DPP_ROW_HALF_MIRROR>(__float_as_int(M), __float_as_int(M))));
         M = fmaxf(M, __int_as_float(dpp_i<DPP_ROW_MIRROR>(__float_as_int(M), __float_as_int(M))));
-        double part_sum = (have && mw > -INFINITY) ? s_ws[lane] * exp((double)mw - (double)M) : 0.0;
+        double part_sum = (have && mw > -INFINITY) ? s_ws[lane] * (double)__builtin_amdgcn_exp2f((mw - M) * kLog2e) : 0.0;
         part_sum += dpp_d<DPP_QUAD_XOR1>(part_sum);
         part_sum += dpp_d<DPP_QUAD_XOR2>(part_sum);
         part_sum += dpp_d<DPP_ROW_HALF_MIRROR>(part_sum);
@@ -207,16 +209,16 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu((NT == 1024 
     // ---- 5b. rank the candidates -------------------------------------------
     if (ncand <= kCandCap) {
         if (ncand <= 64) {
-            if (tid < ncand) {
-                const float v = s_cv[tid];
-                const int id = s_ci[tid];
+            if (wave == 0) {          // candidate i sits in lane i; the others are broadcast by v_readlane
+                const float v = lane < ncand ? s_cv[lane] : -INFINITY;
+                const int id = lane < ncand ? s_ci[lane] : 0x7fffffff;
                 int rank = 0;
                 for (int jj = 0; jj < ncand; ++jj) {
-                    const float u = s_cv[jj];
-                    const int ui = s_ci[jj];
+                    const float u = rl_f(v, jj);
+                    const int ui = rl(id, jj);
                     rank += (u > v || (u == v && ui < id)) ? 1 : 0;
                 }
-                if (rank < a.k) { outv[rank] = v; outi[rank] = id; }
+                if (lane < ncand && rank < a.k) { outv[rank] = v; outi[rank] = id; }
             }
             return;
         }
@@ -347,6 +349,9 @@ int launch_row_scan(const ScanGeometry& g, const void* logits, const BuildWorksp
     const bool aligned = ((uintptr_t)logits % 16 == 0) && (g.stride_seq % vec == 0) && (g.stride_depth % vec == 0) &&
                          (g.stride_row % vec == 0) && (g.vocab % vec == 0);
     const bool small = a.part_elems <= 256 * 32;
+#ifndef OT_SCAN_WIDE
+#define OT_SCAN_WIDE 0
+#endif
     const long long rows = (long long)g.batch * g.rows_per_seq;
     const long long grid = rows * parts;
     if (grid <= 0 || grid > 0x7fffffffLL) return OT_ERR_UNSUPPORTED;
@@ -354,11 +359,15 @@ int launch_row_scan(const ScanGeometry& g, const void* logits, const BuildWorksp
 
 #define OT_SCAN_LAUNCH(DT, NT, VL)                                                                       \
     do {                                                                                                 \
-        if (ev0 || ev1) hipExtLaunchKernelGGL((row_scan_kernel<DT, NT, VL>), gd, dim3(NT), 0, s, ev0, ev1, 0, a); \
-        else hipLaunchKernelGGL((row_scan_kernel<DT, NT, VL>), gd, dim3(NT), 0, s, a);                   \
+        if (ev0 || ev1) hipExtLaunchKernelGGL((row_scan_kernel<DT, NT, 32, VL>), gd, dim3(NT), 0, s, ev0, ev1, 0, a); \
+        else hipLaunchKernelGGL((row_scan_kernel<DT, NT, 32, VL>), gd, dim3(NT), 0, s, a);               \
     } while (0)
     if (g.dtype == OT_BF16) {
         if (small) { if (aligned) OT_SCAN_LAUNCH(OT_BF16, 256, true); else OT_SCAN_LAUNCH(OT_BF16, 256, false); }
+        else if (OT_SCAN_WIDE && aligned) {
+            if (ev0 || ev1) hipExtLaunchKernelGGL((row_scan_kernel<OT_BF16, 512, 64, true>), gd, dim3(512), 0, s, ev0, ev1, 0, a);
+            else hipLaunchKernelGGL((row_scan_kernel<OT_BF16, 512, 64, true>), gd, dim3(512), 0, s, a);
+        }
         else       { if (aligned) OT_SCAN_LAUNCH(OT_BF16, 1024, true); else OT_SCAN_LAUNCH(OT_BF16, 1024, false); }
     } else {
         if (small) { if (aligned) OT_SCAN_LAUNCH(OT_F32, 256, true); else OT_SCAN_LAUNCH(OT_F32, 256, false); }

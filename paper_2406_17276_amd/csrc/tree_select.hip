@@ -215,37 +215,48 @@ __device__ Cut select_keys(const double (&key)[M], double* kt, int* hist, int wa
                 int q = (int)u[r];
                 bk[r] = q < 0 ? 0 : (q > kBuckets - 1 ? kBuckets - 1 : q);
             }
-            for (int i = tid; i < kBuckets; i += NT) hist[i] = 0;
-            lds_sync<SINGLE>();
+            // hist is all zero here (cleared once per kernel, and re-cleared by the scan below)
 #pragma unroll
             for (int r = 0; r < M; ++r)
                 if ((in >> r) & 1u) atomicAdd(&hist[bk[r]], 1);
             lds_sync<SINGLE>();
             const int T = want - f_hi;            // rank of the cut among the keys in range
+            int B = -1, above = 0, inb = 0, total = 0;
             if (g.wave == 0) {
+                constexpr int BPL = kBuckets / 64;                 // buckets per lane of the scanning wavefront
                 const int L = g.lane;
-                const int c0 = hist[4 * L], c1 = hist[4 * L + 1], c2 = hist[4 * L + 2], c3 = hist[4 * L + 3];
-                const int sum = c0 + c1 + c2 + c3;
+                int c[BPL];
+                int sum = 0;
+#pragma unroll
+                for (int i = 0; i < BPL; ++i) { c[i] = hist[BPL * L + i]; sum += c[i]; }
+#pragma unroll
+                for (int i = 0; i < BPL; ++i) hist[BPL * L + i] = 0;
                 const int P = wave_incl_scan(sum, L);
-                const int total = rl(P, 63);
+                total = rl(P, 63);
                 const int above_lane = total - P;                 // keys in higher lanes' buckets
                 const bool has = above_lane < T && above_lane + sum >= T;
-                int B = 4 * L + 3, above = above_lane, inb = c3;
-                if (above + c3 < T) { above += c3; B = 4 * L + 2; inb = c2;
-                    if (above + c2 < T) { above += c2; B = 4 * L + 1; inb = c1;
-                        if (above + c1 < T) { above += c1; B = 4 * L; inb = c0; } } }
+                int Bl = BPL * L, abl = above_lane, inl = 0;
+                bool found = false;
+#pragma unroll
+                for (int i = BPL - 1; i >= 0; --i) {              // highest bucket first
+                    if (!found) {
+                        if (abl + c[i] >= T) { found = true; Bl = BPL * L + i; inl = c[i]; }
+                        else abl += c[i];
+                    }
+                }
                 const u64 bal = __ballot(has);
                 if (bal != 0ull) {
                     const int src = __ffsll((long long)bal) - 1;
-                    if (L == src) { hist[kBuckets] = B; hist[kBuckets + 1] = above; hist[kBuckets + 2] = inb; }
-                } else if (L == 0) {
-                    hist[kBuckets] = -1;
+                    B = rl(Bl, src); above = rl(abl, src); inb = rl(inl, src);
                 }
-                if (L == 0) hist[kBuckets + 3] = total;
+                if (!SINGLE && L == 0) {
+                    hist[kBuckets] = B; hist[kBuckets + 1] = above; hist[kBuckets + 2] = inb; hist[kBuckets + 3] = total;
+                }
             }
-            lds_sync<SINGLE>();
-            const int B = hist[kBuckets], above = hist[kBuckets + 1], inb = hist[kBuckets + 2];
-            const int total = hist[kBuckets + 3];
+            if (!SINGLE) {
+                lds_sync<SINGLE>();
+                B = hist[kBuckets]; above = hist[kBuckets + 1]; inb = hist[kBuckets + 2]; total = hist[kBuckets + 3];
+            }
             if (level == 0) f_lo = f_hi + total;
             if (B < 0) break;                     // cannot happen while count(key >= lo) >= want; be safe
             unsigned gt = 0u, eq = 0u;
@@ -538,7 +549,9 @@ __device__ void finalize_tree(const SelKArgs& a, const Pool& P, int steps, int b
     g.red = s_red; g.bc = s_bc; g.redd = s_redd;           \
     g.phase = g.bphase = g.dphase = 0;                     \
     g.tid = threadIdx.x; g.lane = threadIdx.x & 63;        \
-    g.wave = threadIdx.x >> 6; g.nw = blockDim.x >> 6;
+    g.wave = threadIdx.x >> 6; g.nw = blockDim.x >> 6;     \
+    for (int i_ = threadIdx.x; i_ < kBuckets + 4; i_ += blockDim.x) s_hist[i_] = 0; \
+    __syncthreads();
 
 // One-shot: all steps in one launch, pool resident in LDS.
 template <int KMAX, int DMAX, bool SINGLE>
