@@ -45,10 +45,20 @@ struct AttnKArgs {
     void* O;
     float* part_o;      // [rows_total][splits][D]
     float* part_ml;     // [rows_total][splits][2]
-    int batch, q_heads, kv_heads, g, n, D, max_prefix, splits, W, dtype;
+    int batch, q_heads, kv_heads, g, n, D, max_prefix, splits, W, dtype, row_blocks;
     float scale_log2;   // softmax scale * log2(e)
     long long qs[3], kps[3], vps[3], kts[3], vts[3], os[3];
 };
+
+// max over lanes l and l ^ 32 (v_permlane32_swap: no LDS round trip)
+__device__ __forceinline__ float xhalf_max(float v) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float xhalf_sum(float v) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
 
 __device__ __forceinline__ int clamp_len(int L, int maxp) { return L < 0 ? 0 : (L > maxp ? maxp : L); }
 
@@ -61,25 +71,40 @@ __device__ __forceinline__ void split_range(int T, int S, int s, int& t0, int& t
 // ---------------------------------------------------------------------------
 // bf16 MFMA kernel
 // ---------------------------------------------------------------------------
-template <int D>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_mfma_kernel(const AttnKArgs a) {
+// WIDE = false: 64 packed rows per workgroup, wavefront = (query block of 32 rows) x (half of each
+//                64-key tile); the two halves are merged through LDS at the end.  For few rows.
+// WIDE = true : 128 packed rows per workgroup, wavefront = 32 rows x the whole tile; staging one
+//                tile in LDS is shared by twice as many MFMAs and nothing is merged at the end.
+// Workgroups are numbered so that those which stream the same K/V (the row blocks of one
+// (sequence, KV head, split)) sit on the same XCD, next to each other in its dispatch order, and
+// share that XCD's L2: hardware hands workgroup L to XCD L % 8.
+#ifndef OT_ATTN_WPE
+#define OT_ATTN_WPE 2
+#endif
+template <int D, bool WIDE>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(OT_ATTN_WPE, OT_ATTN_WPE))) void attn_mfma_kernel(const AttnKArgs a) {
     constexpr int TK = 64;                 // keys per tile
     constexpr int KPAD = D + 8;            // bf16 elements per K row in LDS
     constexpr int VDP = D + 16;            // dwords per key-pair row of V in LDS (2 VDP % 64 == 32)
     constexpr int SLABS = D / 16;          // 16-wide d slabs of the QK^T contraction
     constexpr int DB = D / 32;             // 32-wide d blocks of O^T
     constexpr int CH = TK * D / 8 / 256;   // 16-byte chunks per thread per tile (K or V)
+    constexpr int NKB = WIDE ? 2 : 1;      // 32-key blocks per wavefront per tile
+    constexpr int ROWS = WIDE ? 128 : 64;  // packed query rows per workgroup
 
-    __shared__ __attribute__((aligned(16))) unsigned int s_buf[TK * KPAD / 2 + (TK / 2) * VDP];
-    unsigned short* const s_k = (unsigned short*)s_buf;
-    unsigned int* const s_v = s_buf + TK * KPAD / 2;
-    static_assert(sizeof(unsigned int) * (TK * KPAD / 2 + (TK / 2) * VDP) >= 2 * 64 * (DB * 16 + 2) * 4, "merge buffer fits");
+    constexpr int BUF = TK * KPAD / 2 + (TK / 2) * VDP;   // dwords of one staged tile (K then V)
+    extern __shared__ __attribute__((aligned(16))) unsigned int s_buf[];   // two tiles: [2][BUF]
+    static_assert(sizeof(unsigned int) * 2 * BUF >= 2 * 64 * (DB * 16 + 2) * 4, "merge buffer fits");
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int qb = wave & 1, kh = wave >> 1;
+    const int qb = WIDE ? wave : (wave & 1), kh = WIDE ? 0 : (wave >> 1);
     const int l32 = lane & 31, h = lane >> 5;
-    const int split = blockIdx.x, rb = blockIdx.y;
-    const int b = blockIdx.z / a.kv_heads, hk = blockIdx.z - b * a.kv_heads;
+    // workgroup numbering: see above
+    const int xcd = blockIdx.x & 7, q = blockIdx.x >> 3;
+    const int unit = (q / a.row_blocks) * 8 + xcd, rb = q % a.row_blocks;
+    if (unit >= a.batch * a.kv_heads * a.splits) return;
+    const int bz = unit / a.splits, split = unit - bz * a.splits;
+    const int b = bz / a.kv_heads, hk = bz - b * a.kv_heads;
     const int n = a.n;
     const int L = clamp_len(a.prefix_len[b], a.max_prefix);
     const int ptiles = (L + TK - 1) / TK, ttiles = (n + TK - 1) / TK;
@@ -87,7 +112,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     split_range(ptiles + ttiles, a.splits, split, t0, t1);
 
     // this lane's query row
-    const int rho = rb * 64 + qb * 32 + l32;           // packed row inside the KV head
+    const int rho = rb * ROWS + qb * 32 + l32;         // packed row inside the KV head
     const bool row_ok = rho < a.g * n;
     const int hq = hk * a.g + (row_ok ? rho / n : 0);
     const int node = row_ok ? rho % n : 0;
@@ -114,6 +139,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const unsigned short* kt = (const unsigned short*)a.Kt + (long long)b * a.kts[0] + (long long)hk * a.kts[1];
     const unsigned short* vt = (const unsigned short*)a.Vt + (long long)b * a.vts[0] + (long long)hk * a.vts[1];
 
+    const float c = a.scale_log2;          // scores are kept raw; p = 2^(c s - c m)
     float m_run = -INFINITY, l_run = 0.f;
     f32x16 oacc[DB];
 #pragma unroll
@@ -121,43 +147,51 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
         for (int v = 0; v < 16; ++v) oacc[d][v] = 0.f;
 
+    // which 16-byte chunks of a tile this thread moves: chunk cc is KSTEP keys below chunk cc-1
+    constexpr int KSTEP = 256 / (D / 8);
+    const int kkey0 = tid / (D / 8), kcol = (tid % (D / 8)) * 8;
+    // V: neighbouring lanes fetch the same 8 columns of two adjacent keys
+    const int vodd = tid & 1;
+    const int vkey0 = 2 * ((tid >> 1) / (D / 8)) + vodd, vcol = ((tid >> 1) % (D / 8)) * 8;
     u32x4 kreg[CH], vreg[CH];
     auto fetch = [&](int t) {
         const bool tree = t >= ptiles;
         const int key0 = tree ? (t - ptiles) * TK : t * TK;
         const int kend = tree ? n : L;
-        const unsigned short* kb = tree ? kt : kp;
-        const unsigned short* vb = tree ? vt : vp;
-        const long long ks = tree ? a.kts[2] : a.kps[2];
-        const long long vs = tree ? a.vts[2] : a.vps[2];
+        const int ks = (int)(tree ? a.kts[2] : a.kps[2]);
+        const int vs = (int)(tree ? a.vts[2] : a.vps[2]);
+        const unsigned short* kbase = (tree ? kt : kp) + (long long)key0 * ks;     // wave-uniform
+        const unsigned short* vbase = (tree ? vt : vp) + (long long)key0 * vs;
+        const int koff = kkey0 * ks + kcol, voff = vkey0 * vs + vcol;
+        if (key0 + TK <= kend) {
 #pragma unroll
-        for (int c = 0; c < CH; ++c) {
-            const int chunk = c * 256 + tid;
-            const int key = chunk / (D / 8), col = (chunk % (D / 8)) * 8;
-            u32x4 kw = {0u, 0u, 0u, 0u};
-            if (key0 + key < kend) kw = *(const u32x4*)(kb + (long long)(key0 + key) * ks + col);
-            kreg[c] = kw;
-            // V: neighbouring lanes fetch the same 8 columns of two adjacent keys
-            const int vkey = 2 * ((chunk >> 1) / (D / 8)) + (chunk & 1), vcol = ((chunk >> 1) % (D / 8)) * 8;
-            u32x4 vw = {0u, 0u, 0u, 0u};
-            if (key0 + vkey < kend) vw = *(const u32x4*)(vb + (long long)(key0 + vkey) * vs + vcol);
-            vreg[c] = vw;
+            for (int cc = 0; cc < CH; ++cc) {
+                kreg[cc] = *(const u32x4*)(kbase + koff + cc * KSTEP * ks);
+                vreg[cc] = *(const u32x4*)(vbase + voff + cc * KSTEP * vs);
+            }
+        } else {
+#pragma unroll
+            for (int cc = 0; cc < CH; ++cc) {
+                u32x4 kw = {0u, 0u, 0u, 0u}, vw = {0u, 0u, 0u, 0u};
+                if (key0 + kkey0 + cc * KSTEP < kend) kw = *(const u32x4*)(kbase + koff + cc * KSTEP * ks);
+                if (key0 + vkey0 + cc * KSTEP < kend) vw = *(const u32x4*)(vbase + voff + cc * KSTEP * vs);
+                kreg[cc] = kw;
+                vreg[cc] = vw;
+            }
         }
     };
 
-    if (t0 < t1) fetch(t0);
-    for (int t = t0; t < t1; ++t) {
-        // stage the fetched tile
+    auto stage = [&](int buf) {
+        unsigned short* const s_k = (unsigned short*)(s_buf + buf * BUF);
+        unsigned int* const s_v = s_buf + buf * BUF + TK * KPAD / 2;
 #pragma unroll
-        for (int c = 0; c < CH; ++c) {
-            const int chunk = c * 256 + tid;
-            const int key = chunk / (D / 8), col = (chunk % (D / 8)) * 8;
-            *(u32x4*)(s_k + key * KPAD + col) = kreg[c];
+        for (int cc = 0; cc < CH; ++cc) {
+            *(u32x4*)(s_k + (kkey0 + cc * KSTEP) * KPAD + kcol) = kreg[cc];
             // pair the columns of keys 2kp (even lane) and 2kp+1 (odd lane): the even lane builds
             // columns vcol..vcol+3, the odd lane vcol+4..vcol+7
-            const int odd = chunk & 1;
-            const int kp = (chunk >> 1) / (D / 8), vcol = ((chunk >> 1) % (D / 8)) * 8;
-            const u32x4 mine = vreg[c];
+            const int odd = vodd;
+            const int kpi = (vkey0 >> 1) + cc * (KSTEP / 2);
+            const u32x4 mine = vreg[cc];
             const unsigned give0 = odd ? mine.x : mine.z, give1 = odd ? mine.y : mine.w;
             const unsigned got0 = (unsigned)dpp_i<DPP_QUAD_XOR1>(0, (int)give0);
             const unsigned got1 = (unsigned)dpp_i<DPP_QUAD_XOR1>(0, (int)give1);
@@ -169,140 +203,162 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             out.y = __builtin_amdgcn_perm(od0, ev0, 0x07060302u);   // column +1: hi16(even) | hi16(odd) << 16
             out.z = __builtin_amdgcn_perm(od1, ev1, 0x05040100u);
             out.w = __builtin_amdgcn_perm(od1, ev1, 0x07060302u);
-            *(u32x4*)(s_v + kp * VDP + vcol + 4 * odd) = out;
+            *(u32x4*)(s_v + kpi * VDP + vcol + 4 * odd) = out;
         }
-        __syncthreads();
+    };
+
+    // tile t is computed from LDS buffer (t - t0) & 1 while tile t+1 is in flight from memory; it is
+    // staged into the other buffer after the computation, so one barrier per tile suffices
+    if (t0 < t1) { fetch(t0); stage(0); }
+    __syncthreads();
+    for (int t = t0; t < t1; ++t) {
+        const int cur = (t - t0) & 1;
+        const unsigned short* const s_k = (const unsigned short*)(s_buf + cur * BUF);
+        const unsigned int* const s_v = s_buf + cur * BUF + TK * KPAD / 2;
         if (t + 1 < t1) fetch(t + 1);
 
         const bool tree = t >= ptiles;
         const int key0 = tree ? (t - ptiles) * TK : t * TK;
         const int kend = tree ? n : L;
 
-        // S^T block: 32 keys (this wave's half of the tile) x 32 queries
-        f32x16 sacc;
+        // one 32-key block at a time: S^T = K Q^T, online softmax, O^T += V^T P^T
 #pragma unroll
-        for (int v = 0; v < 16; ++v) sacc[v] = 0.f;
+        for (int j = 0; j < NKB; ++j) {
+            const int kbi = WIDE ? j : kh;
+            f32x16 sacc;
 #pragma unroll
-        for (int s = 0; s < SLABS; ++s) {
-            const u32x4 kw = *(const u32x4*)(s_k + (32 * kh + l32) * KPAD + 16 * s + 8 * h);
-            sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kw), qf[s], sacc, 0, 0, 0);
-        }
-        // mask and online softmax; accumulator element v is key 32 kh + 8 (v/4) + 4 h + v%4
-        float sc[16];
-        float tmax = -INFINITY;
+            for (int v = 0; v < 16; ++v) sacc[v] = 0.f;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int kl = 32 * kh + 8 * (v >> 2) + 4 * h + (v & 3);
-            const int key = key0 + kl;
-            bool ok = key < kend;
-            if (tree) ok = ok && ((mrow[key >> 6] >> (key & 63)) & 1ull);
-            sc[v] = ok ? sacc[v] * a.scale_log2 : -INFINITY;
-            tmax = fmaxf(tmax, sc[v]);
-        }
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-        const float m_new = fmaxf(m_run, tmax);
-        float alpha = 1.f;
-        bf16x8 pf[2];
-        if (m_new == -INFINITY) {
-#pragma unroll
-            for (int v = 0; v < 16; ++v) pf[v >> 3][v & 7] = (__bf16)0.f;
-        } else {
-            alpha = __builtin_amdgcn_exp2f(m_run - m_new);      // m_run = -inf gives 0
-            float psum = 0.f;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const float p = __builtin_amdgcn_exp2f(sc[v] - m_new);
-                psum += p;
-                pf[v >> 3][v & 7] = (__bf16)p;
+            for (int s = 0; s < SLABS; ++s) {
+                const u32x4 kw = *(const u32x4*)(s_k + (32 * kbi + l32) * KPAD + 16 * s + 8 * h);
+                sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kw), qf[s], sacc, 0, 0, 0);
             }
-            l_run = l_run * alpha + psum;
-            m_run = m_new;
-        }
+            // visibility; accumulator element v is key 32 kbi + 8 (v/4) + 4 h + v%4
+            if (tree || key0 + TK > kend) {
 #pragma unroll
-        for (int d = 0; d < DB; ++d)
+                for (int v = 0; v < 16; ++v) {
+                    const int key = key0 + 32 * kbi + 8 * (v >> 2) + 4 * h + (v & 3);
+                    bool ok = key < kend;
+                    if (tree) ok = ok && ((mrow[(key >> 6) & 3] >> (key & 63)) & 1ull);
+                    sacc[v] = ok ? sacc[v] : -INFINITY;
+                }
+            }
+            float tmax = sacc[0];
 #pragma unroll
-            for (int v = 0; v < 16; ++v) oacc[d][v] *= alpha;
-        // O^T += V^T P^T over the wave's 32 keys: two 16-key slabs
+            for (int v = 1; v < 16; ++v) tmax = fmaxf(tmax, sacc[v]);
+            tmax = xhalf_max(tmax);
+            const float m_new = fmaxf(m_run, tmax);
+            bf16x8 pf[2];
+            if (m_new == -INFINITY) {
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
+                for (int v = 0; v < 16; ++v) pf[v >> 3][v & 7] = (__bf16)0.f;
+            } else {
+                const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);      // m_run = -inf gives 0
+                const float mc = m_new * c;
+                float psum = 0.f;
 #pragma unroll
-            for (int d = 0; d < DB; ++d) {
-                // keys 32kh+16u+4h+{0..3} and +8: key pairs kp0, kp0+1, kp0+4, kp0+5 of column 32d+l32
-                const int kp0 = 16 * kh + 8 * u + 2 * h;
-                const unsigned int* vcolp = s_v + kp0 * VDP + 32 * d + l32;
-                u32x4 vw;
-                vw.x = vcolp[0]; vw.y = vcolp[VDP]; vw.z = vcolp[4 * VDP]; vw.w = vcolp[5 * VDP];
-                oacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vw), pf[u], oacc[d], 0, 0, 0);
+                for (int v = 0; v < 16; ++v) {
+                    const float p = __builtin_amdgcn_exp2f(fmaf(sacc[v], c, -mc));
+                    psum += p;
+                    pf[v >> 3][v & 7] = (__bf16)p;
+                }
+                l_run = l_run * alpha + psum;
+                m_run = m_new;
+                if (__any(alpha != 1.f)) {       // the running maximum rarely moves after the first tiles
+#pragma unroll
+                    for (int d = 0; d < DB; ++d)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) oacc[d][v] *= alpha;
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+#pragma unroll
+                for (int d = 0; d < DB; ++d) {
+                    // keys 32kbi+16u+4h+{0..3} and +8: key pairs kp0, kp0+1, kp0+4, kp0+5 of column 32d+l32
+                    const int kp0 = 16 * kbi + 8 * u + 2 * h;
+                    const unsigned int* vcolp = s_v + kp0 * VDP + 32 * d + l32;
+                    u32x4 vw;
+                    vw.x = vcolp[0]; vw.y = vcolp[VDP]; vw.z = vcolp[4 * VDP]; vw.w = vcolp[5 * VDP];
+                    oacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vw), pf[u], oacc[d], 0, 0, 0);
+                }
             }
         }
+        if (t + 1 < t1) stage(cur ^ 1);
         __syncthreads();
     }
 
-    // merge the two key-half waves of each query block through LDS (tile buffers are free now)
-    l_run += __shfl_xor(l_run, 32);
-    float* s_merge = (float*)s_buf;          // [2 qb][64 lanes][DB*16 + 2]
-    constexpr int MST = DB * 16 + 2;
-    if (kh == 1) {
-        float* dst = s_merge + (qb * 64 + lane) * MST;
+    l_run = xhalf_sum(l_run);
+    float mm = m_run, lt = l_run, a1 = 1.f, a2 = 0.f;
+    const float* src = nullptr;
+    if (!WIDE) {
+        // merge the two key-half waves of each query block through LDS (tile buffers are free now)
+        float* s_merge = (float*)s_buf;          // [2 qb][64 lanes][DB*16 + 2]
+        constexpr int MST = DB * 16 + 2;
+        if (kh == 1) {
+            float* dst = s_merge + (qb * 64 + lane) * MST;
+#pragma unroll
+            for (int d = 0; d < DB; ++d)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) dst[d * 16 + v] = oacc[d][v];
+            dst[DB * 16] = m_run;
+            dst[DB * 16 + 1] = l_run;
+        }
+        __syncthreads();
+        if (kh == 1) return;
+        src = s_merge + (qb * 64 + lane) * MST;
+        const float m2 = src[DB * 16], l2 = src[DB * 16 + 1];
+        mm = fmaxf(m_run, m2);
+        a1 = 0.f;
+        if (mm != -INFINITY) {
+            a1 = __builtin_amdgcn_exp2f((m_run - mm) * c);
+            a2 = __builtin_amdgcn_exp2f((m2 - mm) * c);
+        }
+        lt = l_run * a1 + l2 * a2;
+    }
+    if (!row_ok) return;
+    const long long row = ((long long)b * a.q_heads + hq) * n + node;
+    if (a.splits == 1) {
+        const float inv = lt > 0.f ? 1.f / lt : 0.f;
+        unsigned short* orow =
+            (unsigned short*)a.O + (long long)b * a.os[0] + (long long)hq * a.os[1] + (long long)node * a.os[2];
 #pragma unroll
         for (int d = 0; d < DB; ++d)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) dst[d * 16 + v] = oacc[d][v];
-        dst[DB * 16] = m_run;
-        dst[DB * 16 + 1] = l_run;
-    }
-    __syncthreads();
-    if (kh == 0) {
-        const float* src = s_merge + (qb * 64 + lane) * MST;
-        const float m2 = src[DB * 16], l2 = src[DB * 16 + 1];
-        const float mm = fmaxf(m_run, m2);
-        float a1 = 0.f, a2 = 0.f;
-        if (mm != -INFINITY) {
-            a1 = __builtin_amdgcn_exp2f(m_run - mm);
-            a2 = __builtin_amdgcn_exp2f(m2 - mm);
-        }
-        const float lt = l_run * a1 + l2 * a2;
-        if (row_ok) {
-            const long long row = ((long long)b * a.q_heads + hq) * n + node;
-            if (a.splits == 1) {
-                const float inv = lt > 0.f ? 1.f / lt : 0.f;
-                unsigned short* orow =
-                    (unsigned short*)a.O + (long long)b * a.os[0] + (long long)hq * a.os[1] + (long long)node * a.os[2];
+            for (int v4 = 0; v4 < 4; ++v4) {
+                unsigned short o4[4];
 #pragma unroll
-                for (int d = 0; d < DB; ++d)
-#pragma unroll
-                    for (int v4 = 0; v4 < 4; ++v4) {
-                        unsigned short o4[4];
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            const int v = v4 * 4 + e;
-                            const float val = (oacc[d][v] * a1 + src[d * 16 + v] * a2) * inv;
-                            o4[e] = __builtin_bit_cast(unsigned short, (__bf16)val);
-                        }
-                        uint2 pk;
-                        pk.x = (unsigned)o4[0] | ((unsigned)o4[1] << 16);
-                        pk.y = (unsigned)o4[2] | ((unsigned)o4[3] << 16);
-                        *(uint2*)(orow + 32 * d + 8 * v4 + 4 * h) = pk;
-                    }
-            } else {
-                float* po = a.part_o + (row * a.splits + split) * D;
-#pragma unroll
-                for (int d = 0; d < DB; ++d)
-#pragma unroll
-                    for (int v4 = 0; v4 < 4; ++v4) {
-                        f32x4 o4;
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            const int v = v4 * 4 + e;
-                            o4[e] = oacc[d][v] * a1 + src[d * 16 + v] * a2;
-                        }
-                        *(f32x4*)(po + 32 * d + 8 * v4 + 4 * h) = o4;
-                    }
-                if (h == 0) {
-                    a.part_ml[(row * a.splits + split) * 2] = mm;
-                    a.part_ml[(row * a.splits + split) * 2 + 1] = lt;
+                for (int e = 0; e < 4; ++e) {
+                    const int v = v4 * 4 + e;
+                    float val = oacc[d][v] * a1;
+                    if (!WIDE) val += src[d * 16 + v] * a2;
+                    o4[e] = __builtin_bit_cast(unsigned short, (__bf16)(val * inv));
                 }
+                uint2 pk;
+                pk.x = (unsigned)o4[0] | ((unsigned)o4[1] << 16);
+                pk.y = (unsigned)o4[2] | ((unsigned)o4[3] << 16);
+                *(uint2*)(orow + 32 * d + 8 * v4 + 4 * h) = pk;
             }
+    } else {
+        float* po = a.part_o + (row * a.splits + split) * D;
+#pragma unroll
+        for (int d = 0; d < DB; ++d)
+#pragma unroll
+            for (int v4 = 0; v4 < 4; ++v4) {
+                f32x4 o4;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int v = v4 * 4 + e;
+                    float val = oacc[d][v] * a1;
+                    if (!WIDE) val += src[d * 16 + v] * a2;
+                    o4[e] = val;
+                }
+                *(f32x4*)(po + 32 * d + 8 * v4 + 4 * h) = o4;
+            }
+        if (h == 0) {
+            // the partial's maximum is stored in log2 units (raw maximum times c)
+            a.part_ml[(row * a.splits + split) * 2] = mm == -INFINITY ? -INFINITY : mm * c;
+            a.part_ml[(row * a.splits + split) * 2 + 1] = lt;
         }
     }
 }
@@ -432,31 +488,51 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const AttnKArgs a) {
 }
 
 // Merge the per-split partials of one output row: O = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s.
-__global__ __launch_bounds__(128) void attn_combine_kernel(const AttnKArgs a) {
-    const long long row = blockIdx.x;
-    const int d = threadIdx.x;
-    if (d >= a.D) return;
+// One wavefront per row (4 rows per workgroup); lane s holds split s's (m, l), the weights are
+// broadcast with v_readlane, every lane accumulates D/64 columns.
+__global__ __launch_bounds__(256) void attn_combine_kernel(const AttnKArgs a) {
+    const int lane = threadIdx.x & 63;
+    const long long row = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const long long rows = (long long)a.batch * a.q_heads * a.n;
+    if (row >= rows) return;
     const int n = a.n;
     const int node = (int)(row % n);
     const int hq = (int)((row / n) % a.q_heads);
     const int b = (int)(row / ((long long)n * a.q_heads));
     const float* ml = a.part_ml + row * a.splits * 2;
-    float M = -INFINITY;
-    for (int s = 0; s < a.splits; ++s) M = fmaxf(M, ml[2 * s]);
-    float acc = 0.f, l = 0.f;
-    if (M != -INFINITY) {
-        for (int s = 0; s < a.splits; ++s) {
-            const float m = ml[2 * s];
-            if (m == -INFINITY) continue;
-            const float w = exp2f(m - M);
-            l += w * ml[2 * s + 1];
-            acc += w * a.part_o[(row * a.splits + s) * a.D + d];
+    const float* po = a.part_o + row * a.splits * a.D;
+    float m = -INFINITY, l = 0.f;
+    if (lane < a.splits) { m = ml[2 * lane]; l = ml[2 * lane + 1]; }
+    const float M = wave_max_f(m);
+    const float w = (m == -INFINITY) ? 0.f : exp2f(m - M);
+    float wl = w * l;
+    wl += __int_as_float(dpp_i<DPP_QUAD_XOR1>(0, __float_as_int(wl)));
+    wl += __int_as_float(dpp_i<DPP_QUAD_XOR2>(0, __float_as_int(wl)));
+    wl += __int_as_float(dpp_i<DPP_ROW_HALF_MIRROR>(0, __float_as_int(wl)));
+    wl += __int_as_float(dpp_i<DPP_ROW_MIRROR>(0, __float_as_int(wl)));
+    const float Lsum = (rl_f(wl, 0) + rl_f(wl, 16)) + (rl_f(wl, 32) + rl_f(wl, 48));
+    const float inv = Lsum > 0.f ? 1.f / Lsum : 0.f;
+    const int per = a.D / 64;                 // 1 or 2 columns per lane
+    float acc0 = 0.f, acc1 = 0.f;
+    for (int s = 0; s < a.splits; ++s) {
+        const float ws = rl_f(w, s);
+        if (per == 2) {
+            const float2 v = *(const float2*)(po + (long long)s * a.D + 2 * lane);
+            acc0 = fmaf(ws, v.x, acc0); acc1 = fmaf(ws, v.y, acc1);
+        } else {
+            acc0 = fmaf(ws, po[(long long)s * a.D + lane], acc0);
         }
     }
-    const float val = l > 0.f ? acc / l : 0.f;
-    const long long off = (long long)b * a.os[0] + (long long)hq * a.os[1] + (long long)node * a.os[2] + d;
-    if (a.dtype == OT_BF16) ((unsigned short*)a.O)[off] = __builtin_bit_cast(unsigned short, (__bf16)val);
-    else ((float*)a.O)[off] = val;
+    const long long off = (long long)b * a.os[0] + (long long)hq * a.os[1] + (long long)node * a.os[2] + per * lane;
+    if (a.dtype == OT_BF16) {
+        unsigned short* o = (unsigned short*)a.O + off;
+        o[0] = __builtin_bit_cast(unsigned short, (__bf16)(acc0 * inv));
+        if (per == 2) o[1] = __builtin_bit_cast(unsigned short, (__bf16)(acc1 * inv));
+    } else {
+        float* o = (float*)a.O + off;
+        o[0] = acc0 * inv;
+        if (per == 2) o[1] = acc1 * inv;
+    }
 }
 
 }  // namespace
@@ -468,7 +544,8 @@ AttnPlan plan_attention(const ot_attn_params& p) {
     const int g = p.q_heads / p.kv_heads;
     int base, tile;
     if (p.dtype == OT_BF16) {
-        pl.row_blocks = (g * p.n + 63) / 64;
+        const int rows_wg = g * p.n > 64 ? 128 : 64;       // wide variant when one KV head has more than 64 rows
+        pl.row_blocks = (g * p.n + rows_wg - 1) / rows_wg;
         base = p.batch * p.kv_heads * pl.row_blocks;
         tile = 64;
     } else {
@@ -509,15 +586,25 @@ int launch_tree_attention(const ot_attn_params& p, const AttnPlan& plan, const v
         a.qs[i] = p.q_strides[i]; a.kps[i] = p.kp_strides[i]; a.vps[i] = p.vp_strides[i];
         a.kts[i] = p.kt_strides[i]; a.vts[i] = p.vt_strides[i]; a.os[i] = p.o_strides[i];
     }
+    a.row_blocks = plan.row_blocks;
     if (p.dtype == OT_BF16) {
-        const dim3 grid(plan.splits, plan.row_blocks, p.batch * p.kv_heads);
-        if (ev0 || ev1) {
-            if (p.head_dim == 128) hipExtLaunchKernelGGL(attn_mfma_kernel<128>, grid, dim3(256), 0, s, ev0, ev1, 0, a);
-            else                   hipExtLaunchKernelGGL(attn_mfma_kernel<64>, grid, dim3(256), 0, s, ev0, ev1, 0, a);
-        } else {
-            if (p.head_dim == 128) hipLaunchKernelGGL(attn_mfma_kernel<128>, grid, dim3(256), 0, s, a);
-            else                   hipLaunchKernelGGL(attn_mfma_kernel<64>, grid, dim3(256), 0, s, a);
-        }
+        const bool wide = a.g * p.n > 64;
+        const long long units = (long long)p.batch * p.kv_heads * plan.splits;
+        const long long wgs = (units + 7) / 8 * 8 * plan.row_blocks;
+        if (wgs > 0x7fffffffLL) return OT_ERR_UNSUPPORTED;
+        const dim3 grid((unsigned)wgs);
+#define OT_ATTN_LAUNCH(DD, WW)                                                                             \
+    do {                                                                                                   \
+        const size_t lds = 2 * (64 * (DD + 8) / 2 + 32 * (DD + 16)) * sizeof(unsigned int);                \
+        if (lds > 64 * 1024)                                                                               \
+            OT_HIP_CHECK(hipFuncSetAttribute((const void*)attn_mfma_kernel<DD, WW>,                        \
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));       \
+        if (ev0 || ev1) hipExtLaunchKernelGGL((attn_mfma_kernel<DD, WW>), grid, dim3(256), lds, s, ev0, ev1, 0, a); \
+        else hipLaunchKernelGGL((attn_mfma_kernel<DD, WW>), grid, dim3(256), lds, s, a);                   \
+    } while (0)
+        if (p.head_dim == 128) { if (wide) OT_ATTN_LAUNCH(128, true); else OT_ATTN_LAUNCH(128, false); }
+        else                   { if (wide) OT_ATTN_LAUNCH(64, true); else OT_ATTN_LAUNCH(64, false); }
+#undef OT_ATTN_LAUNCH
     } else {
         const dim3 grid(plan.splits, plan.row_blocks, p.batch * p.q_heads);
         if (ev0 || ev1) {
@@ -531,7 +618,7 @@ int launch_tree_attention(const ot_attn_params& p, const AttnPlan& plan, const v
     OT_HIP_CHECK(hipGetLastError());
     if (plan.splits > 1) {
         const long long rows = (long long)p.batch * p.q_heads * p.n;
-        hipLaunchKernelGGL(attn_combine_kernel, dim3((unsigned)rows), dim3(128), 0, s, a);
+        hipLaunchKernelGGL(attn_combine_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, a);
         OT_HIP_CHECK(hipGetLastError());
     }
     return OT_OK;
@@ -557,6 +644,7 @@ static int validate_attn(const ot_attn_params* p) {
         for (int i = 0; i < 3; ++i)
             if (st[t][i] < 0 || st[t][i] % vec) return OT_ERR_INVALID_ARG;
         if (st[t][2] < p->head_dim) return OT_ERR_INVALID_ARG;
+        if (st[t][2] > (1 << 22)) return OT_ERR_UNSUPPORTED;    // 64 rows of a tile are addressed with 32-bit offsets
     }
     return OT_OK;
 }
