@@ -17,11 +17,11 @@
 //   O^T += V^T P^T  same instruction, B = P straight from the S^T accumulators (the key order
 //                 inside a 16-key slab is whatever the accumulator layout gives; V is read in
 //                 the same order), A = V gathered from LDS.
-// K/V tiles are fetched 16 bytes per lane into registers one tile ahead and staged through LDS.
-// K sits row-major (16-byte row padding keeps the 16-byte operand reads conflict-free).  V is the
-// transposed operand: it is stored as dwords that pair the SAME column of two adjacent keys
-// (built with one DPP exchange between neighbouring lanes and byte permutes), so that the eight
-// keys a lane needs for one column are four dword reads, conflict-free across the wavefront.
+// K/V tiles are fetched 16 bytes per lane into registers one tile ahead and staged through LDS,
+// both row-major with a few bytes of row padding (conflict-free operand reads).  V is the
+// transposed operand (a lane needs 8 keys of ONE column): it is read with the gfx950 LDS transpose
+// load ds_read_b64_tr_b16, which lets 16 lanes read four 32-byte row segments and hands lane i the
+// i-th column of that 4x16 block -- two such loads per MFMA operand, no data shuffling on the way in.
 // The ancestor mask is applied as a bit test on tree tiles only; prefix tiles only mask the tail.
 //
 // f32 path (attn_f32_kernel): plain fp32 FMA arithmetic, 16 query rows x 32-key tiles.
@@ -36,6 +36,8 @@ constexpr float kLog2e = 1.4426950408889634f;
 constexpr int kMaxSplits = 32;
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 struct AttnKArgs {
@@ -85,14 +87,14 @@ template <int D, bool WIDE>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(OT_ATTN_WPE, OT_ATTN_WPE))) void attn_mfma_kernel(const AttnKArgs a) {
     constexpr int TK = 64;                 // keys per tile
     constexpr int KPAD = D + 8;            // bf16 elements per K row in LDS
-    constexpr int VDP = D + 16;            // dwords per key-pair row of V in LDS (2 VDP % 64 == 32)
+    constexpr int VPAD = D + 16;           // bf16 elements per V row in LDS
     constexpr int SLABS = D / 16;          // 16-wide d slabs of the QK^T contraction
     constexpr int DB = D / 32;             // 32-wide d blocks of O^T
     constexpr int CH = TK * D / 8 / 256;   // 16-byte chunks per thread per tile (K or V)
     constexpr int NKB = WIDE ? 2 : 1;      // 32-key blocks per wavefront per tile
     constexpr int ROWS = WIDE ? 128 : 64;  // packed query rows per workgroup
 
-    constexpr int BUF = TK * KPAD / 2 + (TK / 2) * VDP;   // dwords of one staged tile (K then V)
+    constexpr int BUF = TK * KPAD / 2 + TK * VPAD / 2;    // dwords of one staged tile (K then V)
     extern __shared__ __attribute__((aligned(16))) unsigned int s_buf[];   // two tiles: [2][BUF]
     static_assert(sizeof(unsigned int) * 2 * BUF >= 2 * 64 * (DB * 16 + 2) * 4, "merge buffer fits");
 
@@ -139,6 +141,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(OT_ATTN_WPE
     const unsigned short* kt = (const unsigned short*)a.Kt + (long long)b * a.kts[0] + (long long)hk * a.kts[1];
     const unsigned short* vt = (const unsigned short*)a.Vt + (long long)b * a.vts[0] + (long long)hk * a.vts[1];
 
+    // transpose-load addressing: key row and first column this lane points at inside a 4-key x 32-column block
+    const int tr_j = (lane & 15) >> 2, tr_c = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
     const float c = a.scale_log2;          // scores are kept raw; p = 2^(c s - c m)
     float m_run = -INFINITY, l_run = 0.f;
     f32x16 oacc[DB];
@@ -150,9 +154,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(OT_ATTN_WPE
     // which 16-byte chunks of a tile this thread moves: chunk cc is KSTEP keys below chunk cc-1
     constexpr int KSTEP = 256 / (D / 8);
     const int kkey0 = tid / (D / 8), kcol = (tid % (D / 8)) * 8;
-    // V: neighbouring lanes fetch the same 8 columns of two adjacent keys
-    const int vodd = tid & 1;
-    const int vkey0 = 2 * ((tid >> 1) / (D / 8)) + vodd, vcol = ((tid >> 1) % (D / 8)) * 8;
+    const int vkey0 = kkey0, vcol = kcol;
     u32x4 kreg[CH], vreg[CH];
     auto fetch = [&](int t) {
         const bool tree = t >= ptiles;
@@ -183,27 +185,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(OT_ATTN_WPE
 
     auto stage = [&](int buf) {
         unsigned short* const s_k = (unsigned short*)(s_buf + buf * BUF);
-        unsigned int* const s_v = s_buf + buf * BUF + TK * KPAD / 2;
+        unsigned short* const s_v = s_k + TK * KPAD;
 #pragma unroll
         for (int cc = 0; cc < CH; ++cc) {
             *(u32x4*)(s_k + (kkey0 + cc * KSTEP) * KPAD + kcol) = kreg[cc];
-            // pair the columns of keys 2kp (even lane) and 2kp+1 (odd lane): the even lane builds
-            // columns vcol..vcol+3, the odd lane vcol+4..vcol+7
-            const int odd = vodd;
-            const int kpi = (vkey0 >> 1) + cc * (KSTEP / 2);
-            const u32x4 mine = vreg[cc];
-            const unsigned give0 = odd ? mine.x : mine.z, give1 = odd ? mine.y : mine.w;
-            const unsigned got0 = (unsigned)dpp_i<DPP_QUAD_XOR1>(0, (int)give0);
-            const unsigned got1 = (unsigned)dpp_i<DPP_QUAD_XOR1>(0, (int)give1);
-            const unsigned own0 = odd ? mine.z : mine.x, own1 = odd ? mine.w : mine.y;
-            const unsigned ev0 = odd ? got0 : own0, od0 = odd ? own0 : got0;     // even key / odd key dwords
-            const unsigned ev1 = odd ? got1 : own1, od1 = odd ? own1 : got1;
-            u32x4 out;
-            out.x = __builtin_amdgcn_perm(od0, ev0, 0x05040100u);   // column +0: lo16(even) | lo16(odd) << 16
-            out.y = __builtin_amdgcn_perm(od0, ev0, 0x07060302u);   // column +1: hi16(even) | hi16(odd) << 16
-            out.z = __builtin_amdgcn_perm(od1, ev1, 0x05040100u);
-            out.w = __builtin_amdgcn_perm(od1, ev1, 0x07060302u);
-            *(u32x4*)(s_v + kpi * VDP + vcol + 4 * odd) = out;
+            *(u32x4*)(s_v + (vkey0 + cc * KSTEP) * VPAD + vcol) = vreg[cc];
         }
     };
 
@@ -214,7 +200,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(OT_ATTN_WPE
     for (int t = t0; t < t1; ++t) {
         const int cur = (t - t0) & 1;
         const unsigned short* const s_k = (const unsigned short*)(s_buf + cur * BUF);
-        const unsigned int* const s_v = s_buf + cur * BUF + TK * KPAD / 2;
+        const unsigned short* const s_v = s_k + TK * KPAD;
         if (t + 1 < t1) fetch(t + 1);
 
         const bool tree = t >= ptiles;
@@ -275,11 +261,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(OT_ATTN_WPE
             for (int u = 0; u < 2; ++u) {
 #pragma unroll
                 for (int d = 0; d < DB; ++d) {
-                    // keys 32kbi+16u+4h+{0..3} and +8: key pairs kp0, kp0+1, kp0+4, kp0+5 of column 32d+l32
-                    const int kp0 = 16 * kbi + 8 * u + 2 * h;
-                    const unsigned int* vcolp = s_v + kp0 * VDP + 32 * d + l32;
-                    u32x4 vw;
-                    vw.x = vcolp[0]; vw.y = vcolp[VDP]; vw.z = vcolp[4 * VDP]; vw.w = vcolp[5 * VDP];
+                    // this lane needs column 32d+l32 of keys 32kbi+16u+4h+{0..3} and of the same +8.
+                    // Transpose load: lanes 4j..4j+3 of a 16-lane group address the 32-byte segment
+                    // [key j][16 columns]; lane i of the group receives column i of the 4 keys.
+                    const unsigned short* seg = s_v + (32 * kbi + 16 * u + 4 * h + tr_j) * VPAD + 32 * d + tr_c;
+                    const s16x4 lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)seg);
+                    const s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(seg + 8 * VPAD));
+                    const s16x8 vw = __builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
                     oacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vw), pf[u], oacc[d], 0, 0, 0);
                 }
             }
@@ -595,7 +583,7 @@ int launch_tree_attention(const ot_attn_params& p, const AttnPlan& plan, const v
         const dim3 grid((unsigned)wgs);
 #define OT_ATTN_LAUNCH(DD, WW)                                                                             \
     do {                                                                                                   \
-        const size_t lds = 2 * (64 * (DD + 8) / 2 + 32 * (DD + 16)) * sizeof(unsigned int);                \
+        const size_t lds = 2 * (64 * (DD + 8) / 2 + 64 * (DD + 16) / 2) * sizeof(unsigned int);            \
         if (lds > 64 * 1024)                                                                               \
             OT_HIP_CHECK(hipFuncSetAttribute((const void*)attn_mfma_kernel<DD, WW>,                        \
                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));       \
