@@ -17,11 +17,15 @@
 //   O^T += V^T P^T  same instruction, B = P straight from the S^T accumulators (the key order
 //                 inside a 16-key slab is whatever the accumulator layout gives; V is read in
 //                 the same order), A = V gathered from LDS.
-// K/V tiles are fetched 16 bytes per lane into registers one tile ahead and staged through LDS,
-// both row-major with a few bytes of row padding (conflict-free operand reads).  V is the
-// transposed operand (a lane needs 8 keys of ONE column): it is read with the gfx950 LDS transpose
-// load ds_read_b64_tr_b16, which lets 16 lanes read four 32-byte row segments and hands lane i the
-// i-th column of that 4x16 block -- two such loads per MFMA operand, no data shuffling on the way in.
+// K/V tiles go from global memory straight into LDS (global_load_lds_dwordx4: 16 bytes per lane, no
+// register staging), one tile ahead of the computation, into the other half of a double buffer.  A
+// wavefront's 64 lanes land on 1 KB of consecutive LDS, so rows are unpadded and bank conflicts are
+// avoided by an XOR swizzle instead: lane -> global chunk is chosen such that 16-byte chunk c of key
+// row r sits at chunk position c ^ (r mod 16) (K), and 32-byte segment g of row r at g ^ (r mod 8) (V).
+// Tiles that are not full (prefix tail, tree tiles) take a register path with zero fill into the same
+// layout.  V is the transposed operand (a lane needs 8 keys of ONE column): it is read with the gfx950
+// LDS transpose load ds_read_b64_tr_b16, which lets 16 lanes read four 32-byte row segments and hands
+// lane i the i-th column of that 4x16 block -- two such loads per MFMA operand.
 // The ancestor mask is applied as a bit test on tree tiles only; prefix tiles only mask the tail.
 //
 // f32 path (attn_f32_kernel): plain fp32 FMA arithmetic, 16 query rows x 32-key tiles.
@@ -86,15 +90,15 @@ __device__ __forceinline__ void split_range(int T, int S, int s, int& t0, int& t
 template <int D, bool WIDE>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(OT_ATTN_WPE, OT_ATTN_WPE))) void attn_mfma_kernel(const AttnKArgs a) {
     constexpr int TK = 64;                 // keys per tile
-    constexpr int KPAD = D + 8;            // bf16 elements per K row in LDS
-    constexpr int VPAD = D + 16;           // bf16 elements per V row in LDS
+    constexpr int CPR = D / 8;             // 16-byte chunks per row
+    constexpr int SPR = D / 16;            // 32-byte segments per row
     constexpr int SLABS = D / 16;          // 16-wide d slabs of the QK^T contraction
     constexpr int DB = D / 32;             // 32-wide d blocks of O^T
     constexpr int CH = TK * D / 8 / 256;   // 16-byte chunks per thread per tile (K or V)
     constexpr int NKB = WIDE ? 2 : 1;      // 32-key blocks per wavefront per tile
     constexpr int ROWS = WIDE ? 128 : 64;  // packed query rows per workgroup
 
-    constexpr int BUF = TK * KPAD / 2 + TK * VPAD / 2;    // dwords of one staged tile (K then V)
+    constexpr int BUF = TK * D;            // dwords of one staged tile: K [64][D] bf16, then V [64][D] bf16
     extern __shared__ __attribute__((aligned(16))) unsigned int s_buf[];   // two tiles: [2][BUF]
     static_assert(sizeof(unsigned int) * 2 * BUF >= 2 * 64 * (DB * 16 + 2) * 4, "merge buffer fits");
 
@@ -142,7 +146,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(OT_ATTN_WPE
     const unsigned short* vt = (const unsigned short*)a.Vt + (long long)b * a.vts[0] + (long long)hk * a.vts[1];
 
     // transpose-load addressing: key row and first column this lane points at inside a 4-key x 32-column block
-    const int tr_j = (lane & 15) >> 2, tr_c = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+    const int tr_j = (lane & 15) >> 2, tr_q = 4 * (lane & 3);
+    // swizzle terms of this lane's operand reads: K chunk (2s + h) of row l32 -> position (2s) ^ kx;
+    // V segment (2d + g1) of row 4h + tr_j (mod 8) -> position (2d) ^ vx
+    const int kx = h ^ (l32 & (CPR - 1));
+    const int vx = ((lane >> 4) & 1) ^ ((4 * h + tr_j) & (SPR - 1));
     const float c = a.scale_log2;          // scores are kept raw; p = 2^(c s - c m)
     float m_run = -INFINITY, l_run = 0.f;
     f32x16 oacc[DB];
@@ -151,57 +159,77 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(OT_ATTN_WPE
 #pragma unroll
         for (int v = 0; v < 16; ++v) oacc[d][v] = 0.f;
 
-    // which 16-byte chunks of a tile this thread moves: chunk cc is KSTEP keys below chunk cc-1
-    constexpr int KSTEP = 256 / (D / 8);
-    const int kkey0 = tid / (D / 8), kcol = (tid % (D / 8)) * 8;
-    const int vkey0 = kkey0, vcol = kcol;
-    u32x4 kreg[CH], vreg[CH];
-    auto fetch = [&](int t) {
+    // LDS slot sigma = cc * 256 + tid (16 bytes each) holds key row sigma / CPR, chunk position sigma % CPR;
+    // the chunk stored there is the one the swizzle maps to that position.  KSTEP rows separate cc and cc+1,
+    // a multiple of 16, so the swizzle term is the same for every cc.
+    constexpr int KSTEP = 256 / CPR;
+    const int kkey0 = tid / CPR, pc = tid % CPR;
+    const int kcol = (pc ^ (kkey0 & (CPR - 1))) * 8;                                         // K: chunk c = pc ^ (r % 16)
+    const int vcol = (2 * ((pc >> 1) ^ (kkey0 & (SPR - 1))) + (pc & 1)) * 8;                 // V: segment g = (pc/2) ^ (r % 8)
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    // a full tile: asynchronous copy, global -> LDS
+    auto copy_async = [&](int t, int buf) -> bool {
+        const bool tree = t >= ptiles;
+        const int key0 = tree ? (t - ptiles) * TK : t * TK;
+        const int kend = tree ? n : L;
+        if (key0 + TK > kend) return false;
+        const int ks = (int)(tree ? a.kts[2] : a.kps[2]);
+        const int vs = (int)(tree ? a.vts[2] : a.vps[2]);
+        const unsigned short* kbase = (tree ? kt : kp) + (long long)key0 * ks;     // wave-uniform
+        const unsigned short* vbase = (tree ? vt : vp) + (long long)key0 * vs;
+        unsigned int* const lk = s_buf + buf * BUF;
+        unsigned int* const lv = lk + TK * D / 2;
+#pragma unroll
+        for (int cc = 0; cc < CH; ++cc) {
+            const int slot0 = cc * 256 + wave_u * 64;      // first 16-byte slot this wavefront fills
+            __builtin_amdgcn_global_load_lds(
+                (const __attribute__((address_space(1))) void*)(kbase + (kkey0 + cc * KSTEP) * ks + kcol),
+                (__attribute__((address_space(3))) void*)(lk + slot0 * 4), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(
+                (const __attribute__((address_space(1))) void*)(vbase + (kkey0 + cc * KSTEP) * vs + vcol),
+                (__attribute__((address_space(3))) void*)(lv + slot0 * 4), 16, 0, 0);
+        }
+        return true;
+    };
+    // a partial tile: through registers, rows beyond the end are zero
+    auto copy_sync = [&](int t, int buf) {
         const bool tree = t >= ptiles;
         const int key0 = tree ? (t - ptiles) * TK : t * TK;
         const int kend = tree ? n : L;
         const int ks = (int)(tree ? a.kts[2] : a.kps[2]);
         const int vs = (int)(tree ? a.vts[2] : a.vps[2]);
-        const unsigned short* kbase = (tree ? kt : kp) + (long long)key0 * ks;     // wave-uniform
+        const unsigned short* kbase = (tree ? kt : kp) + (long long)key0 * ks;
         const unsigned short* vbase = (tree ? vt : vp) + (long long)key0 * vs;
-        const int koff = kkey0 * ks + kcol, voff = vkey0 * vs + vcol;
-        if (key0 + TK <= kend) {
-#pragma unroll
-            for (int cc = 0; cc < CH; ++cc) {
-                kreg[cc] = *(const u32x4*)(kbase + koff + cc * KSTEP * ks);
-                vreg[cc] = *(const u32x4*)(vbase + voff + cc * KSTEP * vs);
-            }
-        } else {
-#pragma unroll
-            for (int cc = 0; cc < CH; ++cc) {
-                u32x4 kw = {0u, 0u, 0u, 0u}, vw = {0u, 0u, 0u, 0u};
-                if (key0 + kkey0 + cc * KSTEP < kend) kw = *(const u32x4*)(kbase + koff + cc * KSTEP * ks);
-                if (key0 + vkey0 + cc * KSTEP < kend) vw = *(const u32x4*)(vbase + voff + cc * KSTEP * vs);
-                kreg[cc] = kw;
-                vreg[cc] = vw;
-            }
-        }
-    };
-
-    auto stage = [&](int buf) {
-        unsigned short* const s_k = (unsigned short*)(s_buf + buf * BUF);
-        unsigned short* const s_v = s_k + TK * KPAD;
+        unsigned int* const lk = s_buf + buf * BUF;
+        unsigned int* const lv = lk + TK * D / 2;
+        u32x4 kw[CH], vw[CH];
 #pragma unroll
         for (int cc = 0; cc < CH; ++cc) {
-            *(u32x4*)(s_k + (kkey0 + cc * KSTEP) * KPAD + kcol) = kreg[cc];
-            *(u32x4*)(s_v + (vkey0 + cc * KSTEP) * VPAD + vcol) = vreg[cc];
+            kw[cc] = (u32x4){0u, 0u, 0u, 0u};
+            vw[cc] = (u32x4){0u, 0u, 0u, 0u};
+            if (key0 + kkey0 + cc * KSTEP < kend) {
+                kw[cc] = *(const u32x4*)(kbase + (kkey0 + cc * KSTEP) * ks + kcol);
+                vw[cc] = *(const u32x4*)(vbase + (kkey0 + cc * KSTEP) * vs + vcol);
+            }
+        }
+#pragma unroll
+        for (int cc = 0; cc < CH; ++cc) {
+            *(u32x4*)(lk + (cc * 256 + tid) * 4) = kw[cc];
+            *(u32x4*)(lv + (cc * 256 + tid) * 4) = vw[cc];
         }
     };
 
     // tile t is computed from LDS buffer (t - t0) & 1 while tile t+1 is in flight from memory; it is
     // staged into the other buffer after the computation, so one barrier per tile suffices
-    if (t0 < t1) { fetch(t0); stage(0); }
+    if (t0 < t1 && !copy_async(t0, 0)) copy_sync(t0, 0);
+    __builtin_amdgcn_s_waitcnt(0);          // my copies have landed
     __syncthreads();
     for (int t = t0; t < t1; ++t) {
         const int cur = (t - t0) & 1;
         const unsigned short* const s_k = (const unsigned short*)(s_buf + cur * BUF);
-        const unsigned short* const s_v = s_k + TK * KPAD;
-        if (t + 1 < t1) fetch(t + 1);
+        const unsigned short* const s_v = s_k + TK * D;
+        bool in_flight = false;
+        if (t + 1 < t1) in_flight = copy_async(t + 1, cur ^ 1);
 
         const bool tree = t >= ptiles;
         const int key0 = tree ? (t - ptiles) * TK : t * TK;
@@ -216,7 +244,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(OT_ATTN_WPE
             for (int v = 0; v < 16; ++v) sacc[v] = 0.f;
 #pragma unroll
             for (int s = 0; s < SLABS; ++s) {
-                const u32x4 kw = *(const u32x4*)(s_k + (32 * kbi + l32) * KPAD + 16 * s + 8 * h);
+                const u32x4 kw = *(const u32x4*)(s_k + (32 * kbi + l32) * D + (((2 * s) ^ kx) << 3));
                 sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kw), qf[s], sacc, 0, 0, 0);
             }
             // visibility; accumulator element v is key 32 kbi + 8 (v/4) + 4 h + v%4
@@ -264,15 +292,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(OT_ATTN_WPE
                     // this lane needs column 32d+l32 of keys 32kbi+16u+4h+{0..3} and of the same +8.
                     // Transpose load: lanes 4j..4j+3 of a 16-lane group address the 32-byte segment
                     // [key j][16 columns]; lane i of the group receives column i of the 4 keys.
-                    const unsigned short* seg = s_v + (32 * kbi + 16 * u + 4 * h + tr_j) * VPAD + 32 * d + tr_c;
+                    const unsigned short* seg = s_v + (32 * kbi + 16 * u + 4 * h + tr_j) * D + (((2 * d) ^ vx) << 4) + tr_q;
                     const s16x4 lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)seg);
-                    const s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(seg + 8 * VPAD));
+                    const s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(seg + 8 * D));
                     const s16x8 vw = __builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
                     oacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vw), pf[u], oacc[d], 0, 0, 0);
                 }
             }
         }
-        if (t + 1 < t1) stage(cur ^ 1);
+        if (t + 1 < t1 && !in_flight) copy_sync(t + 1, cur ^ 1);
+        __builtin_amdgcn_s_waitcnt(0);      // my copies have landed
         __syncthreads();
     }
 
@@ -583,7 +612,7 @@ int launch_tree_attention(const ot_attn_params& p, const AttnPlan& plan, const v
         const dim3 grid((unsigned)wgs);
 #define OT_ATTN_LAUNCH(DD, WW)                                                                             \
     do {                                                                                                   \
-        const size_t lds = 2 * (64 * (DD + 8) / 2 + 64 * (DD + 16) / 2) * sizeof(unsigned int);            \
+        const size_t lds = 2 * 64 * DD * sizeof(unsigned int);                                             \
         if (lds > 64 * 1024)                                                                               \
             OT_HIP_CHECK(hipFuncSetAttribute((const void*)attn_mfma_kernel<DD, WW>,                        \
                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));       \
