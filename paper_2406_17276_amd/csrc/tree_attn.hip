@@ -182,12 +182,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(OT_ATTN_WPE
 #pragma unroll
         for (int cc = 0; cc < CH; ++cc) {
             const int slot0 = cc * 256 + wave_u * 64;      // first 16-byte slot this wavefront fills
-            __builtin_amdgcn_global_load_lds(
-                (const __attribute__((address_space(1))) void*)(kbase + (kkey0 + cc * KSTEP) * ks + kcol),
-                (__attribute__((address_space(3))) void*)(lk + slot0 * 4), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds(
-                (const __attribute__((address_space(1))) void*)(vbase + (kkey0 + cc * KSTEP) * vs + vcol),
-                (__attribute__((address_space(3))) void*)(lv + slot0 * 4), 16, 0, 0);
+            // Written as assembly on purpose: with the builtin the compiler, unable to prove that this
+            // copy targets the OTHER buffer, waits for it (vmcnt) before the next LDS read of the
+            // current one and serialises copy and computation.  Completion is awaited explicitly
+            // (s_waitcnt vmcnt(0) before the barrier that publishes the buffer).
+            const unsigned lds_k = (unsigned)(size_t)(__attribute__((address_space(3))) void*)(lk + slot0 * 4);
+            const unsigned lds_v = (unsigned)(size_t)(__attribute__((address_space(3))) void*)(lv + slot0 * 4);
+            const unsigned short* gk = kbase + (kkey0 + cc * KSTEP) * ks + kcol;
+            const unsigned short* gv = vbase + (kkey0 + cc * KSTEP) * vs + vcol;
+            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_k), "v"(gk) : "m0");
+            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_v), "v"(gv) : "m0");
         }
         return true;
     };
@@ -240,13 +244,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(OT_ATTN_WPE
         for (int j = 0; j < NKB; ++j) {
             const int kbi = WIDE ? j : kh;
             f32x16 sacc;
+            u32x4 kfr[SLABS];
 #pragma unroll
             for (int v = 0; v < 16; ++v) sacc[v] = 0.f;
 #pragma unroll
-            for (int s = 0; s < SLABS; ++s) {
-                const u32x4 kw = *(const u32x4*)(s_k + (32 * kbi + l32) * D + (((2 * s) ^ kx) << 3));
-                sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kw), qf[s], sacc, 0, 0, 0);
-            }
+            for (int s = 0; s < SLABS; ++s) kfr[s] = *(const u32x4*)(s_k + (32 * kbi + l32) * D + (((2 * s) ^ kx) << 3));
+#pragma unroll
+            for (int s = 0; s < SLABS; ++s)
+                sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kfr[s]), qf[s], sacc, 0, 0, 0);
             // visibility; accumulator element v is key 32 kbi + 8 (v/4) + 4 h + v%4
             if (tree || key0 + TK > kend) {
 #pragma unroll
