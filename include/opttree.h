@@ -153,6 +153,17 @@ typedef struct ot_attn_params {
 
 OT_API size_t ot_attn_workspace_bytes(const ot_attn_params* p);     /* 0 if p is invalid */
 
+/* The first OT_ATTN_SYNC_BYTES bytes of an attention workspace hold the ticket counters with which the
+ * workgroups that share output rows (the key ranges a long prefix is split into) find out which of them
+ * finishes last and merges the partial results.  They must be zero when ot_tree_verify_attention is
+ * called and every completed call leaves them zero, so a workspace is prepared ONCE after it has been
+ * allocated (and again only if something else wrote to it, or a launch was aborted):
+ * ot_attn_workspace_prepare zeroes them with a small kernel on `hip_stream` (capturable in a graph);
+ * a caller may equally clear them itself.  Returns OT_OK, OT_ERR_INVALID_ARG (null or misaligned
+ * workspace), OT_ERR_WORKSPACE_TOO_SMALL or OT_ERR_HIP. */
+#define OT_ATTN_SYNC_BYTES 4096
+OT_API int ot_attn_workspace_prepare(void* workspace, size_t workspace_bytes, void* hip_stream);
+
 OT_API int ot_tree_verify_attention(const ot_attn_params* p,
                              const void* Q,                          /* [batch][q_heads][n][head_dim] */
                              const void* K_prefix, const void* V_prefix, /* [batch][kv_heads][max_prefix][head_dim]; may be NULL if max_prefix == 0 */
@@ -163,7 +174,7 @@ OT_API int ot_tree_verify_attention(const ot_attn_params* p,
                              void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* Measurement aid: ot_tree_verify_attention that also records the begin and the end of its
- * K/V-streaming kernel (Algorithm 2's tree-masked attention, without the split merge) in two
+ * K/V-streaming kernel (Algorithm 2's tree-masked attention; for bf16 it includes the split merge) in two
  * caller-created hipEvent_t (void*, either may be NULL).  Not capturable in a graph. */
 OT_API int ot_tree_verify_attention_timed(const ot_attn_params* p,
                              const void* Q, const void* K_prefix, const void* V_prefix,

@@ -76,6 +76,8 @@ def lib():
                                        C.POINTER(TreeOut), C.c_void_p]
         L.ot_attn_workspace_bytes.restype = C.c_size_t
         L.ot_attn_workspace_bytes.argtypes = [C.POINTER(AttnParams)]
+        L.ot_attn_workspace_prepare.restype = C.c_int
+        L.ot_attn_workspace_prepare.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p]
         L.ot_tree_verify_attention.restype = C.c_int
         L.ot_tree_verify_attention.argtypes = [C.POINTER(AttnParams)] + [C.c_void_p] * 9 + [C.c_size_t, C.c_void_p]
         L.ot_tree_verify_attention_timed.restype = C.c_int
@@ -217,18 +219,31 @@ def attn_workspace_bytes(p: AttnParams) -> int:
     return int(lib().ot_attn_workspace_bytes(C.byref(p)))
 
 
+def attn_workspace(p: AttnParams, device):
+    """A workspace for ot_tree_verify_attention, already prepared (ot_attn_workspace_prepare on the
+    current stream): its ticket counters are zero, and every completed call leaves them zero."""
+    import torch
+    need = attn_workspace_bytes(p)
+    if need == 0:
+        raise OptTreeError(-2, "ot_attn_workspace_bytes")
+    ws = torch.empty(need, dtype=torch.uint8, device=device)
+    _check(lib().ot_attn_workspace_prepare(ws.data_ptr(), ws.numel(), _stream()), "ot_attn_workspace_prepare")
+    torch.cuda.current_stream().synchronize()      # the workspace may be used on any stream afterwards
+    return ws
+
+
 def tree_verify_attention(Q, K_prefix, V_prefix, K_tree, V_tree, prefix_len, mask, out=None, workspace=None,
                           softmax_scale: float = 0.0):
     """ot_tree_verify_attention on the current stream.  Q [B,Hq,n,D]; K/V_prefix [B,Hkv,Lmax,D] (or None);
-    K/V_tree [B,Hkv,n,D]; prefix_len int32 [B]; mask int64 [B,n,W]."""
+    K/V_tree [B,Hkv,n,D]; prefix_len int32 [B]; mask int64 [B,n,W].  A caller-supplied workspace must be a
+    prepared one (attn_workspace)."""
     import torch
     p = attn_params(Q, K_prefix, V_prefix, K_tree, V_tree, softmax_scale=softmax_scale)
     if out is None:
         out = torch.empty_like(Q)
     p.o_strides = (C.c_int64 * 3)(out.stride(0), out.stride(1), out.stride(2))
-    need = attn_workspace_bytes(p)
-    if workspace is None and need:
-        workspace = torch.empty(need, dtype=torch.uint8, device=Q.device)
+    if workspace is None:
+        workspace = attn_workspace(p, Q.device)
     ptr = lambda t: None if t is None else t.data_ptr()
     _check(lib().ot_tree_verify_attention(
         C.byref(p), ptr(Q), ptr(K_prefix), ptr(V_prefix), ptr(K_tree), ptr(V_tree), ptr(prefix_len), ptr(mask),
@@ -271,10 +286,7 @@ class PreparedAttention:
         self.keep = (Q, K_prefix, V_prefix, K_tree, V_tree, prefix_len, mask)
         self.p = attn_params(Q, K_prefix, V_prefix, K_tree, V_tree, softmax_scale=softmax_scale)
         self.out = torch.empty_like(Q)
-        need = attn_workspace_bytes(self.p)
-        if need == 0:
-            raise OptTreeError(-2, "ot_attn_workspace_bytes")
-        self.ws = torch.empty(need, dtype=torch.uint8, device=Q.device)
+        self.ws = attn_workspace(self.p, Q.device)
         ptr = lambda t: None if t is None else t.data_ptr()
         self._args = (C.byref(self.p), ptr(Q), ptr(K_prefix), ptr(V_prefix), ptr(K_tree), ptr(V_tree),
                       ptr(prefix_len), ptr(mask), ptr(self.out), self.ws.data_ptr(), self.ws.numel())

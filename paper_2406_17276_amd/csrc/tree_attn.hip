@@ -49,8 +49,9 @@ struct AttnKArgs {
     const int32_t* prefix_len;
     const uint64_t* mask;
     void* O;
-    float* part_o;      // [rows_total][splits][D]
-    float* part_ml;     // [rows_total][splits][2]
+    unsigned int* counters;   // one ticket counter per (sequence, KV head, row block), zero between launches
+    float* part_o;      // per-split partial O   (layout: see the kernel that writes it)
+    float* part_ml;     // per-split (m, l)
     int batch, q_heads, kv_heads, g, n, D, max_prefix, splits, W, dtype, row_blocks;
     float scale_log2;   // softmax scale * log2(e)
     long long qs[3], kps[3], vps[3], kts[3], vts[3], os[3];
@@ -79,28 +80,43 @@ __device__ __forceinline__ void split_range(int T, int S, int s, int& t0, int& t
 // ---------------------------------------------------------------------------
 // WIDE = false: 64 packed rows per workgroup, wavefront = (query block of 32 rows) x (half of each
 //                64-key tile); the two halves are merged through LDS at the end.  For few rows.
+//                Three tile buffers: two tiles are in flight while a third is being computed.
 // WIDE = true : 128 packed rows per workgroup, wavefront = 32 rows x the whole tile; staging one
 //                tile in LDS is shared by twice as many MFMAs and nothing is merged at the end.
+//                Two tile buffers, so that two workgroups share a compute unit.
 // Workgroups are numbered so that those which stream the same K/V (the row blocks of one
 // (sequence, KV head, split)) sit on the same XCD, next to each other in its dispatch order, and
 // share that XCD's L2: hardware hands workgroup L to XCD L % 8.
-#ifndef OT_ATTN_WPE
-#define OT_ATTN_WPE 2
+//
+// With more than one split, every workgroup leaves its partial (O, m, l) in the workspace in the
+// accumulator's own register order (coalesced 16-byte stores), then takes a ticket from the counter
+// of its (sequence, KV head, row block); the workgroup that draws the last ticket merges all the
+// partials of those rows and writes O.  Nobody waits for anybody: a workgroup that is not last simply
+// ends.  The counter is reset by the merging workgroup, so it is zero again when the kernel ends.
+#ifndef OT_ATTN_NBUF_NARROW
+#define OT_ATTN_NBUF_NARROW 3
 #endif
 template <int D, bool WIDE>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(OT_ATTN_WPE, OT_ATTN_WPE))) void attn_mfma_kernel(const AttnKArgs a) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_mfma_kernel(const AttnKArgs a) {
     constexpr int TK = 64;                 // keys per tile
     constexpr int CPR = D / 8;             // 16-byte chunks per row
     constexpr int SPR = D / 16;            // 32-byte segments per row
     constexpr int SLABS = D / 16;          // 16-wide d slabs of the QK^T contraction
     constexpr int DB = D / 32;             // 32-wide d blocks of O^T
     constexpr int CH = TK * D / 8 / 256;   // 16-byte chunks per thread per tile (K or V)
+    constexpr int LPT = 2 * CH;            // asynchronous loads per thread per tile
     constexpr int NKB = WIDE ? 2 : 1;      // 32-key blocks per wavefront per tile
     constexpr int ROWS = WIDE ? 128 : 64;  // packed query rows per workgroup
+    constexpr int NQB = ROWS / 32;         // query blocks per workgroup
+    constexpr int NBUF = WIDE ? 2 : OT_ATTN_NBUF_NARROW;
+    constexpr int PD = NBUF - 1;           // tiles requested ahead of the one being computed
+    static_assert(PD >= 1 && PD <= 3 && PD * LPT < 64, "prefetch depth fits the vmcnt counter");
 
     constexpr int BUF = TK * D;            // dwords of one staged tile: K [64][D] bf16, then V [64][D] bf16
-    extern __shared__ __attribute__((aligned(16))) unsigned int s_buf[];   // two tiles: [2][BUF]
-    static_assert(sizeof(unsigned int) * 2 * BUF >= 2 * 64 * (DB * 16 + 2) * 4, "merge buffer fits");
+    extern __shared__ __attribute__((aligned(16))) unsigned int s_buf[];   // [NBUF][BUF]
+    __shared__ int s_last;
+    constexpr int MST = DB * 16 + 2;       // floats per lane in the half-merge scratch
+    static_assert(sizeof(unsigned int) * NBUF * BUF >= 2 * 64 * MST * 4, "merge scratch fits");
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int qb = WIDE ? wave : (wave & 1), kh = WIDE ? 0 : (wave >> 1);
@@ -112,33 +128,32 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(OT_ATTN_WPE
     const int bz = unit / a.splits, split = unit - bz * a.splits;
     const int b = bz / a.kv_heads, hk = bz - b * a.kv_heads;
     const int n = a.n;
-    const int L = clamp_len(a.prefix_len[b], a.max_prefix);
-    const int ptiles = (L + TK - 1) / TK, ttiles = (n + TK - 1) / TK;
-    int t0, t1;
-    split_range(ptiles + ttiles, a.splits, split, t0, t1);
 
-    // this lane's query row
+    // this lane's query row; lanes past the last row work on a copy of it and store nothing
     const int rho = rb * ROWS + qb * 32 + l32;         // packed row inside the KV head
     const bool row_ok = rho < a.g * n;
-    const int hq = hk * a.g + (row_ok ? rho / n : 0);
-    const int node = row_ok ? rho % n : 0;
+    const int rho_c = row_ok ? rho : a.g * n - 1;
+    const int hq = hk * a.g + rho_c / n;
+    const int node = rho_c % n;
 
     // Q fragments: B operand of S^T = K Q^T; lane holds Q[row][16 s + 8 h .. +7]
-    bf16x8 qf[SLABS];
+    u32x4 qw[SLABS];
     {
         const unsigned short* qrow =
             (const unsigned short*)a.Q + (long long)b * a.qs[0] + (long long)hq * a.qs[1] + (long long)node * a.qs[2];
 #pragma unroll
-        for (int s = 0; s < SLABS; ++s) {
-            u32x4 w = {0u, 0u, 0u, 0u};
-            if (row_ok) w = *(const u32x4*)(qrow + 16 * s + 8 * h);
-            qf[s] = __builtin_bit_cast(bf16x8, w);
-        }
+        for (int s = 0; s < SLABS; ++s) qw[s] = *(const u32x4*)(qrow + 16 * s + 8 * h);
     }
     // this lane's ancestor mask row
     uint64_t mrow[4] = {0ull, 0ull, 0ull, 0ull};
-    if (row_ok)
-        for (int w = 0; w < a.W; ++w) mrow[w] = a.mask[((long long)b * n + node) * a.W + w];
+#pragma unroll
+    for (int w = 0; w < 4; ++w)
+        if (w < a.W) mrow[w] = a.mask[((long long)b * n + node) * a.W + w];
+
+    const int L = clamp_len(a.prefix_len[b], a.max_prefix);
+    const int ptiles = (L + TK - 1) / TK, ttiles = (n + TK - 1) / TK;
+    int t0, t1;
+    split_range(ptiles + ttiles, a.splits, split, t0, t1);
 
     const unsigned short* kp = (const unsigned short*)a.Kp + (long long)b * a.kps[0] + (long long)hk * a.kps[1];
     const unsigned short* vp = (const unsigned short*)a.Vp + (long long)b * a.vps[0] + (long long)hk * a.vps[1];
@@ -167,73 +182,62 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(OT_ATTN_WPE
     const int kcol = (pc ^ (kkey0 & (CPR - 1))) * 8;                                         // K: chunk c = pc ^ (r % 16)
     const int vcol = (2 * ((pc >> 1) ^ (kkey0 & (SPR - 1))) + (pc & 1)) * 8;                 // V: segment g = (pc/2) ^ (r % 8)
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
-    // a full tile: asynchronous copy, global -> LDS
-    auto copy_async = [&](int t, int buf) -> bool {
+    // Request tile t: global memory -> LDS buffer `buf`, 16 bytes per lane and instruction, no registers in
+    // between.  Rows past the end of the keys (prefix tail, last tree tile) re-read the last valid row: their
+    // scores are masked below, so their probabilities are exactly zero and the values only need to be finite.
+    // Written as assembly on purpose: the compiler does not track these loads, so it puts no wait between
+    // them and the LDS reads of the tile being computed; completion is awaited explicitly, per tile, with
+    // s_waitcnt vmcnt (loads complete in order) ahead of the barrier that publishes the buffer.
+    auto request_tile = [&](int t, int buf) {
         const bool tree = t >= ptiles;
         const int key0 = tree ? (t - ptiles) * TK : t * TK;
-        const int kend = tree ? n : L;
-        if (key0 + TK > kend) return false;
-        const int ks = (int)(tree ? a.kts[2] : a.kps[2]);
-        const int vs = (int)(tree ? a.vts[2] : a.vps[2]);
-        const unsigned short* kbase = (tree ? kt : kp) + (long long)key0 * ks;     // wave-uniform
-        const unsigned short* vbase = (tree ? vt : vp) + (long long)key0 * vs;
+        const int last = (tree ? n : L) - 1;
+        const long long ks = tree ? a.kts[2] : a.kps[2];
+        const long long vs = tree ? a.vts[2] : a.vps[2];
+        const unsigned short* kbase = tree ? kt : kp;
+        const unsigned short* vbase = tree ? vt : vp;
         unsigned int* const lk = s_buf + buf * BUF;
         unsigned int* const lv = lk + TK * D / 2;
 #pragma unroll
         for (int cc = 0; cc < CH; ++cc) {
             const int slot0 = cc * 256 + wave_u * 64;      // first 16-byte slot this wavefront fills
-            // Written as assembly on purpose: with the builtin the compiler, unable to prove that this
-            // copy targets the OTHER buffer, waits for it (vmcnt) before the next LDS read of the
-            // current one and serialises copy and computation.  Completion is awaited explicitly
-            // (s_waitcnt vmcnt(0) before the barrier that publishes the buffer).
             const unsigned lds_k = (unsigned)(size_t)(__attribute__((address_space(3))) void*)(lk + slot0 * 4);
             const unsigned lds_v = (unsigned)(size_t)(__attribute__((address_space(3))) void*)(lv + slot0 * 4);
-            const unsigned short* gk = kbase + (kkey0 + cc * KSTEP) * ks + kcol;
-            const unsigned short* gv = vbase + (kkey0 + cc * KSTEP) * vs + vcol;
-            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_k), "v"(gk) : "m0");
-            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_v), "v"(gv) : "m0");
-        }
-        return true;
-    };
-    // a partial tile: through registers, rows beyond the end are zero
-    auto copy_sync = [&](int t, int buf) {
-        const bool tree = t >= ptiles;
-        const int key0 = tree ? (t - ptiles) * TK : t * TK;
-        const int kend = tree ? n : L;
-        const int ks = (int)(tree ? a.kts[2] : a.kps[2]);
-        const int vs = (int)(tree ? a.vts[2] : a.vps[2]);
-        const unsigned short* kbase = (tree ? kt : kp) + (long long)key0 * ks;
-        const unsigned short* vbase = (tree ? vt : vp) + (long long)key0 * vs;
-        unsigned int* const lk = s_buf + buf * BUF;
-        unsigned int* const lv = lk + TK * D / 2;
-        u32x4 kw[CH], vw[CH];
-#pragma unroll
-        for (int cc = 0; cc < CH; ++cc) {
-            kw[cc] = (u32x4){0u, 0u, 0u, 0u};
-            vw[cc] = (u32x4){0u, 0u, 0u, 0u};
-            if (key0 + kkey0 + cc * KSTEP < kend) {
-                kw[cc] = *(const u32x4*)(kbase + (kkey0 + cc * KSTEP) * ks + kcol);
-                vw[cc] = *(const u32x4*)(vbase + (kkey0 + cc * KSTEP) * vs + vcol);
-            }
-        }
-#pragma unroll
-        for (int cc = 0; cc < CH; ++cc) {
-            *(u32x4*)(lk + (cc * 256 + tid) * 4) = kw[cc];
-            *(u32x4*)(lv + (cc * 256 + tid) * 4) = vw[cc];
+            int row = key0 + kkey0 + cc * KSTEP;
+            row = row < last ? row : last;
+            const unsigned short* gk = kbase + row * ks + kcol;
+            const unsigned short* gv = vbase + row * vs + vcol;
+            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_k), "v"(gk) : "m0", "memory");
+            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_v), "v"(gv) : "m0", "memory");
         }
     };
 
-    // tile t is computed from LDS buffer (t - t0) & 1 while tile t+1 is in flight from memory; it is
-    // staged into the other buffer after the computation, so one barrier per tile suffices
-    if (t0 < t1 && !copy_async(t0, 0)) copy_sync(t0, 0);
-    __builtin_amdgcn_s_waitcnt(0);          // my copies have landed
-    __syncthreads();
+    // Q and the mask row must have arrived before the first tile request: the compiler waits for its own
+    // loads with a counter that would otherwise also cover the (younger) tile requests.
+#pragma unroll
+    for (int s = 0; s < SLABS; ++s) asm volatile("" : "+v"(qw[s]));
+#pragma unroll
+    for (int w = 0; w < 4; ++w) asm volatile("" : "+v"(mrow[w]));
+    bf16x8 qf[SLABS];
+#pragma unroll
+    for (int s = 0; s < SLABS; ++s) qf[s] = __builtin_bit_cast(bf16x8, qw[s]);
+
+#pragma unroll
+    for (int i = 0; i < PD; ++i)
+        if (t0 + i < t1) request_tile(t0 + i, i);
+    int cur = 0, prev = NBUF - 1;           // buffer of tile t, buffer of tile t - 1 (= of tile t + PD)
     for (int t = t0; t < t1; ++t) {
-        const int cur = (t - t0) & 1;
+        // my requests for tile t have landed (younger ones may still be in flight); after the barrier
+        // everybody's have, and everybody is done reading the buffer of tile t - 1
+        const int ahead = t1 - 1 - t < PD - 1 ? t1 - 1 - t : PD - 1;
+        if (ahead <= 0)      asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        else if (ahead == 1) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(LPT) : "memory");
+        else                 asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(2 * LPT) : "memory");
+        if (t + PD < t1) request_tile(t + PD, prev);
         const unsigned short* const s_k = (const unsigned short*)(s_buf + cur * BUF);
         const unsigned short* const s_v = s_k + TK * D;
-        bool in_flight = false;
-        if (t + 1 < t1) in_flight = copy_async(t + 1, cur ^ 1);
+        prev = cur;
+        cur = cur + 1 == NBUF ? 0 : cur + 1;
 
         const bool tree = t >= ptiles;
         const int key0 = tree ? (t - ptiles) * TK : t * TK;
@@ -305,83 +309,166 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(OT_ATTN_WPE
                 }
             }
         }
-        if (t + 1 < t1 && !in_flight) copy_sync(t + 1, cur ^ 1);
-        __builtin_amdgcn_s_waitcnt(0);      // my copies have landed
-        __syncthreads();
     }
 
     l_run = xhalf_sum(l_run);
-    float mm = m_run, lt = l_run, a1 = 1.f, a2 = 0.f;
-    const float* src = nullptr;
     if (!WIDE) {
-        // merge the two key-half waves of each query block through LDS (tile buffers are free now)
-        float* s_merge = (float*)s_buf;          // [2 qb][64 lanes][DB*16 + 2]
-        constexpr int MST = DB * 16 + 2;
+        // merge the two key-half waves of each query block through LDS (all tiles are consumed)
+        float* s_merge = (float*)s_buf;          // [2 qb][64 lanes][MST]
+        float* mine = s_merge + (qb * 64 + lane) * MST;
+        __syncthreads();
         if (kh == 1) {
-            float* dst = s_merge + (qb * 64 + lane) * MST;
 #pragma unroll
             for (int d = 0; d < DB; ++d)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) dst[d * 16 + v] = oacc[d][v];
-            dst[DB * 16] = m_run;
-            dst[DB * 16 + 1] = l_run;
+                for (int v = 0; v < 16; ++v) mine[d * 16 + v] = oacc[d][v];
+            mine[DB * 16] = m_run;
+            mine[DB * 16 + 1] = l_run;
         }
         __syncthreads();
-        if (kh == 1) return;
-        src = s_merge + (qb * 64 + lane) * MST;
-        const float m2 = src[DB * 16], l2 = src[DB * 16 + 1];
-        mm = fmaxf(m_run, m2);
-        a1 = 0.f;
-        if (mm != -INFINITY) {
-            a1 = __builtin_amdgcn_exp2f((m_run - mm) * c);
-            a2 = __builtin_amdgcn_exp2f((m2 - mm) * c);
+        if (kh == 0) {
+            const float m2 = mine[DB * 16], l2 = mine[DB * 16 + 1];
+            const float mm = fmaxf(m_run, m2);
+            float a1 = 0.f, a2 = 0.f;
+            if (mm != -INFINITY) {
+                a1 = __builtin_amdgcn_exp2f((m_run - mm) * c);
+                a2 = __builtin_amdgcn_exp2f((m2 - mm) * c);
+            }
+            l_run = l_run * a1 + l2 * a2;
+            m_run = mm;
+#pragma unroll
+            for (int d = 0; d < DB; ++d)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) oacc[d][v] = oacc[d][v] * a1 + mine[d * 16 + v] * a2;
         }
-        lt = l_run * a1 + l2 * a2;
     }
-    if (!row_ok) return;
-    const long long row = ((long long)b * a.q_heads + hq) * n + node;
+    const bool holder = WIDE || kh == 0;         // this wavefront holds finished (O, m, l) of its 32 rows
+
     if (a.splits == 1) {
-        const float inv = lt > 0.f ? 1.f / lt : 0.f;
-        unsigned short* orow =
-            (unsigned short*)a.O + (long long)b * a.os[0] + (long long)hq * a.os[1] + (long long)node * a.os[2];
+        if (holder && row_ok) {
+            const float inv = l_run > 0.f ? 1.f / l_run : 0.f;
+            unsigned short* orow =
+                (unsigned short*)a.O + (long long)b * a.os[0] + (long long)hq * a.os[1] + (long long)node * a.os[2];
+#pragma unroll
+            for (int d = 0; d < DB; ++d)
+#pragma unroll
+                for (int v4 = 0; v4 < 4; ++v4) {
+                    unsigned short o4[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        o4[e] = __builtin_bit_cast(unsigned short, (__bf16)(oacc[d][v4 * 4 + e] * inv));
+                    uint2 pk;
+                    pk.x = (unsigned)o4[0] | ((unsigned)o4[1] << 16);
+                    pk.y = (unsigned)o4[2] | ((unsigned)o4[3] << 16);
+                    *(uint2*)(orow + 32 * d + 8 * v4 + 4 * h) = pk;
+                }
+        }
+        return;
+    }
+
+    // ---- several splits: leave the partial, take a ticket, the last one merges ----
+    // Partials travel between workgroups (on different XCDs, each with its own L2) through device-scope
+    // atomic stores and loads, which write through / read around the caches; a device-scope fence would
+    // instead write back and invalidate the whole L2 once per workgroup.  Order: every wavefront waits
+    // until its stores have completed (vmcnt), the workgroup meets at a barrier, then one thread takes the
+    // ticket; the workgroup that sees the last ticket therefore reads completed partials only.
+    // part_o  [group][split][query block][d block][v4][pair][lane] 2 floats
+    // part_ml [group][split][query block][row] (m c, l)
+    typedef unsigned long long u64;
+    auto pack2 = [](float x, float y) -> u64 { return (u64)__float_as_uint(x) | ((u64)__float_as_uint(y) << 32); };
+    const int group = bz * a.row_blocks + rb;
+    if (holder) {
+        u64* po = (u64*)a.part_o + (((size_t)group * a.splits + split) * NQB + qb) * (DB * 8 * 64) + lane;
 #pragma unroll
         for (int d = 0; d < DB; ++d)
+#pragma unroll
+            for (int v2 = 0; v2 < 8; ++v2)
+                __hip_atomic_store(po + (d * 8 + v2) * 64, pack2(oacc[d][2 * v2], oacc[d][2 * v2 + 1]), __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+        if (h == 0)                                                  // lanes l and l + 32 hold the same row
+            __hip_atomic_store((u64*)a.part_ml + (((size_t)group * a.splits + split) * NQB + qb) * 32 + l32,
+                               pack2(m_run == -INFINITY ? -INFINITY : m_run * c /* log2 units */, l_run),
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (tid == 0)
+        s_last = __hip_atomic_fetch_add(a.counters + group, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
+                         (unsigned)(a.splits - 1) ? 1 : 0;
+    __syncthreads();
+    if (!s_last) return;
+    if (tid == 0) __hip_atomic_store(a.counters + group, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // for the next launch
+
+    // merge: thread = (query block cq, lane) x DC of the DB d blocks, same register order as above
+    constexpr int DC = WIDE ? DB : DB / 2;
+    const int cq = WIDE ? wave : (wave & 1);
+    const int d0 = WIDE ? 0 : (wave >> 1) * DC;
+    // CHUNK splits at a time: all their loads are issued before the first one is used (each is a trip to
+    // memory), and the running maximum M is carried from chunk to chunk like in the main loop.
+    constexpr int CHUNK = 48 / (DC * 8) > 4 ? 4 : (48 / (DC * 8) < 1 ? 1 : 48 / (DC * 8));   // register budget
+    const u64* mlp = (const u64*)a.part_ml + ((size_t)group * a.splits * NQB + cq) * 32 + l32;
+    const u64* pp = (const u64*)a.part_o + ((size_t)group * a.splits * NQB + cq) * (DB * 8 * 64) + d0 * 8 * 64 + lane;
+    float M = -INFINITY, Ls = 0.f;
+    f32x16 acc[DC];
+#pragma unroll
+    for (int d = 0; d < DC; ++d)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[d][v] = 0.f;
+    for (int s0 = 0; s0 < a.splits; s0 += CHUNK) {
+        u64 ml[CHUNK], x[CHUNK][DC * 8];
+#pragma unroll
+        for (int i = 0; i < CHUNK; ++i) {
+            const int si = s0 + i < a.splits ? s0 + i : a.splits - 1;      // past the end: a copy, weight 0
+            ml[i] = __hip_atomic_load(mlp + (size_t)si * NQB * 32, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const u64* ps = pp + (size_t)si * NQB * (DB * 8 * 64);
+#pragma unroll
+            for (int e = 0; e < DC * 8; ++e)
+                x[i][e] = __hip_atomic_load(ps + e * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        float mi[CHUNK], m_new = M;
+#pragma unroll
+        for (int i = 0; i < CHUNK; ++i) {
+            mi[i] = s0 + i < a.splits ? __uint_as_float((unsigned)ml[i]) : -INFINITY;
+            m_new = fmaxf(m_new, mi[i]);
+        }
+        if (m_new == -INFINITY) continue;                                    // nothing visible so far
+        const float alpha = __builtin_amdgcn_exp2f(M - m_new);                // M = -inf gives 0
+        Ls *= alpha;
+#pragma unroll
+        for (int d = 0; d < DC; ++d)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[d][v] *= alpha;
+#pragma unroll
+        for (int i = 0; i < CHUNK; ++i) {
+            const float w = mi[i] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(mi[i] - m_new);
+            Ls = fmaf(w, __uint_as_float((unsigned)(ml[i] >> 32)), Ls);
+#pragma unroll
+            for (int e = 0; e < DC * 8; ++e) {
+                acc[e >> 3][2 * (e & 7)] = fmaf(w, __uint_as_float((unsigned)x[i][e]), acc[e >> 3][2 * (e & 7)]);
+                acc[e >> 3][2 * (e & 7) + 1] = fmaf(w, __uint_as_float((unsigned)(x[i][e] >> 32)), acc[e >> 3][2 * (e & 7) + 1]);
+            }
+        }
+        M = m_new;
+    }
+    const int rho2 = rb * ROWS + cq * 32 + l32;
+    if (rho2 < a.g * n) {
+        const int hq2 = hk * a.g + rho2 / n, node2 = rho2 % n;
+        const float inv = Ls > 0.f ? 1.f / Ls : 0.f;
+        unsigned short* orow =
+            (unsigned short*)a.O + (long long)b * a.os[0] + (long long)hq2 * a.os[1] + (long long)node2 * a.os[2];
+#pragma unroll
+        for (int d = 0; d < DC; ++d)
 #pragma unroll
             for (int v4 = 0; v4 < 4; ++v4) {
                 unsigned short o4[4];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int v = v4 * 4 + e;
-                    float val = oacc[d][v] * a1;
-                    if (!WIDE) val += src[d * 16 + v] * a2;
-                    o4[e] = __builtin_bit_cast(unsigned short, (__bf16)(val * inv));
-                }
+                for (int e = 0; e < 4; ++e)
+                    o4[e] = __builtin_bit_cast(unsigned short, (__bf16)(acc[d][v4 * 4 + e] * inv));
                 uint2 pk;
                 pk.x = (unsigned)o4[0] | ((unsigned)o4[1] << 16);
                 pk.y = (unsigned)o4[2] | ((unsigned)o4[3] << 16);
-                *(uint2*)(orow + 32 * d + 8 * v4 + 4 * h) = pk;
+                *(uint2*)(orow + 32 * (d0 + d) + 8 * v4 + 4 * h) = pk;
             }
-    } else {
-        float* po = a.part_o + (row * a.splits + split) * D;
-#pragma unroll
-        for (int d = 0; d < DB; ++d)
-#pragma unroll
-            for (int v4 = 0; v4 < 4; ++v4) {
-                f32x4 o4;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int v = v4 * 4 + e;
-                    float val = oacc[d][v] * a1;
-                    if (!WIDE) val += src[d * 16 + v] * a2;
-                    o4[e] = val;
-                }
-                *(f32x4*)(po + 32 * d + 8 * v4 + 4 * h) = o4;
-            }
-        if (h == 0) {
-            // the partial's maximum is stored in log2 units (raw maximum times c)
-            a.part_ml[(row * a.splits + split) * 2] = mm == -INFINITY ? -INFINITY : mm * c;
-            a.part_ml[(row * a.splits + split) * 2 + 1] = lt;
-        }
     }
 }
 
@@ -509,6 +596,7 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const AttnKArgs a) {
     }
 }
 
+// f32 path only (the bf16 kernel merges its own partials).
 // Merge the per-split partials of one output row: O = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s.
 // One wavefront per row (4 rows per workgroup); lane s holds split s's (m, l), the weights are
 // broadcast with v_readlane, every lane accumulates D/64 columns.
@@ -557,26 +645,45 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(const AttnKArgs a) {
     }
 }
 
+__global__ void attn_clear_sync_kernel(unsigned int* p) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < OT_ATTN_SYNC_BYTES / 4) p[i] = 0u;
+}
+
 }  // namespace
 
 static size_t align_up(size_t v, size_t al) { return (v + al - 1) / al * al; }
 
+// Workgroups that the split count of the bf16 path aims at: what the chip holds at once (256 compute
+// units; the narrow variant's three tile buffers allow one workgroup per unit at head_dim 128, the wide
+// variant's two buffers allow two).
+#ifndef OT_ATTN_NARROW_WGS
+#define OT_ATTN_NARROW_WGS 256
+#endif
+#ifndef OT_ATTN_WIDE_WGS
+#define OT_ATTN_WIDE_WGS 512
+#endif
+
 AttnPlan plan_attention(const ot_attn_params& p) {
     AttnPlan pl;
     const int g = p.q_heads / p.kv_heads;
-    int base, tile;
+    int base, tile, rows_wg = 0, splits;
     if (p.dtype == OT_BF16) {
-        const int rows_wg = g * p.n > 64 ? 128 : 64;       // wide variant when one KV head has more than 64 rows
+        const bool wide = g * p.n > 64;                    // wide variant when one KV head has more than 64 rows
+        rows_wg = wide ? 128 : 64;
         pl.row_blocks = (g * p.n + rows_wg - 1) / rows_wg;
         base = p.batch * p.kv_heads * pl.row_blocks;
         tile = 64;
+        int target = wide ? OT_ATTN_WIDE_WGS : OT_ATTN_NARROW_WGS;
+        if (!wide && p.head_dim == 64) target *= 2;
+        splits = target / base;                            // never more workgroups than fit at once
     } else {
         pl.row_blocks = (p.n + 15) / 16;
         base = p.batch * p.q_heads * pl.row_blocks;
         tile = 32;
+        splits = (512 + base - 1) / base;
     }
     const int max_tiles = (p.max_prefix + tile - 1) / tile + (p.n + tile - 1) / tile;
-    int splits = (512 + base - 1) / base;
     if (splits > max_tiles) splits = max_tiles;
     if (splits > kMaxSplits) splits = kMaxSplits;
     if (splits < 1) splits = 1;
@@ -584,10 +691,11 @@ AttnPlan plan_attention(const ot_attn_params& p) {
     const int per = (max_tiles + splits - 1) / splits;
     splits = (max_tiles + per - 1) / per;
     pl.splits = splits;
-    const size_t rows = (size_t)p.batch * p.q_heads * p.n;
+    // bf16: partials are stored per workgroup (rows padded to the row block); f32: per output row
+    const size_t rows = p.dtype == OT_BF16 ? (size_t)base * rows_wg : (size_t)p.batch * p.q_heads * p.n;
     pl.part_o_bytes = splits > 1 ? align_up(rows * splits * p.head_dim * 4, 256) : 0;
     pl.part_ml_bytes = splits > 1 ? align_up(rows * splits * 2 * 4, 256) : 0;
-    pl.bytes = pl.part_o_bytes + pl.part_ml_bytes + 256;
+    pl.bytes = OT_ATTN_SYNC_BYTES + pl.part_o_bytes + pl.part_ml_bytes + 256;
     return pl;
 }
 
@@ -597,8 +705,9 @@ int launch_tree_attention(const ot_attn_params& p, const AttnPlan& plan, const v
     AttnKArgs a;
     a.Q = Q; a.Kp = Kp; a.Vp = Vp; a.Kt = Kt; a.Vt = Vt;
     a.prefix_len = prefix_len; a.mask = mask; a.O = O;
-    a.part_o = (float*)workspace;
-    a.part_ml = (float*)((char*)workspace + plan.part_o_bytes);
+    a.counters = (unsigned int*)workspace;
+    a.part_o = (float*)((char*)workspace + OT_ATTN_SYNC_BYTES);
+    a.part_ml = (float*)((char*)workspace + OT_ATTN_SYNC_BYTES + plan.part_o_bytes);
     a.batch = p.batch; a.q_heads = p.q_heads; a.kv_heads = p.kv_heads; a.g = p.q_heads / p.kv_heads;
     a.n = p.n; a.D = p.head_dim; a.max_prefix = p.max_prefix; a.splits = plan.splits;
     a.W = OT_MASK_WORDS(p.n); a.dtype = p.dtype;
@@ -614,10 +723,12 @@ int launch_tree_attention(const ot_attn_params& p, const AttnPlan& plan, const v
         const long long units = (long long)p.batch * p.kv_heads * plan.splits;
         const long long wgs = (units + 7) / 8 * 8 * plan.row_blocks;
         if (wgs > 0x7fffffffLL) return OT_ERR_UNSUPPORTED;
+        if (plan.splits > 1 && (long long)p.batch * p.kv_heads * plan.row_blocks * 4 > OT_ATTN_SYNC_BYTES)
+            return OT_ERR_UNSUPPORTED;      // cannot happen: splits > 1 only with few workgroups
         const dim3 grid((unsigned)wgs);
 #define OT_ATTN_LAUNCH(DD, WW)                                                                             \
     do {                                                                                                   \
-        const size_t lds = 2 * 64 * DD * sizeof(unsigned int);                                             \
+        const size_t lds = (size_t)((WW) ? 2 : OT_ATTN_NBUF_NARROW) * 64 * DD * sizeof(unsigned int);      \
         if (lds > 64 * 1024)                                                                               \
             OT_HIP_CHECK(hipFuncSetAttribute((const void*)attn_mfma_kernel<DD, WW>,                        \
                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));       \
@@ -638,7 +749,7 @@ int launch_tree_attention(const ot_attn_params& p, const AttnPlan& plan, const v
         }
     }
     OT_HIP_CHECK(hipGetLastError());
-    if (plan.splits > 1) {
+    if (plan.splits > 1 && p.dtype != OT_BF16) {
         const long long rows = (long long)p.batch * p.q_heads * p.n;
         hipLaunchKernelGGL(attn_combine_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, a);
         OT_HIP_CHECK(hipGetLastError());
@@ -693,6 +804,15 @@ static int attention_entry(const ot_attn_params* p, const void* Q, const void* K
     if (workspace_bytes < plan.bytes) return OT_ERR_WORKSPACE_TOO_SMALL;
     return launch_tree_attention(*p, plan, Q, K_prefix, V_prefix, K_tree, V_tree, prefix_len, mask, O, workspace,
                                  (hipStream_t)hip_stream, (hipEvent_t)ev0, (hipEvent_t)ev1);
+}
+
+int ot_attn_workspace_prepare(void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!workspace || ((uintptr_t)workspace % 16)) return OT_ERR_INVALID_ARG;
+    if (workspace_bytes < OT_ATTN_SYNC_BYTES) return OT_ERR_WORKSPACE_TOO_SMALL;
+    hipLaunchKernelGGL(attn_clear_sync_kernel, dim3(OT_ATTN_SYNC_BYTES / 4 / 256), dim3(256), 0, (hipStream_t)hip_stream,
+                       (unsigned int*)workspace);
+    OT_HIP_CHECK(hipGetLastError());
+    return OT_OK;
 }
 
 int ot_tree_verify_attention(const ot_attn_params* p, const void* Q, const void* K_prefix, const void* V_prefix,

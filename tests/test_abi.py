@@ -95,6 +95,10 @@ def test_attention_rejects_bad_arguments_without_launching():
     assert L.ot_tree_verify_attention(C.byref(p), *bad, need, None) == -1
     assert L.ot_tree_verify_attention(C.byref(p), *args, need - 1, None) == -3
     assert L.ot_tree_verify_attention(C.byref(_ap(head_dim=96)), *args, need, None) == -2
+    assert need > 4096                                                               # room for the ticket counters
+    assert L.ot_attn_workspace_prepare(None, need, None) == -1
+    assert L.ot_attn_workspace_prepare(C.c_void_p(0x1008), need, None) == -1
+    assert L.ot_attn_workspace_prepare(f, 100, None) == -3
 
 
 def test_binding_fails_loudly_when_library_is_missing(monkeypatch):

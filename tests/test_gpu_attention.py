@@ -102,6 +102,9 @@ def test_large_budget_shape_one_kv_group():
     ("bf16", 1, 2, 2, 128, 0, 70, 0.0, "star"),        # empty prefix, two tree tiles
     ("bf16", 1, 4, 1, 128, 64, 256, 0.0, "random"),    # maximum n
     ("bf16", 1, 1, 1, 128, 5000, 1, 0.0, "random"),    # a single node
+    ("bf16", 2, 4, 4, 64, 300, 40, 0.3, "random"),     # head_dim 64, 64-row workgroups, several splits
+    ("bf16", 3, 2, 2, 128, 2000, 20, 0.9, "random"),   # very ragged: short sequences leave splits empty
+    ("bf16", 1, 16, 1, 128, 700, 30, 0.0, "random"),   # 128-row workgroups, several splits, ragged last row block
 ])
 def test_shapes_and_edges(dtype, B, Hq, Hkv, D, L, n, ragged, shape):
     w = _shape(dtype, B, Hq, Hkv, D, L, n, ragged)
@@ -149,3 +152,28 @@ def test_prefix_length_is_clamped_on_device():
     y = dict(x); y["prefix_len"] = np.array([10_000], dtype=np.int32)
     got = _gpu_attention(y, mask, "f32")
     assert np.abs(got - want).max() < 1e-5
+
+
+def test_one_workspace_serves_consecutive_calls():
+    """The split merge keeps ticket counters in the workspace and must leave them zero: the same prepared
+    workspace is used for three calls in a row, the last one on a smaller problem."""
+    import torch
+    from paper_2406_17276_amd import api
+    big = _shape("bf16", 1, 4, 4, 128, 900, 50)
+    small = _shape("bf16", 1, 2, 2, 128, 260, 17)
+    ws = None
+    for w, seed in [(big, 11), (big, 12), (small, 13)]:
+        x = wl.make_attention_inputs(w, seed)
+        mask = _random_masks(w.batch, w.n, seed)
+        dev = {k: U.to_device(v, "bf16") for k, v in x.items() if k != "prefix_len"}
+        plen = torch.from_numpy(x["prefix_len"].astype(np.int32)).cuda()
+        p = api.attn_params(dev["Q"], dev["K_prefix"], dev["V_prefix"], dev["K_tree"], dev["V_tree"])
+        if ws is None:
+            ws = api.attn_workspace(p, "cuda")
+        assert api.attn_workspace_bytes(p) <= ws.numel()
+        out = api.tree_verify_attention(dev["Q"], dev["K_prefix"], dev["V_prefix"], dev["K_tree"], dev["V_tree"],
+                                        plen, U.mask_to_device(mask), workspace=ws)
+        torch.cuda.synchronize()
+        want = _oracle_attention(x, mask, "bf16")
+        assert np.abs(U.from_device_f64(out) - want).max() < 2e-2
+        assert int(ws[:4096].view(torch.int32).abs().sum().item()) == 0
