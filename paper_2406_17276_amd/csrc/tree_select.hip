@@ -85,6 +85,7 @@ struct Group {
     double* redd;    // LDS double[2][4]
     int phase, bphase, dphase;
     int tid, lane, wave, nw;
+    int nt;          // threads of the group = stride of its LDS key tables
 
     __device__ __forceinline__ int combine(int v, bool is_max) {
         if (SINGLE) return v;
@@ -167,6 +168,53 @@ __device__ __forceinline__ void sort_desc(double (&x)[M]) {
                     }
 }
 
+// Exact end game of a selection, on keys sorted per lane (descending, NaN last): ks[a..b) are this lane's
+// keys still inside the range, f_hi keys of the workgroup lie above the range, f_lo lie above or inside it,
+// every key inside is >= lo and f_lo >= want > f_hi.  Pivots are keys strictly above lo, proposed by the lane
+// with most keys in range; the workgroup counts the keys >= pivot and narrows the range.  Ends when no key
+// lies strictly above lo inside the range: then every key left inside equals lo, the cut value.
+// kt is an LDS table [M][threads of the group].
+struct Range {
+    int a, b;          // this lane's keys inside the range: ks[a..b)
+    int f_hi, f_lo;    // keys of the workgroup above the range / above or inside it
+    double lo;         // every key inside is >= lo
+};
+template <int M, bool SINGLE>
+__device__ __forceinline__ Range pivot_rounds(const double (&ks)[M], double* kt, int want, Range rg, Group<SINGLE>& g) {
+    int a = rg.a, b = rg.b, f_hi = rg.f_hi, f_lo = rg.f_lo;
+    double lo = rg.lo;
+    const int NT = g.nt, tid = g.tid;
+#pragma unroll
+    for (int r = 0; r < M; ++r) kt[r * NT + tid] = ks[r];
+    // every round moves lo up or the upper end down to a key strictly inside, so M * blockDim rounds
+    // always suffice; the bound makes termination unconditional
+    for (int round = 0; round < M * 256 + 2; ++round) {
+        const int cnt = b - a;
+        double prop = nan_d();
+        if (cnt > 0) {
+            const int T = want - f_hi, R = f_lo - f_hi;
+            int q = (int)((float)cnt * (float)(2 * T - 1) * __frcp_rn((float)(2 * R)));
+            q = q > cnt - 1 ? cnt - 1 : (q < 0 ? 0 : q);
+            const double top = kt[a * NT + tid];
+            prop = kt[(a + q) * NT + tid];
+            if (!(prop > lo)) prop = top;
+        }
+        const bool valid = prop > lo;
+        const int win = g.max_i(valid ? ((cnt << 16) | (0xffff - tid)) : 0);
+        if (win == 0) break;
+        const double p = g.bcast(prop, 0xffff - (win & 0xffff));
+        int ge = 0;
+#pragma unroll
+        for (int r = 0; r < M; ++r) ge += ks[r] >= p ? 1 : 0;
+        const int f_p = g.sum_i(ge);
+        if (f_p >= want) { lo = p; b = ge; f_lo = f_p; }
+        else             { a = ge; f_hi = f_p; }
+    }
+    Range out;
+    out.a = a; out.b = b; out.f_hi = f_hi; out.f_lo = f_lo; out.lo = lo;
+    return out;
+}
+
 // Result of "keep the `want` largest keys of the workgroup".
 struct Cut {
     unsigned keep;     // bit r: this lane's key[r] is kept for certain
@@ -189,7 +237,7 @@ struct Cut {
 template <int M, bool SINGLE, bool SORTED>
 __device__ Cut select_keys(const double (&key)[M], double* kt, int* hist, int want, bool have_first,
                            double first_pivot, Group<SINGLE>& g) {
-    const int NT = blockDim.x, tid = g.tid;
+    (void)kt;
     Cut cut;
     cut.keep = 0u; cut.need = 0; cut.total_eq = 0;
     double lmin = nan_d(), lmax = nan_d();
@@ -288,39 +336,15 @@ __device__ Cut select_keys(const double (&key)[M], double* kt, int* hist, int wa
 #pragma unroll
     for (int r = 0; r < M; ++r) ks[r] = key[r];
     if (!SORTED) sort_desc<M>(ks);
-#pragma unroll
-    for (int r = 0; r < M; ++r) kt[r * NT + tid] = ks[r];
-    int a = __popc(cut.keep), b = a + __popc(in);
-    // every round moves lo up or the upper end down to a key strictly inside, so M * blockDim rounds
-    // always suffice; the bound makes termination unconditional
-    for (int round = 0; round < M * 256 + 2; ++round) {
-        const int cnt = b - a;
-        double prop = nan_d();
-        if (cnt > 0) {
-            const int T = want - f_hi, R = f_lo - f_hi;
-            int q = (int)((float)cnt * (float)(2 * T - 1) * __frcp_rn((float)(2 * R)));
-            q = q > cnt - 1 ? cnt - 1 : (q < 0 ? 0 : q);
-            const double top = kt[a * NT + tid];
-            prop = kt[(a + q) * NT + tid];
-            if (!(prop > lo)) prop = top;
-        }
-        const bool valid = prop > lo;
-        const int win = g.max_i(valid ? ((cnt << 16) | (0xffff - tid)) : 0);
-        if (win == 0) break;
-        const double p = g.bcast(prop, 0xffff - (win & 0xffff));
-        int ge = 0;
-#pragma unroll
-        for (int r = 0; r < M; ++r) ge += ks[r] >= p ? 1 : 0;
-        const int f_p = g.sum_i(ge);
-        if (f_p >= want) { lo = p; b = ge; f_lo = f_p; }
-        else             { a = ge; f_hi = f_p; }
-    }
-    cut.tau = lo;
+    Range rg;
+    rg.a = __popc(cut.keep); rg.b = rg.a + __popc(in); rg.f_hi = f_hi; rg.f_lo = f_lo; rg.lo = lo;
+    rg = pivot_rounds<M, SINGLE>(ks, kt, want, rg, g);
+    cut.tau = rg.lo;
     cut.keep = 0u;
 #pragma unroll
-    for (int r = 0; r < M; ++r) cut.keep |= (key[r] > lo ? 1u : 0u) << r;
-    cut.need = want - f_hi;
-    cut.total_eq = f_lo - f_hi;
+    for (int r = 0; r < M; ++r) cut.keep |= (key[r] > rg.lo ? 1u : 0u) << r;
+    cut.need = want - rg.f_hi;
+    cut.total_eq = rg.f_lo - rg.f_hi;
     return cut;
 }
 
@@ -550,6 +574,7 @@ __device__ void finalize_tree(const SelKArgs& a, const Pool& P, int steps, int b
     g.phase = g.bphase = g.dphase = 0;                     \
     g.tid = threadIdx.x; g.lane = threadIdx.x & 63;        \
     g.wave = threadIdx.x >> 6; g.nw = blockDim.x >> 6;     \
+    g.nt = blockDim.x;                                     \
     for (int i_ = threadIdx.x; i_ < kBuckets + 4; i_ += blockDim.x) s_hist[i_] = 0; \
     __syncthreads();
 
@@ -647,6 +672,315 @@ __global__ __launch_bounds__(256) void tree_finalize_kernel(const SelKArgs a) {
     finalize_tree<DMAX, SINGLE>(a, P, steps, b, lo0, g, s_cntw, s_hist);
 }
 
+// ---------------------------------------------------------------------------
+// Fast path: n <= 64 (one wavefront owns the whole frontier, no barriers after the prologue) and the
+// row statistics of the whole tree fit in LDS.
+//   prologue  256 threads turn (top-k logits, lse) of every row into log-probabilities
+//             dl[row][r] = x - lse (fp64) in LDS; three of the four wavefronts then leave.
+//   step t    lane j: ck[r] = S_j + dl[row(t, j)][r] -- already sorted by rank; cut_sorted() finds how
+//             many of them survive; only (log p^, parent slot, rank) go to the pool, token ids are
+//             fetched at the end, for the nodes of the tree only.
+//   finish    final selection, then every tree node moves to the lane of its output index: the
+//             ancestor masks (one 64-bit word) are built with lane permutes by pointer doubling
+//             and all outputs are written with one store each.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ double wave_max_d(double v) {
+    v = fmax(v, dpp_d<DPP_QUAD_XOR1>(v));
+    v = fmax(v, dpp_d<DPP_QUAD_XOR2>(v));
+    v = fmax(v, dpp_d<DPP_ROW_HALF_MIRROR>(v));
+    v = fmax(v, dpp_d<DPP_ROW_MIRROR>(v));
+    return fmax(fmax(rl_d(v, 0), rl_d(v, 16)), fmax(rl_d(v, 32), rl_d(v, 48)));
+}
+
+// The cut bucket of a 256-bin histogram (one wavefront; lane L scans bins 4L..4L+3 and clears them):
+// B = the bin that holds the T-th largest key, above = keys in higher bins, inb = keys in bin B,
+// total = all keys.  B = -1 if there are fewer than T keys.
+__device__ __forceinline__ void hist_cut(int* hist, int T, int L, int& B, int& above, int& inb, int& total) {
+    constexpr int BPL = kBuckets / 64;
+    int c[BPL];
+    int sum = 0;
+#pragma unroll
+    for (int i = 0; i < BPL; ++i) { c[i] = hist[BPL * L + i]; sum += c[i]; }
+#pragma unroll
+    for (int i = 0; i < BPL; ++i) hist[BPL * L + i] = 0;
+    const int P = wave_incl_scan(sum, L);
+    total = rl(P, 63);
+    const int above_lane = total - P;                 // keys in higher lanes' bins
+    const bool has = above_lane < T && above_lane + sum >= T;
+    int Bl = BPL * L, abl = above_lane, inl = 0;
+    bool found = false;
+#pragma unroll
+    for (int i = BPL - 1; i >= 0; --i) {              // highest bin first
+        if (!found) {
+            if (abl + c[i] >= T) { found = true; Bl = BPL * L + i; inl = c[i]; }
+            else abl += c[i];
+        }
+    }
+    const u64 bal = __ballot(has);
+    B = -1; above = 0; inb = 0;
+    if (bal != 0ull) {
+        const int src = __ffsll((long long)bal) - 1;
+        B = rl(Bl, src); above = rl(abl, src); inb = rl(inl, src);
+    }
+}
+
+// How many of this lane's candidates survive "keep the `want` best of the wavefront's candidates".
+// ck: this lane's candidates, descending, NaN = absent (NaN last).  r0: every lane that has candidates
+// has more than r0 of them and (r0 + 1) x (such lanes) >= want, so the smallest rank-r0 candidate is a
+// lower bound of the cut.  Ties at the cut go to the smaller lane, then the smaller rank.
+// The survivors of a lane are a prefix of its list, so the search keeps two prefix lengths per lane,
+// a (certainly kept) <= b (kept or undecided), instead of per-key flags:
+//   two histogram levels (256 bins each) over [lower bound, largest key] narrow the undecided keys to
+//   one of 65536 cells; if the cut falls between two bins the answer is exact and the search is over,
+//   otherwise the pivot rounds finish on the few keys left.
+template <int M>
+__device__ __forceinline__ int cut_sorted(const double (&ck)[M], double* kt, int* hist, int want, int r0, int lane,
+                                          Group<true>& g) {
+    double c0 = ck[0];
+    if (r0 != 0) {
+#pragma unroll
+        for (int r = 1; r < M; ++r) c0 = (r == r0) ? ck[r] : c0;
+    }
+    double lo = wave_min_d(c0);
+    const double gmax = wave_max_d(ck[0]);
+    int a = 0, b = 0;
+#pragma unroll
+    for (int r = 0; r < M; ++r) b += ck[r] >= lo ? 1 : 0;
+    int f_hi = 0, f_lo = 0;
+    if (gmax > lo) {
+        // u = (key - lo) * scale lies in [0, 256) for every key in [lo, gmax]; the factor below 256 absorbs
+        // the error of the approximate reciprocal.  Keys below lo or absent give u <= 0 or NaN -> bin 0,
+        // and are kept out by the prefix length b.
+        const double scale = 255.9 * __builtin_amdgcn_rcp(next_up(gmax) - lo);
+        double u[M];
+#pragma unroll
+        for (int r = 0; r < M; ++r) u[r] = (ck[r] - lo) * scale;
+        for (int level = 0; level < 2; ++level) {
+            int bk[M];
+#pragma unroll
+            for (int r = 0; r < M; ++r) {
+                const int q = (int)u[r];              // saturating; NaN -> 0
+                bk[r] = q < 0 ? 0 : q;                // keys above the range (level 1) keep a value >= 256
+            }
+#pragma unroll
+            for (int r = 0; r < M; ++r)
+                if (r >= a && r < b) atomicAdd(&hist[bk[r]], 1);
+            lds_sync<true>();
+            const int T = want - f_hi;                // rank of the cut among the undecided keys
+            int B, above, inb, total;
+            hist_cut(hist, T, lane, B, above, inb, total);
+            if (level == 0) f_lo = total;
+            if (B < 0) break;                         // cannot happen (at least `want` keys are >= lo); be safe
+            int n_gt = 0, n_ge = 0;                   // prefix lengths: keys above bin B, keys in or above it
+#pragma unroll
+            for (int r = 0; r < M; ++r) { n_gt += bk[r] > B ? 1 : 0; n_ge += bk[r] >= B ? 1 : 0; }
+            n_ge = n_ge < b ? n_ge : b;               // bin 0 also collects the keys below the range
+            n_gt = n_gt < b ? n_gt : b;
+            if (above + inb == T) return n_ge;        // the cut falls between two bins
+            a = n_gt; b = n_ge;
+            f_hi += above; f_lo = f_hi + inb;
+#pragma unroll
+            for (int r = 0; r < M; ++r) u[r] = (u[r] - (double)B) * (double)kBuckets;
+        }
+    } else {
+        f_lo = wave_sum_u(b);                          // every key >= lo equals lo
+    }
+    Range rg;
+    rg.a = a; rg.b = b; rg.f_hi = f_hi; rg.f_lo = f_lo; rg.lo = lo;
+    rg = pivot_rounds<M, true>(ck, kt, want, rg, g);
+    int cnt = 0, lane_eq = 0;
+#pragma unroll
+    for (int r = 0; r < M; ++r) { cnt += ck[r] > rg.lo ? 1 : 0; lane_eq += ck[r] == rg.lo ? 1 : 0; }
+    const int need = want - rg.f_hi, total_eq = rg.f_lo - rg.f_hi;
+    int take = lane_eq;
+    if (total_eq != need) {
+        const int before = wave_incl_scan(lane_eq, lane) - lane_eq;
+        take = need - before;
+        take = take < 0 ? 0 : (take > lane_eq ? lane_eq : take);
+    }
+    return cnt + take;
+}
+
+struct FastLds {
+    double* dl;               // [rows + 1][KMAX]  log-probabilities of the top-k of every row; last row: NaN
+    double* key;              // [DMAX][64]        pool: log p^ by (layer, slot); later the final selection's table
+    double* kt;               // [KMAX][64]        table of the pivot rounds; later the nodes by output index
+    unsigned short* meta;     // [DMAX][64]        pool: parent slot | rank << 8
+    unsigned char* oidx;      // [DMAX][64]        output index of a selected pool node
+};
+__host__ __device__ inline size_t fast_lds_bytes(int rows, int KMAX, int DMAX) {
+    const int km = KMAX < 4 ? 4 : KMAX;               // the table doubles as 64 x 16 bytes of node records
+    return (size_t)(rows + 1) * KMAX * 8 + (size_t)DMAX * 64 * 8 + (size_t)km * 64 * 8 + (size_t)DMAX * 64 * 2 +
+           (size_t)DMAX * 64;
+}
+
+template <int KMAX, int DMAX>
+__global__ __launch_bounds__(256) void tree_fast_kernel(const SelKArgs a) {
+    extern __shared__ __attribute__((aligned(16))) u64 smem[];
+    __shared__ int s_hist[kBuckets + 4];
+    const int tid = threadIdx.x, b = blockIdx.x, D = a.depth, k = a.k, n = a.n;
+    const int rows = a.rows_per_seq;
+    FastLds P;
+    P.dl = (double*)smem;
+    P.key = P.dl + (size_t)(rows + 1) * KMAX;
+    P.kt = P.key + DMAX * 64;
+    P.meta = (unsigned short*)(P.kt + (KMAX < 4 ? 4 : KMAX) * 64);
+    P.oidx = (unsigned char*)(P.meta + DMAX * 64);
+    const size_t rbase = (size_t)b * rows;
+
+    // ---- prologue, all four wavefronts ----
+    for (int i = tid; i < kBuckets + 4; i += 256) s_hist[i] = 0;
+    for (int i = tid; i < (rows + 1) * KMAX; i += 256) {
+        const int row = i / KMAX, r = i - row * KMAX;
+        double v = nan_d();
+        if (row < rows && r < k) v = (double)a.row_topv[(rbase + row) * k + r] - a.row_lse[rbase + row];   // Eq. 2, log space
+        P.dl[i] = v;
+    }
+    __syncthreads();
+    if (tid >= 64) return;
+    const int lane = tid;
+    Group<true> g;
+    g.red = nullptr; g.bc = nullptr; g.redd = nullptr;
+    g.phase = g.bphase = g.dphase = 0;
+    g.tid = lane; g.lane = lane; g.wave = 0; g.nw = 1; g.nt = 64;
+
+    // ---- Algorithm 1, step by step ----
+    for (int t = 0; t < D; ++t) {
+        const int F = a.F[t], Fn = a.F[t + 1];
+        const bool active = lane < F;
+        const double* drow = P.dl + (size_t)(active ? a.row_start[t] + lane : rows) * KMAX;
+        const double S = t == 0 ? 0.0 : P.key[(t - 1) * 64 + lane];
+        double ck[KMAX];
+#pragma unroll
+        for (int r = 0; r < KMAX; r += 2) {
+            const double2 d2 = *(const double2*)(drow + r);
+            ck[r] = S + d2.x;                         // log p^(child) = log p^(parent) + log p   (Eq. 2)
+            ck[r + 1] = S + d2.y;
+        }
+        int cnt;
+        if (k * F <= Fn) cnt = active ? k : 0;
+        else cnt = cut_sorted<KMAX>(ck, P.kt, s_hist, Fn, a.r0[t], lane, g);
+        const int off = wave_incl_scan(cnt, lane) - cnt;
+#pragma unroll
+        for (int r = 0; r < KMAX; ++r) {
+            if (r < cnt) {
+                P.key[t * 64 + off + r] = ck[r];
+                P.meta[t * 64 + off + r] = (unsigned short)(lane | (r << 8));
+            }
+        }
+        lds_sync<true>();
+    }
+
+    // ---- last line of Algorithm 1: the n best nodes of the pool ----
+    int pool_nodes = 0;
+    for (int t = 0; t < D; ++t) pool_nodes += a.F[t + 1];
+    const int n_out = pool_nodes < n ? pool_nodes : n;
+    double pk[DMAX];
+    int tk[DMAX], mt[DMAX];
+#pragma unroll
+    for (int t = 0; t < DMAX; ++t) {
+        const bool valid = t < D && lane < a.F[t + 1];
+        pk[t] = valid ? P.key[t * 64 + lane] : nan_d();
+        mt[t] = valid ? (int)P.meta[t * 64 + lane] : 0;
+    }
+#pragma unroll
+    for (int t = 0; t < DMAX; ++t) {                  // token ids: in flight during the selection
+        tk[t] = 0;
+        if (t < D && lane < a.F[t + 1]) tk[t] = a.row_topi[(rbase + a.row_start[t] + (mt[t] & 255)) * k + (mt[t] >> 8)];
+    }
+    unsigned int sel = 0;                             // bit t: pool node (layer t+1, slot lane) is in the tree
+    if (pool_nodes <= n) {
+#pragma unroll
+        for (int t = 0; t < DMAX; ++t) sel |= (pk[t] == pk[t] ? 1u : 0u) << t;
+    } else {
+        // a layer with n nodes: at least n pool nodes reach its smallest log p^
+        double lo0 = nan_d();
+        int used = 0;
+#pragma unroll
+        for (int t = 0; t < DMAX; ++t)
+            if (t < D && a.F[t + 1] >= n && used < 2) { lo0 = fmax(lo0, wave_min_d(pk[t])); ++used; }
+        lds_sync<true>();                             // the pool keys sit in registers: their LDS region becomes the table
+        const Cut cut = select_keys<DMAX, true, false>(pk, P.key, s_hist, n, lo0 == lo0, lo0, g);
+        sel = cut.keep;
+        int need = cut.need;
+        if (need > 0 && cut.total_eq == need) {
+#pragma unroll
+            for (int t = 0; t < DMAX; ++t) sel |= (pk[t] == cut.tau ? 1u : 0u) << t;
+        } else if (need > 0) {                        // ties at the cut: shallower first, then smaller slot
+#pragma unroll
+            for (int t = 0; t < DMAX; ++t) {
+                if (t < D) {
+                    const u64 bal = __ballot(pk[t] == cut.tau);
+                    const int before = __popcll(bal & ((1ull << lane) - 1ull));
+                    if (pk[t] == cut.tau && before < need) sel |= 1u << t;
+                    const int layer_eq = __popcll(bal);
+                    need -= layer_eq < need ? layer_eq : need;
+                }
+            }
+        }
+    }
+
+    // output index = rank in (depth, slot) order among the selected nodes
+    int my_i[DMAX];
+    {
+        int base = 0;
+#pragma unroll
+        for (int t = 0; t < DMAX; ++t) {
+            const u64 bal = __ballot((sel >> t) & 1u);
+            my_i[t] = base + __popcll(bal & ((1ull << lane) - 1ull));
+            if ((sel >> t) & 1u) P.oidx[t * 64 + lane] = (unsigned char)my_i[t];
+            base += __popcll(bal);
+        }
+    }
+    lds_sync<true>();
+    // every tree node moves to the lane of its output index: 16-byte record (log p^, token, parent | depth << 16)
+    u64* rec = (u64*)P.kt;
+#pragma unroll
+    for (int t = 0; t < DMAX; ++t) {
+        if ((sel >> t) & 1u) {
+            const int pi = t > 0 ? (int)P.oidx[(t - 1) * 64 + (mt[t] & 255)] : 0xffff;
+            rec[2 * my_i[t]] = (u64)__double_as_longlong(pk[t]);
+            rec[2 * my_i[t] + 1] = (u64)(unsigned)tk[t] | ((u64)(unsigned)(pi | ((t + 1) << 16)) << 32);
+        }
+    }
+    lds_sync<true>();
+    const bool node = lane < n_out;
+    double key = nan_d();
+    int tok = -1, par = -1, dep = 0;
+    if (node) {
+        key = __longlong_as_double((long long)rec[2 * lane]);
+        const u64 w = rec[2 * lane + 1];
+        tok = (int)(unsigned)w;
+        const unsigned pd = (unsigned)(w >> 32);
+        par = (pd & 0xffff) == 0xffff ? -1 : (int)(pd & 0xffff);
+        dep = (int)(pd >> 16);
+    }
+    // ancestor masks (Algorithm 2) by pointer doubling: after round r, m covers the node and its 2^(r+1) - 1
+    // nearest ancestors, anc is the 2^(r+1)-th ancestor (a depth-1 node stands for "none": it points at itself)
+    u64 m = node ? 1ull << lane : 0ull;
+    int anc = (node && par >= 0) ? par : lane;
+    for (int span = 1; span < D; span *= 2) {
+        const unsigned lo32 = (unsigned)__shfl((int)(unsigned)m, anc);
+        const unsigned hi32 = (unsigned)__shfl((int)(unsigned)(m >> 32), anc);
+        m |= (u64)lo32 | ((u64)hi32 << 32);
+        anc = __shfl(anc, anc);
+    }
+    if (lane < n) {
+        const size_t o = (size_t)b * n + lane;
+        a.out.token[o] = tok;
+        a.out.parent[o] = par;
+        a.out.depth[o] = dep;
+        a.out.score[o] = node ? (float)key : -INFINITY;
+        a.out.mask[o] = m;                            // n <= 64: one mask word per node
+    }
+    // E = sum of p^ (Eq. 3)
+    const double e_sum = wave_sum_d(node ? exp(key) : 0.0);
+    if (lane == 0) {
+        a.out.expect[b] = e_sum;
+        a.out.n_out[b] = n_out;
+    }
+}
+
 SelKArgs make_args(const SelectGeometry& g, const BuildWorkspace& ws) {
     SelKArgs a;
     a.row_lse = ws.row_lse; a.row_topv = ws.row_topv; a.row_topi = ws.row_topi;
@@ -729,11 +1063,41 @@ int launch_finalize_t(const SelKArgs& a, int batch, int NT, hipStream_t s) {
     return OT_OK;
 }
 
+// LDS the fast path may use (of the 160 KB of a compute unit)
+constexpr size_t kFastLdsLimit = 144 * 1024;
+
+template <int KMAX, int DMAX>
+int launch_fast_t(const SelKArgs& a, int batch, hipStream_t s) {
+    const size_t lds = fast_lds_bytes(a.rows_per_seq, KMAX, DMAX);
+    int st = set_lds(tree_fast_kernel<KMAX, DMAX>, lds);
+    if (st != OT_OK) return st;
+    hipLaunchKernelGGL((tree_fast_kernel<KMAX, DMAX>), dim3(batch), dim3(256), lds, s, a);
+    OT_HIP_CHECK(hipGetLastError());
+    return OT_OK;
+}
+template <int KMAX>
+int launch_fast_k(const SelKArgs& a, int batch, hipStream_t s) {
+    if (a.depth <= 8) return launch_fast_t<KMAX, 8>(a, batch, s);
+    if (a.depth <= 10) return launch_fast_t<KMAX, 10>(a, batch, s);
+    if (a.depth <= 12) return launch_fast_t<KMAX, 12>(a, batch, s);
+    if (a.depth <= 16) return launch_fast_t<KMAX, 16>(a, batch, s);
+    if (a.depth <= 20) return launch_fast_t<KMAX, 20>(a, batch, s);
+    return launch_fast_t<KMAX, 32>(a, batch, s);
+}
+int fast_kmax(int k) { return k <= 4 ? 4 : (k <= 8 ? 8 : (k <= 10 ? 10 : 16)); }
+int fast_dmax(int d) { return d <= 8 ? 8 : (d <= 10 ? 10 : (d <= 12 ? 12 : (d <= 16 ? 16 : (d <= 20 ? 20 : 32)))); }
+
 }  // namespace
 
 int launch_tree_oneshot(const SelectGeometry& g, const BuildWorkspace& ws, const ot_tree_out& out, hipStream_t s) {
     SelKArgs a = make_args(g, ws);
     a.out = out;
+    if (g.n <= 64 && fast_lds_bytes(g.rows_per_seq, fast_kmax(g.k), fast_dmax(g.depth)) <= kFastLdsLimit) {
+        if (g.k <= 4) return launch_fast_k<4>(a, g.batch, s);
+        if (g.k <= 8) return launch_fast_k<8>(a, g.batch, s);
+        if (g.k <= 10) return launch_fast_k<10>(a, g.batch, s);
+        return launch_fast_k<16>(a, g.batch, s);
+    }
     const int NT = threads_for(g.n);
     return NT == 64 ? launch_oneshot_s<true>(a, g.batch, NT, s) : launch_oneshot_s<false>(a, g.batch, NT, s);
 }

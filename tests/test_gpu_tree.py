@@ -73,6 +73,11 @@ def _random_case(V, k, n, d, B, dtype, seed, scale=3.0):
     (300, 2, 200, 4, 1, "f32"),        # n larger than the pool (2+4+8+16)
     (2048, 12, 130, 3, 2, "bf16"),     # 3 waves
     (512, 8, 256, 32, 1, "f32"),       # maximum n and depth
+    (200, 16, 64, 26, 2, "f32"),       # one wavefront, but the row table exceeds LDS: general path
+    (3000, 10, 64, 20, 1, "bf16"),     # one wavefront, deep tree, row table in LDS
+    (400, 8, 60, 10, 16, "f32"),       # a batch of 70B-shaped trees
+    (300, 16, 40, 2, 2, "f32"),        # depth 2: first cut at the second step
+    (300, 3, 64, 7, 3, "f32"),         # frontier grows 1, 3, 9, 27, 64
 ])
 def test_random_shapes_and_edges(V, k, n, d, B, dtype):
     stored, want = _random_case(V, k, n, d, B, dtype, seed=V + k + n)
