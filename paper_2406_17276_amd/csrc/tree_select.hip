@@ -724,24 +724,27 @@ __device__ __forceinline__ void hist_cut(int* hist, int T, int L, int& B, int& a
     }
 }
 
-// How many of this lane's candidates survive "keep the `want` best of the wavefront's candidates".
-// ck: this lane's candidates, descending, NaN = absent (NaN last).  r0: every lane that has candidates
-// has more than r0 of them and (r0 + 1) x (such lanes) >= want, so the smallest rank-r0 candidate is a
-// lower bound of the cut.  Ties at the cut go to the smaller lane, then the smaller rank.
+// "Keep the `want` largest of the wavefront's keys" for keys that are sorted inside every lane.
+// ck: this lane's keys, descending, NaN = absent (NaN last).  lo: at least `want` keys are >= lo.
+// Result: exact = true: the cnt largest keys of this lane are kept (all kept keys are strictly larger
+// than all others).  exact = false: the keys > tau are kept (cnt of this lane's), and `need` of the
+// `total_eq` keys == tau, in an order the caller defines.
 // The survivors of a lane are a prefix of its list, so the search keeps two prefix lengths per lane,
 // a (certainly kept) <= b (kept or undecided), instead of per-key flags:
 //   two histogram levels (256 bins each) over [lower bound, largest key] narrow the undecided keys to
 //   one of 65536 cells; if the cut falls between two bins the answer is exact and the search is over,
 //   otherwise the pivot rounds finish on the few keys left.
+struct SortedCut {
+    int cnt;
+    bool exact;
+    double tau;
+    int need, total_eq;
+};
 template <int M>
-__device__ __forceinline__ int cut_sorted(const double (&ck)[M], double* kt, int* hist, int want, int r0, int lane,
-                                          Group<true>& g) {
-    double c0 = ck[0];
-    if (r0 != 0) {
-#pragma unroll
-        for (int r = 1; r < M; ++r) c0 = (r == r0) ? ck[r] : c0;
-    }
-    double lo = wave_min_d(c0);
+__device__ __forceinline__ SortedCut cut_sorted(const double (&ck)[M], double* kt, int* hist, int want, double lo,
+                                                int lane, Group<true>& g) {
+    SortedCut out;
+    out.exact = false; out.tau = lo; out.need = 0; out.total_eq = 0;
     const double gmax = wave_max_d(ck[0]);
     int a = 0, b = 0;
 #pragma unroll
@@ -776,7 +779,10 @@ __device__ __forceinline__ int cut_sorted(const double (&ck)[M], double* kt, int
             for (int r = 0; r < M; ++r) { n_gt += bk[r] > B ? 1 : 0; n_ge += bk[r] >= B ? 1 : 0; }
             n_ge = n_ge < b ? n_ge : b;               // bin 0 also collects the keys below the range
             n_gt = n_gt < b ? n_gt : b;
-            if (above + inb == T) return n_ge;        // the cut falls between two bins
+            if (above + inb == T) {                   // the cut falls between two bins
+                out.cnt = n_ge; out.exact = true;
+                return out;
+            }
             a = n_gt; b = n_ge;
             f_hi += above; f_lo = f_hi + inb;
 #pragma unroll
@@ -788,17 +794,37 @@ __device__ __forceinline__ int cut_sorted(const double (&ck)[M], double* kt, int
     Range rg;
     rg.a = a; rg.b = b; rg.f_hi = f_hi; rg.f_lo = f_lo; rg.lo = lo;
     rg = pivot_rounds<M, true>(ck, kt, want, rg, g);
-    int cnt = 0, lane_eq = 0;
+    int cnt = 0;
 #pragma unroll
-    for (int r = 0; r < M; ++r) { cnt += ck[r] > rg.lo ? 1 : 0; lane_eq += ck[r] == rg.lo ? 1 : 0; }
-    const int need = want - rg.f_hi, total_eq = rg.f_lo - rg.f_hi;
+    for (int r = 0; r < M; ++r) cnt += ck[r] > rg.lo ? 1 : 0;
+    out.cnt = cnt; out.tau = rg.lo; out.need = want - rg.f_hi; out.total_eq = rg.f_lo - rg.f_hi;
+    return out;
+}
+
+// One drafting step: how many of this lane's candidates (sorted by rank) survive the cut to `want`.
+// r0: every lane that has candidates has more than r0 of them and (r0 + 1) x (such lanes) >= want, so the
+// smallest rank-r0 candidate is a lower bound of the cut.  Ties at the cut go to the smaller lane
+// (parent slot), then the smaller rank.
+template <int M>
+__device__ __forceinline__ int step_cut(const double (&ck)[M], double* kt, int* hist, int want, int r0, int lane,
+                                        Group<true>& g) {
+    double c0 = ck[0];
+    if (r0 != 0) {
+#pragma unroll
+        for (int r = 1; r < M; ++r) c0 = (r == r0) ? ck[r] : c0;
+    }
+    const SortedCut sc = cut_sorted<M>(ck, kt, hist, want, wave_min_d(c0), lane, g);
+    if (sc.exact) return sc.cnt;
+    int lane_eq = 0;
+#pragma unroll
+    for (int r = 0; r < M; ++r) lane_eq += ck[r] == sc.tau ? 1 : 0;
     int take = lane_eq;
-    if (total_eq != need) {
+    if (sc.total_eq != sc.need) {
         const int before = wave_incl_scan(lane_eq, lane) - lane_eq;
-        take = need - before;
+        take = sc.need - before;
         take = take < 0 ? 0 : (take > lane_eq ? lane_eq : take);
     }
-    return cnt + take;
+    return sc.cnt + take;
 }
 
 struct FastLds {
@@ -830,11 +856,24 @@ __global__ __launch_bounds__(256) void tree_fast_kernel(const SelKArgs a) {
 
     // ---- prologue, all four wavefronts ----
     for (int i = tid; i < kBuckets + 4; i += 256) s_hist[i] = 0;
-    for (int i = tid; i < (rows + 1) * KMAX; i += 256) {
-        const int row = i / KMAX, r = i - row * KMAX;
-        double v = nan_d();
-        if (row < rows && r < k) v = (double)a.row_topv[(rbase + row) * k + r] - a.row_lse[rbase + row];   // Eq. 2, log space
-        P.dl[i] = v;
+    // one row per thread and pass: lse once, the k logits of the row, k subtractions; row `rows` is all NaN
+    {
+        const float* tv = a.row_topv + rbase * k;
+        const double* tl = a.row_lse + rbase;
+        for (int row = tid; row <= rows; row += 256) {
+            const bool real = row < rows;
+            const double lse = real ? tl[row] : nan_d();
+            float x[KMAX];
+#pragma unroll
+            for (int r = 0; r < KMAX; ++r) x[r] = (real && r < k) ? tv[row * k + r] : 0.f;
+#pragma unroll
+            for (int r = 0; r < KMAX; r += 2) {
+                double2 d2;
+                d2.x = r < k ? (double)x[r] - lse : nan_d();            // log p = x - lse (Eq. 2, log space); NaN = absent
+                d2.y = r + 1 < k ? (double)x[r + 1] - lse : nan_d();
+                *(double2*)(P.dl + (size_t)row * KMAX + r) = d2;
+            }
+        }
     }
     __syncthreads();
     if (tid >= 64) return;
@@ -859,7 +898,7 @@ __global__ __launch_bounds__(256) void tree_fast_kernel(const SelKArgs a) {
         }
         int cnt;
         if (k * F <= Fn) cnt = active ? k : 0;
-        else cnt = cut_sorted<KMAX>(ck, P.kt, s_hist, Fn, a.r0[t], lane, g);
+        else cnt = step_cut<KMAX>(ck, P.kt, s_hist, Fn, a.r0[t], lane, g);
         const int off = wave_incl_scan(cnt, lane) - cnt;
 #pragma unroll
         for (int r = 0; r < KMAX; ++r) {
@@ -883,38 +922,60 @@ __global__ __launch_bounds__(256) void tree_fast_kernel(const SelKArgs a) {
         pk[t] = valid ? P.key[t * 64 + lane] : nan_d();
         mt[t] = valid ? (int)P.meta[t * 64 + lane] : 0;
     }
+    const int32_t* ti = a.row_topi + rbase * k;
 #pragma unroll
     for (int t = 0; t < DMAX; ++t) {                  // token ids: in flight during the selection
         tk[t] = 0;
-        if (t < D && lane < a.F[t + 1]) tk[t] = a.row_topi[(rbase + a.row_start[t] + (mt[t] & 255)) * k + (mt[t] >> 8)];
+        if (t < D && lane < a.F[t + 1]) tk[t] = ti[(a.row_start[t] + (mt[t] & 255)) * k + (mt[t] >> 8)];
     }
     unsigned int sel = 0;                             // bit t: pool node (layer t+1, slot lane) is in the tree
     if (pool_nodes <= n) {
 #pragma unroll
         for (int t = 0; t < DMAX; ++t) sel |= (pk[t] == pk[t] ? 1u : 0u) << t;
     } else {
-        // a layer with n nodes: at least n pool nodes reach its smallest log p^
+        // lower bound of the cut: a layer with n nodes -- at least n pool nodes reach its smallest log p^;
+        // failing that, the smallest log p^ of the pool
         double lo0 = nan_d();
         int used = 0;
 #pragma unroll
         for (int t = 0; t < DMAX; ++t)
             if (t < D && a.F[t + 1] >= n && used < 2) { lo0 = fmax(lo0, wave_min_d(pk[t])); ++used; }
+        if (used == 0) {
+            double lmin = nan_d();
+#pragma unroll
+            for (int t = 0; t < DMAX; ++t) lmin = fmin(lmin, pk[t]);
+            lo0 = wave_min_d(lmin);
+        }
+        // the lane's pool keys, sorted, go through the same search as a drafting step
+        double ps[DMAX];
+#pragma unroll
+        for (int t = 0; t < DMAX; ++t) ps[t] = pk[t];
+        sort_desc<DMAX>(ps);
         lds_sync<true>();                             // the pool keys sit in registers: their LDS region becomes the table
-        const Cut cut = select_keys<DMAX, true, false>(pk, P.key, s_hist, n, lo0 == lo0, lo0, g);
-        sel = cut.keep;
-        int need = cut.need;
-        if (need > 0 && cut.total_eq == need) {
+        const SortedCut sc = cut_sorted<DMAX>(ps, P.key, s_hist, n, lo0, lane, g);
+        if (sc.exact) {
+            double thr = nan_d();                     // this lane's smallest kept key
 #pragma unroll
-            for (int t = 0; t < DMAX; ++t) sel |= (pk[t] == cut.tau ? 1u : 0u) << t;
-        } else if (need > 0) {                        // ties at the cut: shallower first, then smaller slot
+            for (int t = 0; t < DMAX; ++t) thr = (t == sc.cnt - 1) ? ps[t] : thr;
 #pragma unroll
-            for (int t = 0; t < DMAX; ++t) {
-                if (t < D) {
-                    const u64 bal = __ballot(pk[t] == cut.tau);
-                    const int before = __popcll(bal & ((1ull << lane) - 1ull));
-                    if (pk[t] == cut.tau && before < need) sel |= 1u << t;
-                    const int layer_eq = __popcll(bal);
-                    need -= layer_eq < need ? layer_eq : need;
+            for (int t = 0; t < DMAX; ++t) sel |= (pk[t] >= thr ? 1u : 0u) << t;      // thr = NaN: none
+        } else {
+#pragma unroll
+            for (int t = 0; t < DMAX; ++t) sel |= (pk[t] > sc.tau ? 1u : 0u) << t;
+            int need = sc.need;
+            if (need > 0 && sc.total_eq == need) {
+#pragma unroll
+                for (int t = 0; t < DMAX; ++t) sel |= (pk[t] == sc.tau ? 1u : 0u) << t;
+            } else if (need > 0) {                    // ties at the cut: shallower first, then smaller slot
+#pragma unroll
+                for (int t = 0; t < DMAX; ++t) {
+                    if (t < D) {
+                        const u64 bal = __ballot(pk[t] == sc.tau);
+                        const int before = __popcll(bal & ((1ull << lane) - 1ull));
+                        if (pk[t] == sc.tau && before < need) sel |= 1u << t;
+                        const int layer_eq = __popcll(bal);
+                        need -= layer_eq < need ? layer_eq : need;
+                    }
                 }
             }
         }
