@@ -29,7 +29,7 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published
 # HBM bytes one row-scan launch moves (rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, scaled by the same
 # counters' readings for a plain 256 MiB copy); see profiles/bench_7b_hbm_traffic_pmc.txt
-SCAN_TRAFFIC_BYTES = {"7b": 26.58e6}
+SCAN_TRAFFIC_BYTES = {"7b": 26.56e6}
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, published
 
 
