@@ -183,11 +183,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const int vcol = (2 * ((pc >> 1) ^ (kkey0 & (SPR - 1))) + (pc & 1)) * 8;                 // V: segment g = (pc/2) ^ (r % 8)
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
     // Request tile t: global memory -> LDS buffer `buf`, 16 bytes per lane and instruction, no registers in
-    // between.  Rows past the end of the keys (prefix tail, last tree tile) re-read the last valid row: their
-    // scores are masked below, so their probabilities are exactly zero and the values only need to be finite.
-    // Written as assembly on purpose: the compiler does not track these loads, so it puts no wait between
-    // them and the LDS reads of the tile being computed; completion is awaited explicitly, per tile, with
-    // s_waitcnt vmcnt (loads complete in order) ahead of the barrier that publishes the buffer.
+    // between.  Full tiles address memory as (uniform base of the tile's rows) + (this lane's fixed 32-bit
+    // offset), which costs no vector arithmetic.  Tiles that reach past the end of the keys (prefix tail,
+    // last tree tile) compute per-lane addresses and re-read the last valid row for the rows past the end:
+    // their scores are masked below, so their probabilities are exactly zero and the values only need to be
+    // finite.  Written as assembly on purpose: the compiler does not track these loads, so it puts no wait
+    // between them and the LDS reads of the tile being computed; completion is awaited explicitly, per tile,
+    // with s_waitcnt vmcnt (loads complete in order) ahead of the barrier that publishes the buffer.
+    const unsigned kofs_p = (unsigned)(kkey0 * (int)a.kps[2] + kcol) * 2u, vofs_p = (unsigned)(kkey0 * (int)a.vps[2] + vcol) * 2u;
+    const unsigned kofs_t = (unsigned)(kkey0 * (int)a.kts[2] + kcol) * 2u, vofs_t = (unsigned)(kkey0 * (int)a.vts[2] + vcol) * 2u;
     auto request_tile = [&](int t, int buf) {
         const bool tree = t >= ptiles;
         const int key0 = tree ? (t - ptiles) * TK : t * TK;
@@ -198,17 +202,31 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         const unsigned short* vbase = tree ? vt : vp;
         unsigned int* const lk = s_buf + buf * BUF;
         unsigned int* const lv = lk + TK * D / 2;
+        if (key0 + TK - 1 <= last) {
+            const unsigned kofs = tree ? kofs_t : kofs_p, vofs = tree ? vofs_t : vofs_p;
 #pragma unroll
-        for (int cc = 0; cc < CH; ++cc) {
-            const int slot0 = cc * 256 + wave_u * 64;      // first 16-byte slot this wavefront fills
-            const unsigned lds_k = (unsigned)(size_t)(__attribute__((address_space(3))) void*)(lk + slot0 * 4);
-            const unsigned lds_v = (unsigned)(size_t)(__attribute__((address_space(3))) void*)(lv + slot0 * 4);
-            int row = key0 + kkey0 + cc * KSTEP;
-            row = row < last ? row : last;
-            const unsigned short* gk = kbase + row * ks + kcol;
-            const unsigned short* gv = vbase + row * vs + vcol;
-            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_k), "v"(gk) : "m0", "memory");
-            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_v), "v"(gv) : "m0", "memory");
+            for (int cc = 0; cc < CH; ++cc) {
+                const int slot0 = cc * 256 + wave_u * 64;      // first 16-byte slot this wavefront fills
+                const unsigned lds_k = (unsigned)(size_t)(__attribute__((address_space(3))) void*)(lk + slot0 * 4);
+                const unsigned lds_v = (unsigned)(size_t)(__attribute__((address_space(3))) void*)(lv + slot0 * 4);
+                const unsigned short* gk = kbase + (long long)(key0 + cc * KSTEP) * ks;      // uniform
+                const unsigned short* gv = vbase + (long long)(key0 + cc * KSTEP) * vs;
+                asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_k), "v"(kofs), "s"(gk) : "m0", "memory");
+                asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_v), "v"(vofs), "s"(gv) : "m0", "memory");
+            }
+        } else {
+#pragma unroll
+            for (int cc = 0; cc < CH; ++cc) {
+                const int slot0 = cc * 256 + wave_u * 64;
+                const unsigned lds_k = (unsigned)(size_t)(__attribute__((address_space(3))) void*)(lk + slot0 * 4);
+                const unsigned lds_v = (unsigned)(size_t)(__attribute__((address_space(3))) void*)(lv + slot0 * 4);
+                int row = key0 + kkey0 + cc * KSTEP;
+                row = row < last ? row : last;
+                const unsigned short* gk = kbase + row * ks + kcol;
+                const unsigned short* gv = vbase + row * vs + vcol;
+                asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_k), "v"(gk) : "m0", "memory");
+                asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_v), "v"(gv) : "m0", "memory");
+            }
         }
     };
 
