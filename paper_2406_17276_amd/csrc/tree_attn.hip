@@ -31,6 +31,8 @@
 // f32 path (attn_f32_kernel): plain fp32 FMA arithmetic, 16 query rows x 32-key tiles.
 #include <math.h>
 
+#include <type_traits>
+
 #include "common.hpp"
 
 namespace ot {
@@ -204,15 +206,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         unsigned int* const lv = lk + TK * D / 2;
         if (key0 + TK - 1 <= last) {
             const unsigned kofs = tree ? kofs_t : kofs_p, vofs = tree ? vofs_t : vofs_p;
+            const unsigned short* gk = kbase + (long long)key0 * ks;      // uniform: rows key0 + cc KSTEP of the tile
+            const unsigned short* gv = vbase + (long long)key0 * vs;
+            unsigned lds_k = (unsigned)(size_t)(__attribute__((address_space(3))) void*)(lk + wave_u * 256);
+            unsigned lds_v = (unsigned)(size_t)(__attribute__((address_space(3))) void*)(lv + wave_u * 256);
 #pragma unroll
-            for (int cc = 0; cc < CH; ++cc) {
-                const int slot0 = cc * 256 + wave_u * 64;      // first 16-byte slot this wavefront fills
-                const unsigned lds_k = (unsigned)(size_t)(__attribute__((address_space(3))) void*)(lk + slot0 * 4);
-                const unsigned lds_v = (unsigned)(size_t)(__attribute__((address_space(3))) void*)(lv + slot0 * 4);
-                const unsigned short* gk = kbase + (long long)(key0 + cc * KSTEP) * ks;      // uniform
-                const unsigned short* gv = vbase + (long long)(key0 + cc * KSTEP) * vs;
+            for (int cc = 0; cc < CH; ++cc) {                 // 16-byte slots cc * 256 + wave * 64 + lane
                 asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_k), "v"(kofs), "s"(gk) : "m0", "memory");
                 asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_v), "v"(vofs), "s"(gv) : "m0", "memory");
+                gk += KSTEP * ks; gv += KSTEP * vs;
+                lds_k += 256 * 16; lds_v += 256 * 16;
             }
         } else {
 #pragma unroll
@@ -243,19 +246,21 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
     for (int i = 0; i < PD; ++i)
         if (t0 + i < t1) request_tile(t0 + i, i);
-    int cur = 0, prev = NBUF - 1;           // buffer of tile t, buffer of tile t - 1 (= of tile t + PD)
-    for (int t = t0; t < t1; ++t) {
+    // One tile, out of buffer CUR.  The buffer index is a compile-time constant (the loop below is unrolled
+    // NBUF times), so that every LDS address of the operand reads is a loop-invariant per-lane value plus an
+    // immediate offset.
+    auto tile_step = [&](int t, auto cur_c) {
+        constexpr int CUR = decltype(cur_c)::value;
+        constexpr int PREV = (CUR + NBUF - 1) % NBUF;      // buffer of tile t - 1 (= of tile t + PD)
         // my requests for tile t have landed (younger ones may still be in flight); after the barrier
         // everybody's have, and everybody is done reading the buffer of tile t - 1
         const int ahead = t1 - 1 - t < PD - 1 ? t1 - 1 - t : PD - 1;
         if (ahead <= 0)      asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
         else if (ahead == 1) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(LPT) : "memory");
         else                 asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(2 * LPT) : "memory");
-        if (t + PD < t1) request_tile(t + PD, prev);
-        const unsigned short* const s_k = (const unsigned short*)(s_buf + cur * BUF);
+        if (t + PD < t1) request_tile(t + PD, PREV);
+        const unsigned short* const s_k = (const unsigned short*)(s_buf + CUR * BUF);
         const unsigned short* const s_v = s_k + TK * D;
-        prev = cur;
-        cur = cur + 1 == NBUF ? 0 : cur + 1;
 
         const bool tree = t >= ptiles;
         const int key0 = tree ? (t - ptiles) * TK : t * TK;
@@ -327,6 +332,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                 }
             }
         }
+    };
+    for (int t = t0; t < t1; t += NBUF) {
+        tile_step(t, std::integral_constant<int, 0>{});
+        if (t + 1 < t1) tile_step(t + 1, std::integral_constant<int, 1>{});
+        if (NBUF > 2 && t + 2 < t1) tile_step(t + 2, std::integral_constant<int, (NBUF > 2 ? 2 : 0)>{});
+        if (NBUF > 3 && t + 3 < t1) tile_step(t + 3, std::integral_constant<int, (NBUF > 3 ? 3 : 0)>{});
     }
 
     l_run = xhalf_sum(l_run);
