@@ -946,7 +946,53 @@ __global__ __launch_bounds__(256) void tree_fast_kernel(const SelKArgs a) {
             for (int t = 0; t < DMAX; ++t) lmin = fmin(lmin, pk[t]);
             lo0 = wave_min_d(lmin);
         }
-        // the lane's pool keys, sorted, go through the same search as a drafting step
+        // Quick search on the unsorted keys: every key >= lo0 gets a 16-bit code, monotone in the key, over
+        // [lo0, largest key]; a 256-bin histogram of the high byte finds the bin of the cut, if needed a second
+        // one of the low byte inside that bin.  When the cut falls between two codes the tree is "code >= cut
+        // code"; otherwise (ties or near-ties at the cut) the exact search below decides.
+        bool done = false;
+        {
+            double lmax = nan_d();
+#pragma unroll
+            for (int t = 0; t < DMAX; ++t) lmax = fmax(lmax, pk[t]);
+            const double gmax = wave_max_d(lmax);
+            if (gmax > lo0) {
+                const double scale = 65535.0 * __builtin_amdgcn_rcp(next_up(gmax) - lo0);
+                int code[DMAX];
+#pragma unroll
+                for (int t = 0; t < DMAX; ++t) {
+                    const int q = (int)((pk[t] - lo0) * scale);          // saturating; NaN -> 0
+                    code[t] = pk[t] >= lo0 ? (q > 65535 ? 65535 : q) : -1;    // -1: below the bound or absent
+                }
+#pragma unroll
+                for (int t = 0; t < DMAX; ++t)
+                    if (code[t] >= 0) atomicAdd(&s_hist[code[t] >> 8], 1);
+                lds_sync<true>();
+                int B0, above0, inb0, total0;
+                hist_cut(s_hist, n, lane, B0, above0, inb0, total0);
+                if (B0 >= 0) {
+                    int cut_code = -1;
+                    if (above0 + inb0 == n) {
+                        cut_code = B0 << 8;
+                    } else {
+#pragma unroll
+                        for (int t = 0; t < DMAX; ++t)
+                            if ((code[t] >> 8) == B0) atomicAdd(&s_hist[code[t] & 255], 1);
+                        lds_sync<true>();
+                        int B1, above1, inb1, total1;
+                        hist_cut(s_hist, n - above0, lane, B1, above1, inb1, total1);
+                        if (B1 >= 0 && above1 + inb1 == n - above0) cut_code = (B0 << 8) | B1;
+                    }
+                    if (cut_code >= 0) {
+#pragma unroll
+                        for (int t = 0; t < DMAX; ++t) sel |= (code[t] >= cut_code ? 1u : 0u) << t;
+                        done = true;
+                    }
+                }
+            }
+        }
+        if (!done) {
+        // exact search: the lane's pool keys, sorted, go through the same routine as a drafting step
         double ps[DMAX];
 #pragma unroll
         for (int t = 0; t < DMAX; ++t) ps[t] = pk[t];
@@ -978,6 +1024,7 @@ __global__ __launch_bounds__(256) void tree_fast_kernel(const SelKArgs a) {
                     }
                 }
             }
+        }
         }
     }
 
