@@ -108,7 +108,7 @@ OT_API int ot_build_tree_timed(const ot_build_params* p, const void* logits,
 /* Streaming form of the same computation: what a decoder calls between the
  * draft model's forwards (the loop of Algorithm 1).  The strides of `p` are
  * ignored by begin; each expand call passes its own.
- *   ot_tree_begin   resets the builder kept in `workspace`;
+ *   ot_tree_begin   resets the builder kept in `workspace` (a small kernel on `hip_stream`);
  *   ot_tree_expand  consumes the F_t rows of step t (row (b,j) at
  *                   rows + b*stride_seq + j*stride_row) and writes the next
  *                   frontier: token and parent slot of its F_{t+1} slots
@@ -124,6 +124,20 @@ OT_API int ot_tree_expand(const ot_build_params* p, int32_t step, const void* ro
 OT_API int ot_tree_finalize(const ot_build_params* p, int32_t steps_done,
                      void* workspace, size_t workspace_bytes,
                      const ot_tree_out* out, void* hip_stream);
+
+/* Adaptive depth: the loop condition of Algorithm 1 ("while ... E_sub(T,n) - E > delta: E <- E_sub(T,n);
+ * drafting step").  Called after the expand of step steps_done-1, ot_tree_esub computes, per sequence,
+ *   e_sub[b] = E_sub(T, n): the sum of the n largest p^ among the nodes drafted so far (Sec. 3: the best
+ *              E over the root-containing n-node subtrees of T; non-decreasing in the steps, Thm. 3.2),
+ *   go_on[b] = 1 if e_sub[b] - E[b] > delta, and then E[b] <- e_sub[b]; else 0.   (E[b] = 0 after begin.)
+ * e_sub (double[batch]) and go_on (int32[batch]) are device pointers.  A sequence whose go_on was 0 is
+ * frozen: later ot_tree_expand calls leave its tree and its frontier outputs untouched, later ot_tree_esub
+ * calls return go_on = 0 for it, and ot_tree_finalize selects among the layers it had when it stopped.
+ * The caller ends the loop when no go_on is set or the maximum depth p->depth is reached.
+ * Returns OT_ERR_INVALID_ARG for steps_done outside 1..depth, a NaN delta, or null / misaligned pointers. */
+OT_API int ot_tree_esub(const ot_build_params* p, int32_t steps_done, double delta,
+                 void* workspace, size_t workspace_bytes,
+                 double* e_sub, int32_t* go_on, void* hip_stream);
 
 /* ------------------------------------------------------------------------
  * Tree-masked verification attention (Algorithm 2: the target model's forward

@@ -237,3 +237,24 @@ def build_tree(logits: np.ndarray, k: int, n: int, depth: int):
     out["row_lse"] = b.row_lse
     out["row_topk"] = b.row_topk
     return out
+
+
+def build_tree_adaptive(logits: np.ndarray, k: int, n: int, max_depth: int, delta: float):
+    """Algorithm 1 with its stopping rule: after the first drafting step, another step is drafted while the
+    depth is below max_depth and E_sub(T, n) - E > delta, with E <- E_sub(T, n) before the step (E starts
+    at 0).  logits[t, j, :] as in build_tree.  Returns finalize()'s dict plus 'steps' (layers drafted) and
+    'e_sub_trace' (E_sub after every step)."""
+    b = TreeBuilder(k, n)
+    E = 0.0
+    b.expand(np.asarray(logits[0, :1, :], dtype=np.float64))
+    trace = [b.e_sub()]
+    while len(b.layers) < max_depth and b.e_sub() - E > delta:
+        E = b.e_sub()
+        F = b.frontier_score.shape[0]
+        b.expand(np.asarray(logits[len(b.layers), :F, :], dtype=np.float64))
+        trace.append(b.e_sub())
+    out = b.finalize()
+    out["layers"] = b.layers
+    out["steps"] = len(b.layers)
+    out["e_sub_trace"] = trace
+    return out

@@ -74,6 +74,9 @@ def lib():
         L.ot_tree_finalize.restype = C.c_int
         L.ot_tree_finalize.argtypes = [C.POINTER(BuildParams), C.c_int32, C.c_void_p, C.c_size_t,
                                        C.POINTER(TreeOut), C.c_void_p]
+        L.ot_tree_esub.restype = C.c_int
+        L.ot_tree_esub.argtypes = [C.POINTER(BuildParams), C.c_int32, C.c_double, C.c_void_p, C.c_size_t,
+                                   C.c_void_p, C.c_void_p, C.c_void_p]
         L.ot_attn_workspace_bytes.restype = C.c_size_t
         L.ot_attn_workspace_bytes.argtypes = [C.POINTER(AttnParams)]
         L.ot_attn_workspace_prepare.restype = C.c_int
@@ -188,6 +191,16 @@ class TreeStream:
                                     self.frontier_parent.data_ptr(), _stream()), "ot_tree_expand")
         self.step += 1
         return self.frontier_token, self.frontier_parent
+
+    def e_sub(self, delta: float):
+        """ot_tree_esub after the latest expand: (E_sub per sequence, go-on flag per sequence), device tensors."""
+        import torch
+        if not hasattr(self, "_esub"):
+            self._esub = torch.empty(self.p.batch, dtype=torch.float64, device=self.ws.device)
+            self._go = torch.empty(self.p.batch, dtype=torch.int32, device=self.ws.device)
+        _check(lib().ot_tree_esub(C.byref(self.p), self.step, float(delta), self.ws.data_ptr(), self.ws.numel(),
+                                  self._esub.data_ptr(), self._go.data_ptr(), _stream()), "ot_tree_esub")
+        return self._esub, self._go
 
     def finalize(self, out: Tree | None = None) -> Tree:
         if out is None:

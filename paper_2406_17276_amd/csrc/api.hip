@@ -66,6 +66,10 @@ BuildWorkspace carve_build_workspace(const ot_build_params& p, void* base) {
     w.step_tau = (double*)take((size_t)p.batch * p.depth * 8);
     w.pool_tok = (int32_t*)take(pool * 4);
     w.pool_par = (int32_t*)take(pool * 4);
+    w.pool_p = (double*)take(pool * 8);
+    w.seq_E = (double*)take((size_t)p.batch * 8);
+    w.seq_steps = (int32_t*)take((size_t)p.batch * 4);
+    w.seq_active = (int32_t*)take((size_t)p.batch * 4);
     w.bytes = off;
     return w;
 }
@@ -147,12 +151,14 @@ int ot_build_tree_timed(const ot_build_params* p, const void* logits, void* work
 }
 
 int ot_tree_begin(const ot_build_params* p, void* workspace, size_t workspace_bytes, void* hip_stream) {
-    (void)hip_stream;
     int st = validate_build(p, false);
     if (st != OT_OK) return st;
     if (!workspace || (uintptr_t)workspace % 16) return OT_ERR_INVALID_ARG;
-    if (workspace_bytes < carve_build_workspace(*p, workspace).bytes) return OT_ERR_WORKSPACE_TOO_SMALL;
-    return OT_OK;   // every step overwrites the state it owns; nothing to clear
+    const BuildWorkspace ws = carve_build_workspace(*p, workspace);
+    if (workspace_bytes < ws.bytes) return OT_ERR_WORKSPACE_TOO_SMALL;
+    // every step overwrites the pool state it owns; only the per-sequence loop state (E = 0, no layer, not
+    // stopped) has to be set
+    return launch_tree_begin(select_geometry(*p, make_frontier(p->k, p->n, p->depth)), ws, (hipStream_t)hip_stream);
 }
 
 int ot_tree_expand(const ot_build_params* p, int32_t step, const void* rows, int64_t stride_seq, int64_t stride_row,
@@ -198,6 +204,18 @@ int ot_tree_finalize(const ot_build_params* p, int32_t steps_done, void* workspa
     return launch_tree_finalize(select_geometry(*p, f), steps_done, ws, *out, (hipStream_t)hip_stream);
 }
 
-
+int ot_tree_esub(const ot_build_params* p, int32_t steps_done, double delta, void* workspace, size_t workspace_bytes,
+                 double* e_sub, int32_t* go_on, void* hip_stream) {
+    int st = validate_build(p, false);
+    if (st != OT_OK) return st;
+    if (steps_done < 1 || steps_done > p->depth) return OT_ERR_INVALID_ARG;
+    if (!(delta == delta)) return OT_ERR_INVALID_ARG;
+    if (!workspace || (uintptr_t)workspace % 16 || !e_sub || !go_on) return OT_ERR_INVALID_ARG;
+    if ((uintptr_t)e_sub % 8 || (uintptr_t)go_on % 4) return OT_ERR_INVALID_ARG;
+    const BuildWorkspace ws = carve_build_workspace(*p, workspace);
+    if (workspace_bytes < ws.bytes) return OT_ERR_WORKSPACE_TOO_SMALL;
+    const Frontier f = make_frontier(p->k, p->n, p->depth);
+    return launch_tree_esub(select_geometry(*p, f), steps_done, delta, ws, e_sub, go_on, (hipStream_t)hip_stream);
+}
 
 }  // extern "C"

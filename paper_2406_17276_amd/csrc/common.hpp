@@ -50,6 +50,10 @@ struct BuildWorkspace {
     double* step_tau;               // [batch][depth]      streaming state: cut value of every step
     int32_t* pool_tok;              // [batch][depth][n]
     int32_t* pool_par;              // [batch][depth][n]
+    double* pool_p;                 // [batch][depth][n]   streaming state: p^ of every pool node
+    double* seq_E;                  // [batch]             streaming state: E of Algorithm 1's loop
+    int32_t* seq_steps;             // [batch]             layers drafted (frozen when the loop has stopped)
+    int32_t* seq_active;            // [batch]             0 once E_sub - E <= delta was seen
     size_t bytes;
 };
 BuildWorkspace carve_build_workspace(const ot_build_params& p, void* base);
@@ -79,6 +83,9 @@ int launch_tree_step(const SelectGeometry& g, int step, const BuildWorkspace& ws
                      int32_t* frontier_parent, hipStream_t s);
 int launch_tree_finalize(const SelectGeometry& g, int steps_done, const BuildWorkspace& ws, const ot_tree_out& out,
                          hipStream_t s);
+int launch_tree_begin(const SelectGeometry& g, const BuildWorkspace& ws, hipStream_t s);
+int launch_tree_esub(const SelectGeometry& g, int steps_done, double delta, const BuildWorkspace& ws, double* e_sub,
+                     int32_t* go_on, hipStream_t s);
 
 struct AttnPlan {
     int row_blocks;      // blocks of query rows per KV head

@@ -28,6 +28,9 @@ struct SelKArgs {
     int r0[OT_MAX_DEPTH + 2];      // rank whose per-lane minimum is a lower bound of step t's cut
     double* pool_key; int32_t* pool_tok; int32_t* pool_par;   // [batch][depth][n]  (streaming state)
     double* step_tau;                                         // [batch][depth]     (streaming state)
+    double* pool_p;                                           // [batch][depth][n]  (streaming state) p^ of every pool node
+    double* seq_E; int32_t* seq_steps; int32_t* seq_active;   // [batch]            (streaming state) adaptive depth
+    double* e_sub; int32_t* go_on; double delta;              // outputs / threshold of the E_sub query
     ot_tree_out out;
     int32_t* frontier_token; int32_t* frontier_parent;        // [batch][n]         (streaming step)
     int step;
@@ -432,19 +435,14 @@ inline size_t pool_lds_bytes(int D, int NT, int DK, int KM) {
 
 // Last line of Algorithm 1 and the outputs.  `steps` layers are in the pool; lo0 (or NaN) is a
 // value that at least n pool nodes reach (the largest cut value of the steps that cut to n).
+// The n best nodes of a pool of `steps` layers (last line of Algorithm 1; also the set whose p^ sum is
+// E_sub(T, n)).  pk[t] = log p^ of pool node (layer t+1, slot tid), NaN = absent; lo0 (or NaN) is a value that
+// at least n pool nodes reach.  Returns bit t set for the selected nodes of this thread.  Ties at the cut:
+// shallower first, then smaller slot.  The pool's key region in LDS becomes the selection's table.
 template <int DMAX, bool SINGLE>
-__device__ void finalize_tree(const SelKArgs& a, const Pool& P, int steps, int b, double lo0, Group<SINGLE>& g,
-                              int* s_cntw /*[OT_MAX_DEPTH][4]*/, int* s_hist) {
-    const int NT = blockDim.x, tid = threadIdx.x, n = a.n;
-    const int W = OT_MASK_WORDS(n);
-    int pool_nodes = 0;
-    for (int t = 0; t < steps; ++t) pool_nodes += a.F[t + 1];
-    const int n_out = pool_nodes < n ? pool_nodes : n;
-
-    double pk[DMAX];
-#pragma unroll
-    for (int t = 0; t < DMAX; ++t) pk[t] = (t < steps && tid < a.F[t + 1]) ? P.key[t * NT + tid] : nan_d();
-
+__device__ unsigned int pool_select(const SelKArgs& a, const Pool& P, const double (&pk)[DMAX], int steps, int pool_nodes,
+                                    double lo0, Group<SINGLE>& g, int* s_hist) {
+    const int n = a.n;
     unsigned int sel = 0;           // bit t: pool node (layer t+1, slot tid) is in the tree
     if (pool_nodes <= n) {
 #pragma unroll
@@ -470,6 +468,23 @@ __device__ void finalize_tree(const SelKArgs& a, const Pool& P, int steps, int b
             }
         }
     }
+    return sel;
+}
+
+template <int DMAX, bool SINGLE>
+__device__ void finalize_tree(const SelKArgs& a, const Pool& P, int steps, int b, double lo0, Group<SINGLE>& g,
+                              int* s_cntw /*[OT_MAX_DEPTH][4]*/, int* s_hist) {
+    const int NT = blockDim.x, tid = threadIdx.x, n = a.n;
+    const int W = OT_MASK_WORDS(n);
+    int pool_nodes = 0;
+    for (int t = 0; t < steps; ++t) pool_nodes += a.F[t + 1];
+    const int n_out = pool_nodes < n ? pool_nodes : n;
+
+    double pk[DMAX];
+#pragma unroll
+    for (int t = 0; t < DMAX; ++t) pk[t] = (t < steps && tid < a.F[t + 1]) ? P.key[t * NT + tid] : nan_d();
+
+    const unsigned int sel = pool_select<DMAX, SINGLE>(a, P, pk, steps, pool_nodes, lo0, g, s_hist);
 
     // output index = rank in (depth, slot) order among the selected nodes
     const int lane = tid & 63;
@@ -621,6 +636,7 @@ __global__ __launch_bounds__(256) void tree_oneshot_kernel(const SelKArgs a) {
 // Streaming: one drafting step; the pool lives in the caller's workspace between launches.
 template <int KMAX, bool SINGLE>
 __global__ __launch_bounds__(256) void tree_step_kernel(const SelKArgs a) {
+    if (!a.seq_active[blockIdx.x]) return;      // frozen by the adaptive-depth rule: its tree stays as it is
     OT_SELECT_SHARED
     (void)s_cntw;
     const int tid = threadIdx.x, b = blockIdx.x, t = a.step, n = a.n;
@@ -637,12 +653,13 @@ __global__ __launch_bounds__(256) void tree_step_kernel(const SelKArgs a) {
     int cnt, off;
     double tau;
     layer_cut<KMAX, SINGLE>(ck, (double*)smem, s_hist, active, a.k, F, Fn, a.r0[t], g, cnt, off, tau);
-    if (tid == 0) a.step_tau[(size_t)b * a.depth + t] = tau;
+    if (tid == 0) { a.step_tau[(size_t)b * a.depth + t] = tau; a.seq_steps[b] = t + 1; }
 #pragma unroll
     for (int r = 0; r < KMAX; ++r) {
         if (r < cnt) {
             const size_t o = pb + (size_t)t * n + off + r;
             a.pool_key[o] = ck[r];
+            a.pool_p[o] = exp(ck[r]);             // p^ (Eq. 2), kept for E_sub
             a.pool_tok[o] = id[r];
             a.pool_par[o] = tid;
             a.frontier_token[(size_t)b * n + off + r] = id[r];
@@ -654,7 +671,8 @@ __global__ __launch_bounds__(256) void tree_step_kernel(const SelKArgs a) {
 template <int DMAX, bool SINGLE>
 __global__ __launch_bounds__(256) void tree_finalize_kernel(const SelKArgs a) {
     OT_SELECT_SHARED
-    const int NT = blockDim.x, tid = threadIdx.x, b = blockIdx.x, n = a.n, steps = a.step;
+    const int NT = blockDim.x, tid = threadIdx.x, b = blockIdx.x, n = a.n;
+    const int steps = a.step < a.seq_steps[b] ? a.step : a.seq_steps[b];     // a frozen sequence has fewer layers
     const Pool P = carve_pool(smem, a.depth, NT, DMAX, 0);
     const size_t pb = (size_t)b * a.depth * n;
     double lo0 = nan_d();
@@ -670,6 +688,55 @@ __global__ __launch_bounds__(256) void tree_finalize_kernel(const SelKArgs a) {
     }
     __syncthreads();
     finalize_tree<DMAX, SINGLE>(a, P, steps, b, lo0, g, s_cntw, s_hist);
+}
+
+// E_sub(T, n) of the tree drafted so far = the sum of the n largest p^ of the pool (Sec. 3, text ahead of
+// Algorithm 1), and the loop condition of Algorithm 1: go on while E_sub - E > delta, with E <- E_sub.
+// A sequence that stops is frozen (tree_step_kernel skips it, tree_finalize_kernel uses its layer count).
+template <int DMAX, bool SINGLE>
+__global__ __launch_bounds__(256) void tree_esub_kernel(const SelKArgs a) {
+    OT_SELECT_SHARED
+    (void)s_cntw;
+    const int NT = blockDim.x, tid = threadIdx.x, b = blockIdx.x, n = a.n;
+    const int steps = a.step < a.seq_steps[b] ? a.step : a.seq_steps[b];
+    const Pool P = carve_pool(smem, a.depth, NT, DMAX, 0);
+    const size_t pb = (size_t)b * a.depth * n;
+    double lo0 = nan_d();
+    int pool_nodes = 0;
+    double pk[DMAX], pp[DMAX];
+#pragma unroll
+    for (int t = 0; t < DMAX; ++t) {
+        pk[t] = nan_d(); pp[t] = 0.0;
+        if (t < steps) {
+            pool_nodes += a.F[t + 1];
+            if (tid < a.F[t + 1]) {
+                pk[t] = a.pool_key[pb + (size_t)t * n + tid];
+                pp[t] = a.pool_p[pb + (size_t)t * n + tid];
+            }
+            const double tau = a.step_tau[(size_t)b * a.depth + t];
+            if (tau == tau) lo0 = (lo0 == lo0) ? fmax(lo0, tau) : tau;
+        }
+    }
+    __syncthreads();
+    const unsigned int sel = pool_select<DMAX, SINGLE>(a, P, pk, steps, pool_nodes, lo0, g, s_hist);
+    double e = 0.0;
+#pragma unroll
+    for (int t = 0; t < DMAX; ++t) e += ((sel >> t) & 1u) ? pp[t] : 0.0;
+    e = g.sum_d(e);
+    if (tid == 0) {
+        a.e_sub[b] = e;
+        int go = 0;
+        if (a.seq_active[b]) {
+            go = (e - a.seq_E[b] > a.delta) ? 1 : 0;
+            if (go) a.seq_E[b] = e; else a.seq_active[b] = 0;
+        }
+        a.go_on[b] = go;
+    }
+}
+
+__global__ void tree_begin_kernel(double* seq_E, int32_t* seq_steps, int32_t* seq_active, int batch) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b < batch) { seq_E[b] = 0.0; seq_steps[b] = 0; seq_active[b] = 1; }
 }
 
 // ---------------------------------------------------------------------------
@@ -1103,6 +1170,8 @@ SelKArgs make_args(const SelectGeometry& g, const BuildWorkspace& ws) {
         a.r0[t] = F > 0 ? (want + F - 1) / F - 1 : 0;
     }
     a.pool_key = ws.pool_key; a.pool_tok = ws.pool_tok; a.pool_par = ws.pool_par; a.step_tau = ws.step_tau;
+    a.pool_p = ws.pool_p; a.seq_E = ws.seq_E; a.seq_steps = ws.seq_steps; a.seq_active = ws.seq_active;
+    a.e_sub = nullptr; a.go_on = nullptr; a.delta = 0.0;
     a.out = ot_tree_out{nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
     a.frontier_token = nullptr; a.frontier_parent = nullptr;
     a.step = 0;
@@ -1217,6 +1286,38 @@ int launch_tree_step(const SelectGeometry& g, int step, const BuildWorkspace& ws
     a.frontier_token = frontier_token; a.frontier_parent = frontier_parent;
     const int NT = threads_for(g.n);
     return NT == 64 ? launch_step_s<true>(a, g.batch, NT, s) : launch_step_s<false>(a, g.batch, NT, s);
+}
+
+template <int DMAX, bool SINGLE>
+int launch_esub_t(const SelKArgs& a, int batch, int NT, hipStream_t s) {
+    const size_t lds = pool_lds_bytes(a.depth, NT, DMAX, 0);
+    int st = set_lds(tree_esub_kernel<DMAX, SINGLE>, lds);
+    if (st != OT_OK) return st;
+    hipLaunchKernelGGL((tree_esub_kernel<DMAX, SINGLE>), dim3(batch), dim3(NT), lds, s, a);
+    OT_HIP_CHECK(hipGetLastError());
+    return OT_OK;
+}
+
+int launch_tree_begin(const SelectGeometry& g, const BuildWorkspace& ws, hipStream_t s) {
+    hipLaunchKernelGGL(tree_begin_kernel, dim3((g.batch + 255) / 256), dim3(256), 0, s, ws.seq_E, ws.seq_steps,
+                       ws.seq_active, g.batch);
+    OT_HIP_CHECK(hipGetLastError());
+    return OT_OK;
+}
+
+int launch_tree_esub(const SelectGeometry& g, int steps_done, double delta, const BuildWorkspace& ws, double* e_sub,
+                     int32_t* go_on, hipStream_t s) {
+    SelKArgs a = make_args(g, ws);
+    a.step = steps_done; a.delta = delta; a.e_sub = e_sub; a.go_on = go_on;
+    const int NT = threads_for(g.n);
+    if (NT == 64) {
+        if (steps_done <= 8) return launch_esub_t<8, true>(a, g.batch, NT, s);
+        if (steps_done <= 16) return launch_esub_t<16, true>(a, g.batch, NT, s);
+        return launch_esub_t<32, true>(a, g.batch, NT, s);
+    }
+    if (steps_done <= 8) return launch_esub_t<8, false>(a, g.batch, NT, s);
+    if (steps_done <= 16) return launch_esub_t<16, false>(a, g.batch, NT, s);
+    return launch_esub_t<32, false>(a, g.batch, NT, s);
 }
 
 int launch_tree_finalize(const SelectGeometry& g, int steps_done, const BuildWorkspace& ws, const ot_tree_out& out,

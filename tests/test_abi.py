@@ -106,3 +106,16 @@ def test_binding_fails_loudly_when_library_is_missing(monkeypatch):
     monkeypatch.setattr(api, "_LIB_PATH", "/nonexistent/libopttree.so")
     with pytest.raises(FileNotFoundError):
         api.lib()
+
+
+def test_esub_rejects_bad_arguments_without_launching():
+    L = api.lib()
+    p = _bp()
+    need = api.build_workspace_bytes(p)
+    f = C.c_void_p(0x1000)
+    assert L.ot_tree_esub(C.byref(p), 0, 0.1, f, need, f, f, None) == -1            # no step done yet
+    assert L.ot_tree_esub(C.byref(p), p.depth + 1, 0.1, f, need, f, f, None) == -1
+    assert L.ot_tree_esub(C.byref(p), 1, float("nan"), f, need, f, f, None) == -1
+    assert L.ot_tree_esub(C.byref(p), 1, 0.1, f, need, None, f, None) == -1
+    assert L.ot_tree_esub(C.byref(p), 1, 0.1, f, need, f, C.c_void_p(0x1002), None) == -1
+    assert L.ot_tree_esub(C.byref(p), 1, 0.1, f, need - 1, f, f, None) == -3

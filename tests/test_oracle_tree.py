@@ -254,3 +254,58 @@ def test_frontier_sizes():
     assert ot.frontier_sizes(10, 50, 10)[:4] == [1, 10, 50, 50]
     assert sum(ot.frontier_sizes(10, 50, 10)[:10]) == 411
     assert sum(ot.frontier_sizes(16, 256, 20)[:20]) == 4625
+
+
+# ---------------------------------------------------------------- adaptive depth (Algorithm 1's loop)
+def _hand_logits():
+    g = json.load(open(os.path.join(GOLDEN, "hand_tree.json")))
+    logits = np.full((g["steps"], g["n"], g["vocab"]), -30.0)
+    for t in range(g["steps"]):
+        rows = np.log(np.array(g["rows"][str(t)], dtype=np.float64))
+        logits[t, :rows.shape[0]] = rows
+    return g, logits
+
+
+@pytest.mark.parametrize("delta,steps", [(0.05, 3), (0.5, 3), (0.8, 2), (0.9, 1), (5.0, 1)])
+def test_adaptive_depth_on_the_hand_example(delta, steps):
+    # E_sub after the steps is 0.9, 1.68, 1.767 (golden file): gains 0.9, 0.78, 0.087.  The loop drafts step
+    # i+1 only if gain_i > delta, and never more than 3 steps here.
+    g, logits = _hand_logits()
+    out = ot.build_tree_adaptive(logits, g["k"], g["n"], g["steps"], delta)
+    assert out["steps"] == steps
+    np.testing.assert_allclose(out["e_sub_trace"], g["e_sub_after_step"][:steps], rtol=1e-12)
+    if steps == 3:
+        assert list(out["token"]) == g["token"] and list(out["parent"]) == g["parent"]
+    if steps == 1:                      # the tree is the root's top-k children
+        assert out["n_out"] == 2 and list(out["token"][:2]) == [0, 1] and list(out["depth"][:2]) == [1, 1]
+
+
+def test_adaptive_depth_reduces_to_fixed_depth_and_to_one_step():
+    V, k, n, dmax = 50, 3, 8, 6
+    logits = _random_logits(V, k, n, dmax, 21)
+    full = ot.build_tree(logits, k, n, dmax)
+    neg = ot.build_tree_adaptive(logits, k, n, dmax, -1.0)      # every gain is >= 0 > -1 (Thm. 3.2): never stops early
+    assert neg["steps"] == dmax
+    for key in ("token", "parent", "depth", "mask"):
+        np.testing.assert_array_equal(neg[key], full[key])
+    assert neg["expect"] == full["expect"]
+    one = ot.build_tree_adaptive(logits, k, n, dmax, 10.0)      # no gain exceeds 10 (E <= n): one step only
+    assert one["steps"] == 1
+    ref = ot.build_tree(logits[:1], k, n, 1)
+    np.testing.assert_array_equal(one["token"], ref["token"])
+
+
+def test_adaptive_depth_trace_obeys_the_loop_condition():
+    V, k, n, dmax = 60, 4, 12, 8
+    for seed, delta in [(3, 0.02), (4, 0.05), (5, 0.2), (6, 0.005)]:
+        logits = _random_logits(V, k, n, dmax, seed)
+        out = ot.build_tree_adaptive(logits, k, n, dmax, delta)
+        tr = out["e_sub_trace"]
+        assert len(tr) == out["steps"]
+        # E_sub after t steps is the E of the fixed-depth tree of t steps (the brute-force-pinned routine)
+        for t in range(1, out["steps"] + 1):
+            assert tr[t - 1] == pytest.approx(ot.build_tree(logits[:t], k, n, t)["expect"], rel=1e-13)
+        gains = np.diff([0.0] + tr)
+        assert np.all(gains[:-1] > delta)                       # every step but the last was licensed
+        if out["steps"] < dmax:
+            assert gains[-1] <= delta                           # stopped because the gain fell to delta or below
