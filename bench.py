@@ -102,6 +102,7 @@ def main():
     ap.add_argument("--mode", default="stream", choices=["stream", "graph"])
     ap.add_argument("--ring", type=int, default=0, help="input copies cycled through (0: enough for 768 MB)")
     ap.add_argument("--no-events", action="store_true", help="do not time individual kernels in the timed region")
+    ap.add_argument("--no-adaptive", action="store_true", help="skip the adaptive-depth streaming leg")
     ap.add_argument("--cpu-steps", type=int, default=4, help="oracle steps timed for cpu_baseline (0 = skip)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (reference dispatch for scaling rocprofv3 "
@@ -251,6 +252,30 @@ def main():
             "algorithmic_bytes": kv_bytes + qo_bytes, "avg_kernel_us": attn_ms * 1e3,
             "mfma_tflops": attn_flops / (attn_ms * 1e-3) / 1e12,
             "mfma_frac_of_peak": attn_flops / (attn_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS}
+
+    # ---- adaptive depth (Algorithm 1's loop) through the streaming entry points, outside the timed region:
+    # begin, then per drafting step expand + E_sub query, then finalize; delta = -1 never stops early, so the
+    # figure is the cost of a full-depth loop without the host reading the go-on flags in between.
+    if args.mode == "stream" and not args.no_adaptive:
+        dcode = api.OT_BF16 if w.dtype == "bf16" else api.OT_F32
+        ts = api.TreeStream(w.batch, w.vocab, w.k, w.n, w.depth, dcode)
+        reps = 20
+        def adaptive_loop(lg):
+            api._check(api.lib().ot_tree_begin(C.byref(ts.p), ts.ws.data_ptr(), ts.ws.numel(), stream), "ot_tree_begin")
+            ts.step = 0
+            for t in range(w.depth):
+                ts.expand(lg[:, t])
+                ts.e_sub(-1.0)
+            return ts.finalize()
+        adaptive_loop(builds[0].logits)
+        torch.cuda.synchronize()
+        ta = time.perf_counter()
+        for i in range(reps):
+            adaptive_loop(builds[i % ring].logits)
+        torch.cuda.synchronize()
+        us_loop = (time.perf_counter() - ta) * 1e6 / reps
+        result["adaptive_depth"] = {"us_per_tree": us_loop, "us_per_drafting_step": us_loop / w.depth, "steps": w.depth,
+                                    "delta": -1.0, "calls_per_step": "ot_tree_expand + ot_tree_esub"}
 
     # ---- CPU oracle on a bounded sample of the same workload ----------------------------------
     if args.cpu_steps > 0:
