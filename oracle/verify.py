@@ -1,0 +1,47 @@
+"""fp64 / exact oracle for the greedy verification of a draft tree.  TEST INFRASTRUCTURE ONLY.
+
+Preliminaries, "Speculative Decoding", and Algorithm 2 of the paper (arxiv 2406.17276): with greedy
+sampling the ground truth at a position is the target model's most probable token there; among the
+branches of the draft tree that start at the root, the longest one that agrees with the ground truth is
+accepted, and the target's token after the last accepted node comes for free, so A tokens are produced
+where A - 1 is the number of accepted draft nodes.  The accepted nodes' K/V rows then join the cache.
+
+Plain Python loops and NumPy indexing only; the most probable token of a row is numpy.argmax (first
+maximum = smallest token id among equal logits, the same tie rule as in the tree builder).
+"""
+from __future__ import annotations
+
+import numpy as np
+
+
+def greedy_verify(target_logits: np.ndarray, token: np.ndarray, parent: np.ndarray, n_out: int):
+    """target_logits[0] is the target's row at the root position (the last token of the input), row 1 + i
+    its row at tree node i.  token / parent as produced by the tree builder (parent -1 = child of the
+    root).  Returns (A, accepted node indices [A - 1], produced tokens [A])."""
+    n_out = int(n_out)
+    cur = -1                                    # the root
+    nodes, produced = [], []
+    while True:
+        g = int(np.argmax(target_logits[cur + 1]))      # ground truth after `cur`
+        produced.append(g)
+        nxt = [i for i in range(n_out) if int(parent[i]) == cur and int(token[i]) == g]
+        if not nxt:
+            break                               # no branch continues with the ground truth
+        if len(nxt) != 1:
+            raise AssertionError("two children of one node carry the same token")
+        cur = nxt[0]
+        nodes.append(cur)
+    return len(produced), nodes, produced
+
+
+def kv_append(K_prefix, V_prefix, K_tree, V_tree, prefix_len, nodes):
+    """Append the accepted nodes' K/V rows to the cache of one sequence (arrays [heads][rows][D]); rows that
+    would not fit in the allocated prefix are dropped.  Returns the new prefix length."""
+    L = int(prefix_len)
+    cap = K_prefix.shape[1]
+    for j, i in enumerate(nodes):
+        if L + j >= cap:
+            return cap
+        K_prefix[:, L + j, :] = K_tree[:, i, :]
+        V_prefix[:, L + j, :] = V_tree[:, i, :]
+    return L + len(nodes)
