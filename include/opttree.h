@@ -197,6 +197,43 @@ OT_API int ot_tree_verify_attention_timed(const ot_attn_params* p,
                              void* O, void* workspace, size_t workspace_bytes, void* hip_stream,
                              void* kernel_begin_event, void* kernel_end_event);
 
+/* ------------------------------------------------------------------------
+ * Greedy verification (Preliminaries, "Speculative Decoding"; Algorithm 2, "Verify" and "Concat").
+ *
+ * target_logits [batch][n + 1][vocab]: the target model's output rows, row 0 at the root position (the last
+ * token of the input), row 1 + i at tree node i (element (b, r, v) at base + b*stride_seq + r*stride_row + v).
+ * The ground truth after a position is the most probable token of its row (equal logits: the smaller token
+ * id).  Starting at the root, the child of the current node that carries the ground truth is accepted and
+ * becomes the current node, until no child does; the ground truth after the last accepted node is produced
+ * as well.  Per sequence:
+ *   accept_len[b]            A  = tokens produced = accepted nodes + 1            (1..n_out[b] + 1)
+ *   accept_node[b][0..A-2]   output indices of the accepted nodes, root side first (rest of [n]: -1)
+ *   accept_token[b][0..A-1]  the produced tokens (rest of [n + 1]: -1)
+ * token / parent / n_out are the tree builder's outputs ([batch][n], [batch][n], [batch]).
+ * ---------------------------------------------------------------------- */
+typedef struct ot_verify_params {
+    int32_t batch, vocab, n;
+    int32_t logits_dtype;               /* OT_F32 | OT_BF16 */
+    int64_t stride_seq, stride_row;     /* in elements; stride_row >= vocab */
+} ot_verify_params;
+
+OT_API size_t ot_verify_workspace_bytes(const ot_verify_params* p);   /* 0 if p is invalid */
+
+OT_API int ot_verify_greedy(const ot_verify_params* p, const void* target_logits,
+                     const int32_t* token, const int32_t* parent, const int32_t* n_out,
+                     void* workspace, size_t workspace_bytes,
+                     int32_t* accept_len, int32_t* accept_node, int32_t* accept_token, void* hip_stream);
+
+/* The accepted nodes join the cache ("Concat" of Algorithm 2): for j < A - 1 the K and V rows of tree node
+ * accept_node[b][j] are copied to prefix row prefix_len[b] + j of every KV head, and
+ * new_prefix_len[b] = min(prefix_len[b] + A - 1, max_prefix); rows that do not fit in max_prefix are dropped.
+ * Uses batch, kv_heads, head_dim, n, max_prefix, dtype and the K/V strides of `p` (the attention call's
+ * parameters).  K_tree / V_tree must not overlap the prefix rows that are written.  Needs no workspace. */
+OT_API int ot_kv_append(const ot_attn_params* p, void* K_prefix, void* V_prefix,
+                 const void* K_tree, const void* V_tree,
+                 const int32_t* prefix_len, const int32_t* accept_len, const int32_t* accept_node,
+                 int32_t* new_prefix_len, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -45,6 +45,11 @@ class AttnParams(C.Structure):
                 ("kt_strides", C.c_int64 * 3), ("vt_strides", C.c_int64 * 3), ("o_strides", C.c_int64 * 3)]
 
 
+class VerifyParams(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("vocab", C.c_int32), ("n", C.c_int32), ("logits_dtype", C.c_int32),
+                ("stride_seq", C.c_int64), ("stride_row", C.c_int64)]
+
+
 def lib():
     """Open libopttree.so (once).  Raises if it has not been built."""
     global _lib
@@ -77,6 +82,12 @@ def lib():
         L.ot_tree_esub.restype = C.c_int
         L.ot_tree_esub.argtypes = [C.POINTER(BuildParams), C.c_int32, C.c_double, C.c_void_p, C.c_size_t,
                                    C.c_void_p, C.c_void_p, C.c_void_p]
+        L.ot_verify_workspace_bytes.restype = C.c_size_t
+        L.ot_verify_workspace_bytes.argtypes = [C.POINTER(VerifyParams)]
+        L.ot_verify_greedy.restype = C.c_int
+        L.ot_verify_greedy.argtypes = [C.POINTER(VerifyParams)] + [C.c_void_p] * 5 + [C.c_size_t] + [C.c_void_p] * 4
+        L.ot_kv_append.restype = C.c_int
+        L.ot_kv_append.argtypes = [C.POINTER(AttnParams)] + [C.c_void_p] * 9
         L.ot_attn_workspace_bytes.restype = C.c_size_t
         L.ot_attn_workspace_bytes.argtypes = [C.POINTER(AttnParams)]
         L.ot_attn_workspace_prepare.restype = C.c_int
@@ -263,6 +274,44 @@ def tree_verify_attention(Q, K_prefix, V_prefix, K_tree, V_tree, prefix_len, mas
         ptr(out), ptr(workspace), 0 if workspace is None else workspace.numel(), _stream()),
         "ot_tree_verify_attention")
     return out
+
+
+def verify_greedy(target_logits, tree: "Tree", workspace=None):
+    """ot_verify_greedy on the current stream.  target_logits [B, n + 1, V] (row 0 = the root position);
+    returns (accept_len [B], accept_node [B, n], accept_token [B, n + 1]) as int32 device tensors."""
+    import torch
+    if target_logits.dim() != 3 or target_logits.stride(2) != 1:
+        raise ValueError("target_logits must be [B, n + 1, V] with a contiguous last dimension")
+    B, rows, V = target_logits.shape
+    n = rows - 1
+    p = VerifyParams(B, V, n, _dtype_code(target_logits), target_logits.stride(0), target_logits.stride(1))
+    need = int(lib().ot_verify_workspace_bytes(C.byref(p)))
+    if need == 0:
+        raise OptTreeError(-2, "ot_verify_workspace_bytes")
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=target_logits.device)
+    dev = target_logits.device
+    accept_len = torch.empty(B, dtype=torch.int32, device=dev)
+    accept_node = torch.empty((B, n), dtype=torch.int32, device=dev)
+    accept_token = torch.empty((B, n + 1), dtype=torch.int32, device=dev)
+    _check(lib().ot_verify_greedy(C.byref(p), target_logits.data_ptr(), tree.token.data_ptr(), tree.parent.data_ptr(),
+                                  tree.n_out.data_ptr(), workspace.data_ptr(), workspace.numel(),
+                                  accept_len.data_ptr(), accept_node.data_ptr(), accept_token.data_ptr(), _stream()),
+           "ot_verify_greedy")
+    return accept_len, accept_node, accept_token
+
+
+def kv_append(K_prefix, V_prefix, K_tree, V_tree, prefix_len, accept_len, accept_node):
+    """ot_kv_append on the current stream: the accepted nodes' K/V rows are appended to the prefix cache in
+    place; returns the new prefix lengths (int32 [B])."""
+    import torch
+    B, Hkv, n, D = K_tree.shape
+    p = attn_params(K_tree, K_prefix, V_prefix, K_tree, V_tree)
+    new_len = torch.empty(B, dtype=torch.int32, device=K_tree.device)
+    _check(lib().ot_kv_append(C.byref(p), K_prefix.data_ptr(), V_prefix.data_ptr(), K_tree.data_ptr(),
+                              V_tree.data_ptr(), prefix_len.data_ptr(), accept_len.data_ptr(),
+                              accept_node.data_ptr(), new_len.data_ptr(), _stream()), "ot_kv_append")
+    return new_len
 
 
 # ---------------------------------------------------------------------------

@@ -1,0 +1,203 @@
+// Greedy verification of a draft tree (Preliminaries, "Speculative Decoding"; Algorithm 2, "Verify"):
+//   ground truth after a position = the target model's most probable token there;
+//   the longest root branch of the tree that agrees with the ground truth is accepted, and the target's token
+//   after the last accepted node is produced as well (A tokens for A - 1 accepted nodes);
+//   the accepted nodes' K/V rows are appended to the cache.
+// Three kernels: the row scan of the tree builder with k = 1 (arg-max of every target row; ties -> smaller
+// token id), a walk down the tree (one workgroup per sequence, thread i = node i, one step per accepted
+// node), and a row gather for the K/V append.
+#include <string.h>
+
+#include "common.hpp"
+
+namespace ot {
+namespace {
+
+struct WalkKArgs {
+    const int32_t* row_top;      // [batch][n + 1]  arg-max of the target's rows (row 0 = the root position)
+    const int32_t *token, *parent, *n_out;
+    int32_t *accept_len, *accept_node, *accept_token;
+    int n;
+};
+
+// Thread i owns node i.  Children of one node carry distinct tokens, so at most one thread matches per step;
+// the chain of matches is at most n_out long, which bounds the loop.
+__global__ __launch_bounds__(256) void verify_walk_kernel(const WalkKArgs a) {
+    __shared__ int s_next[2];
+    const int b = blockIdx.x, i = threadIdx.x, n = a.n;
+    const int n_out = a.n_out[b] < n ? a.n_out[b] : n;
+    const bool have = i < n_out;
+    const int my_tok = have ? a.token[(size_t)b * n + i] : -1;
+    const int my_par = have ? a.parent[(size_t)b * n + i] : -2;
+    const int32_t* top = a.row_top + (size_t)b * (n + 1);
+    int cur = -1, A = 0;
+    for (int step = 0; step <= n_out; ++step) {
+        if (i == 0) s_next[step & 1] = -1;
+        __syncthreads();
+        const int g = top[cur + 1];                          // ground truth after `cur`
+        if (have && my_par == cur && my_tok == g) s_next[step & 1] = i;
+        __syncthreads();
+        const int nx = s_next[step & 1];
+        if (i == 0) {
+            a.accept_token[(size_t)b * (n + 1) + A] = g;
+            if (nx >= 0) a.accept_node[(size_t)b * n + A] = nx;
+        }
+        ++A;
+        if (nx < 0) break;
+        cur = nx;
+    }
+    // A tokens produced, A - 1 nodes accepted; the rest of the output rows is padding
+    for (int j = A - 1 + i; j < n; j += blockDim.x) a.accept_node[(size_t)b * n + j] = -1;
+    for (int j = A + i; j < n + 1; j += blockDim.x) a.accept_token[(size_t)b * (n + 1) + j] = -1;
+    if (i == 0) a.accept_len[b] = A;
+}
+
+struct AppendKArgs {
+    void *Kp, *Vp;
+    const void *Kt, *Vt;
+    const int32_t *prefix_len, *accept_len, *accept_node;
+    int32_t* new_prefix_len;
+    int kv_heads, n, D, max_prefix, esize;
+    long long kps[3], vps[3], kts[3], vts[3];
+};
+
+// grid (accepted row j, batch x KV head); one wavefront copies the K row and the V row of node accept_node[j]
+// to prefix row L + j, 16 bytes per lane
+__global__ __launch_bounds__(64) void kv_append_kernel(const AppendKArgs a) {
+    const int j = blockIdx.x, bh = blockIdx.y;
+    const int b = bh / a.kv_heads, h = bh - b * a.kv_heads;
+    int L = a.prefix_len[b];
+    L = L < 0 ? 0 : (L > a.max_prefix ? a.max_prefix : L);
+    const int cnt = a.accept_len[b] - 1;                     // accepted nodes
+    if (j == 0 && h == 0 && threadIdx.x == 0) a.new_prefix_len[b] = L + cnt < a.max_prefix ? L + cnt : a.max_prefix;
+    if (j >= cnt || L + j >= a.max_prefix) return;
+    const int node = a.accept_node[(size_t)b * a.n + j];
+    if (node < 0 || node >= a.n) return;
+    const int chunks = a.D * a.esize / 16;                    // 16-byte chunks per row
+    const int lane = threadIdx.x;
+    const char* ks = (const char*)a.Kt + ((long long)b * a.kts[0] + (long long)h * a.kts[1] + (long long)node * a.kts[2]) * a.esize;
+    const char* vs = (const char*)a.Vt + ((long long)b * a.vts[0] + (long long)h * a.vts[1] + (long long)node * a.vts[2]) * a.esize;
+    char* kd = (char*)a.Kp + ((long long)b * a.kps[0] + (long long)h * a.kps[1] + (long long)(L + j) * a.kps[2]) * a.esize;
+    char* vd = (char*)a.Vp + ((long long)b * a.vps[0] + (long long)h * a.vps[1] + (long long)(L + j) * a.vps[2]) * a.esize;
+    for (int c = lane; c < chunks; c += 64) {
+        *(u32x4*)(kd + 16 * c) = *(const u32x4*)(ks + 16 * c);
+        *(u32x4*)(vd + 16 * c) = *(const u32x4*)(vs + 16 * c);
+    }
+}
+
+size_t align256(size_t v) { return (v + 255) / 256 * 256; }
+
+// row statistics of the (n + 1) target rows per sequence, k = 1
+BuildWorkspace carve_verify_workspace(const ot_verify_params& p, void* base) {
+    const size_t rows = (size_t)p.batch * (size_t)(p.n + 1);
+    const size_t parts = (size_t)scan_parts(p.vocab);
+    BuildWorkspace w;
+    memset(&w, 0, sizeof(w));
+    size_t off = 0;
+    char* b = (char*)base;
+    auto take = [&](size_t bytes) { char* q = b + off; off = align256(off + bytes); return (void*)q; };
+    w.row_lse = (double*)take(rows * 8);
+    w.row_topv = (float*)take(rows * 4);
+    w.row_topi = (int32_t*)take(rows * 4);
+    if (parts > 1) {
+        w.part_m = (float*)take(rows * parts * 4);
+        w.part_s = (double*)take(rows * parts * 8);
+        w.part_topv = (float*)take(rows * parts * 4);
+        w.part_topi = (int32_t*)take(rows * parts * 4);
+    }
+    w.bytes = off;
+    return w;
+}
+
+int validate_verify(const ot_verify_params* p) {
+    if (!p) return OT_ERR_INVALID_ARG;
+    if (p->batch < 1 || p->vocab < 1 || p->n < 1) return OT_ERR_INVALID_ARG;
+    if (p->logits_dtype != OT_F32 && p->logits_dtype != OT_BF16) return OT_ERR_INVALID_ARG;
+    if (p->stride_row < p->vocab || p->stride_seq < 0) return OT_ERR_INVALID_ARG;
+    if (p->n > OT_MAX_NODES || scan_parts(p->vocab) > 8) return OT_ERR_UNSUPPORTED;
+    return OT_OK;
+}
+
+}  // namespace
+}  // namespace ot
+
+using namespace ot;
+
+extern "C" {
+
+size_t ot_verify_workspace_bytes(const ot_verify_params* p) {
+    if (validate_verify(p) != OT_OK) return 0;
+    return carve_verify_workspace(*p, nullptr).bytes;
+}
+
+int ot_verify_greedy(const ot_verify_params* p, const void* target_logits, const int32_t* token, const int32_t* parent,
+                     const int32_t* n_out, void* workspace, size_t workspace_bytes, int32_t* accept_len,
+                     int32_t* accept_node, int32_t* accept_token, void* hip_stream) {
+    int st = validate_verify(p);
+    if (st != OT_OK) return st;
+    if (!target_logits || !token || !parent || !n_out || !workspace || !accept_len || !accept_node || !accept_token)
+        return OT_ERR_INVALID_ARG;
+    if ((uintptr_t)workspace % 16) return OT_ERR_INVALID_ARG;
+    const int esize = p->logits_dtype == OT_BF16 ? 2 : 4;
+    if ((uintptr_t)target_logits % esize) return OT_ERR_INVALID_ARG;
+    const void* ip[6] = {token, parent, n_out, accept_len, accept_node, accept_token};
+    for (int i = 0; i < 6; ++i)
+        if ((uintptr_t)ip[i] % 4) return OT_ERR_INVALID_ARG;
+    const BuildWorkspace ws = carve_verify_workspace(*p, workspace);
+    if (workspace_bytes < ws.bytes) return OT_ERR_WORKSPACE_TOO_SMALL;
+    hipStream_t s = (hipStream_t)hip_stream;
+
+    ScanGeometry sg;
+    sg.batch = p->batch; sg.vocab = p->vocab; sg.k = 1; sg.dtype = p->logits_dtype;
+    sg.nsteps = 1; sg.rows_per_seq = p->n + 1;
+    memset(sg.row_start, 0, sizeof(sg.row_start));
+    sg.row_start[1] = p->n + 1;
+    sg.stride_seq = p->stride_seq; sg.stride_depth = 0; sg.stride_row = p->stride_row;
+    st = launch_row_scan(sg, target_logits, ws, s);
+    if (st != OT_OK) return st;
+
+    WalkKArgs a;
+    a.row_top = ws.row_topi; a.token = token; a.parent = parent; a.n_out = n_out;
+    a.accept_len = accept_len; a.accept_node = accept_node; a.accept_token = accept_token; a.n = p->n;
+    const int threads = (p->n + 63) / 64 * 64;
+    hipLaunchKernelGGL(verify_walk_kernel, dim3(p->batch), dim3(threads), 0, s, a);
+    OT_HIP_CHECK(hipGetLastError());
+    return OT_OK;
+}
+
+int ot_kv_append(const ot_attn_params* p, void* K_prefix, void* V_prefix, const void* K_tree, const void* V_tree,
+                 const int32_t* prefix_len, const int32_t* accept_len, const int32_t* accept_node,
+                 int32_t* new_prefix_len, void* hip_stream) {
+    if (!p) return OT_ERR_INVALID_ARG;
+    if (p->batch < 1 || p->kv_heads < 1 || p->n < 1 || p->max_prefix < 1 || p->head_dim < 1) return OT_ERR_INVALID_ARG;
+    if (p->dtype != OT_F32 && p->dtype != OT_BF16) return OT_ERR_INVALID_ARG;
+    if (p->n > OT_MAX_NODES) return OT_ERR_UNSUPPORTED;
+    if ((long long)p->batch * p->kv_heads > 65535) return OT_ERR_UNSUPPORTED;
+    const int esize = p->dtype == OT_BF16 ? 2 : 4;
+    if ((p->head_dim * esize) % 16) return OT_ERR_UNSUPPORTED;
+    if (!K_prefix || !V_prefix || !K_tree || !V_tree || !prefix_len || !accept_len || !accept_node || !new_prefix_len)
+        return OT_ERR_INVALID_ARG;
+    const void* vp[4] = {K_prefix, V_prefix, K_tree, V_tree};
+    for (int i = 0; i < 4; ++i)
+        if ((uintptr_t)vp[i] % 16) return OT_ERR_INVALID_ARG;
+    const int vec = 16 / esize;
+    const int64_t* strides[4] = {p->kp_strides, p->vp_strides, p->kt_strides, p->vt_strides};
+    for (int t = 0; t < 4; ++t) {
+        for (int i = 0; i < 3; ++i)
+            if (strides[t][i] < 0 || strides[t][i] % vec) return OT_ERR_INVALID_ARG;
+        if (strides[t][2] < p->head_dim) return OT_ERR_INVALID_ARG;
+    }
+    AppendKArgs a;
+    a.Kp = K_prefix; a.Vp = V_prefix; a.Kt = K_tree; a.Vt = V_tree;
+    a.prefix_len = prefix_len; a.accept_len = accept_len; a.accept_node = accept_node; a.new_prefix_len = new_prefix_len;
+    a.kv_heads = p->kv_heads; a.n = p->n; a.D = p->head_dim; a.max_prefix = p->max_prefix; a.esize = esize;
+    for (int i = 0; i < 3; ++i) {
+        a.kps[i] = p->kp_strides[i]; a.vps[i] = p->vp_strides[i]; a.kts[i] = p->kt_strides[i]; a.vts[i] = p->vt_strides[i];
+    }
+    // at most n nodes can be accepted; rows beyond a sequence's accepted count end at once
+    hipLaunchKernelGGL(kv_append_kernel, dim3(p->n, p->batch * p->kv_heads), dim3(64), 0, (hipStream_t)hip_stream, a);
+    OT_HIP_CHECK(hipGetLastError());
+    return OT_OK;
+}
+
+}  // extern "C"

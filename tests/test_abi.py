@@ -119,3 +119,25 @@ def test_esub_rejects_bad_arguments_without_launching():
     assert L.ot_tree_esub(C.byref(p), 1, 0.1, f, need, None, f, None) == -1
     assert L.ot_tree_esub(C.byref(p), 1, 0.1, f, need, f, C.c_void_p(0x1002), None) == -1
     assert L.ot_tree_esub(C.byref(p), 1, 0.1, f, need - 1, f, f, None) == -3
+
+
+def test_verify_rejects_bad_arguments_without_launching():
+    L = api.lib()
+    vp = lambda **kw: api.VerifyParams(**{**dict(batch=2, vocab=1000, n=16, logits_dtype=api.OT_F32, stride_seq=17000,
+                                                  stride_row=1000), **kw})
+    p = vp()
+    need = L.ot_verify_workspace_bytes(C.byref(p))
+    assert need > 0
+    assert L.ot_verify_workspace_bytes(C.byref(vp(n=0))) == 0
+    assert L.ot_verify_workspace_bytes(C.byref(vp(n=257))) == 0
+    assert L.ot_verify_workspace_bytes(C.byref(vp(stride_row=999))) == 0
+    f = C.c_void_p(0x1000)
+    args = [f] * 4
+    assert L.ot_verify_greedy(C.byref(p), None, f, f, f, f, need, f, f, f, None) == -1
+    assert L.ot_verify_greedy(C.byref(p), f, f, f, f, f, need - 1, f, f, f, None) == -3
+    assert L.ot_verify_greedy(C.byref(p), f, f, f, f, C.c_void_p(0x1008), need, f, f, f, None) == -1
+    assert L.ot_verify_greedy(C.byref(vp(logits_dtype=7)), f, f, f, f, f, need, f, f, f, None) == -1
+    ap = _ap()
+    assert L.ot_kv_append(C.byref(ap), None, f, f, f, f, f, f, f, None) == -1
+    assert L.ot_kv_append(C.byref(ap), C.c_void_p(0x1004), f, f, f, f, f, f, f, None) == -1
+    assert L.ot_kv_append(C.byref(_ap(max_prefix=0)), f, f, f, f, f, f, f, f, None) == -1
