@@ -277,6 +277,30 @@ def main():
         result["adaptive_depth"] = {"us_per_tree": us_loop, "us_per_drafting_step": us_loop / w.depth, "steps": w.depth,
                                     "delta": -1.0, "calls_per_step": "ot_tree_expand + ot_tree_esub"}
 
+    # ---- greedy verification + K/V append of the same shape, outside the timed region: target rows for the root
+    # and the n nodes, the tree slot 0 built, the attention call's caches
+    if args.mode == "stream" and not args.no_adaptive:
+        gt = torch.Generator(device="cuda"); gt.manual_seed(seed + 999)
+        tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+        targets = [(torch.randn((w.batch, w.n + 1, w.vocab), generator=gt, device="cuda") * 4.0).to(tdt) for _ in range(4)]
+        tree0 = builds[0].out
+        kp, vp, kt, vt = (attns[0].keep[i] for i in (1, 2, 3, 4))
+        vws = torch.empty(int(api.lib().ot_verify_workspace_bytes(C.byref(api.VerifyParams(
+            w.batch, w.vocab, w.n, api.OT_BF16 if w.dtype == "bf16" else api.OT_F32, targets[0].stride(0),
+            targets[0].stride(1))))), dtype=torch.uint8, device="cuda")
+        def verify_once(i):
+            alen, anode, _ = api.verify_greedy(targets[i % 4], tree0, workspace=vws)
+            api.kv_append(kp, vp, kt, vt, plen_d, alen, anode)
+        verify_once(0)
+        torch.cuda.synchronize()
+        tv = time.perf_counter()
+        for i in range(100):
+            verify_once(i)
+        torch.cuda.synchronize()
+        result["greedy_verify"] = {"us_per_call_pair": (time.perf_counter() - tv) * 1e4,
+                                   "calls": "ot_verify_greedy + ot_kv_append",
+                                   "target_rows": w.batch * (w.n + 1), "target_bytes": w.batch * (w.n + 1) * w.vocab * w.elem_bytes()}
+
     # ---- CPU oracle on a bounded sample of the same workload ----------------------------------
     if args.cpu_steps > 0:
         from threadpoolctl import threadpool_limits
