@@ -102,7 +102,7 @@ def main():
     ap.add_argument("--mode", default="stream", choices=["stream", "graph"])
     ap.add_argument("--ring", type=int, default=0, help="input copies cycled through (0: enough for 768 MB)")
     ap.add_argument("--no-events", action="store_true", help="do not time individual kernels in the timed region")
-    ap.add_argument("--no-adaptive", action="store_true", help="skip the adaptive-depth streaming leg")
+    ap.add_argument("--main-only", action="store_true", help="skip the adaptive-depth and greedy-verification legs")
     ap.add_argument("--cpu-steps", type=int, default=4, help="oracle steps timed for cpu_baseline (0 = skip)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (reference dispatch for scaling rocprofv3 "
@@ -256,7 +256,7 @@ def main():
     # ---- adaptive depth (Algorithm 1's loop) through the streaming entry points, outside the timed region:
     # begin, then per drafting step expand + E_sub query, then finalize; delta = -1 never stops early, so the
     # figure is the cost of a full-depth loop without the host reading the go-on flags in between.
-    if args.mode == "stream" and not args.no_adaptive:
+    if args.mode == "stream" and not args.main_only:
         dcode = api.OT_BF16 if w.dtype == "bf16" else api.OT_F32
         ts = api.TreeStream(w.batch, w.vocab, w.k, w.n, w.depth, dcode)
         reps = 20
@@ -279,7 +279,7 @@ def main():
 
     # ---- greedy verification + K/V append of the same shape, outside the timed region: target rows for the root
     # and the n nodes, the tree slot 0 built, the attention call's caches
-    if args.mode == "stream" and not args.no_adaptive:
+    if args.mode == "stream" and not args.main_only:
         gt = torch.Generator(device="cuda"); gt.manual_seed(seed + 999)
         tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
         targets = [(torch.randn((w.batch, w.n + 1, w.vocab), generator=gt, device="cuda") * 4.0).to(tdt) for _ in range(4)]
