@@ -225,8 +225,49 @@ def main():
             attns[i % ring].timed(stream, e[2], e[3])
         torch.cuda.synchronize()
         ms_per_step_events = (time.perf_counter() - t1) * 1e3 / K
-        scan_ms = float(np.mean([hip.elapsed_ms(e[0], e[1]) for e in ev]))
-        attn_ms = float(np.mean([hip.elapsed_ms(e[2], e[3]) for e in ev]))
+        scan_all = np.array([hip.elapsed_ms(e[0], e[1]) for e in ev])
+        attn_all = np.array([hip.elapsed_ms(e[2], e[3]) for e in ev])
+        scan_ms, attn_ms = float(scan_all.mean()), float(attn_all.mean())
+
+    # ---- warm variant: the same K steps on ring slot 0 only (inputs stay in the Infinity Cache / L2) --------
+    ms_per_step_warm = None
+    if graph is None and not args.main_only:
+        for i in range(min(20, args.warmup)):
+            builds[0](stream); attns[0](stream)
+        torch.cuda.synchronize()
+        tw = time.perf_counter()
+        for i in range(K):
+            builds[0](stream)
+            attns[0](stream)
+        torch.cuda.synchronize()
+        ms_per_step_warm = (time.perf_counter() - tw) * 1e3 / K
+
+    # ---- yardsticks: what this GPU reaches on a plain 1 GiB streaming read and on a register-only MFMA loop ---
+    yard = None
+    if not args.main_only:
+        L = api.lib()
+        big = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        big.random_(0, 255)
+        sink = torch.zeros(4096, dtype=torch.int32, device="cuda")
+        for _ in range(2):
+            api._check(L.ot_yardstick_stream_read(big.data_ptr(), big.numel(), sink.data_ptr(), stream), "yardstick")
+        torch.cuda.synchronize()
+        ty = time.perf_counter()
+        for _ in range(10):
+            api._check(L.ot_yardstick_stream_read(big.data_ptr(), big.numel(), sink.data_ptr(), stream), "yardstick")
+        torch.cuda.synchronize()
+        read_gbs = 10 * big.numel() / (time.perf_counter() - ty) / 1e9
+        del big
+        iters = 4000
+        api._check(L.ot_yardstick_mfma_loop(iters, sink.data_ptr(), stream), "yardstick")
+        torch.cuda.synchronize()
+        ty = time.perf_counter()
+        for _ in range(3):
+            api._check(L.ot_yardstick_mfma_loop(iters, sink.data_ptr(), stream), "yardstick")
+        torch.cuda.synchronize()
+        mfma_tf = 3 * 2048 * 4 * 4 * iters * 32768.0 / (time.perf_counter() - ty) / 1e12
+        yard = {"hbm_read_GBs": read_gbs, "mfma_bf16_TFLOPs": mfma_tf,
+                "what": "ot_yardstick_stream_read over 1 GiB; ot_yardstick_mfma_loop (v_mfma_f32_32x32x16_bf16, register operands)"}
 
     result = {
         "metric": "tree-build+verify-attention steps/sec", "value": K / dt, "unit": "steps/s",
@@ -237,21 +278,30 @@ def main():
                                f"attention {w.q_heads}q/{w.kv_heads}kv heads, head_dim {w.head_dim}, prefix {w.prefix}",
                    "mode": args.mode, "ring_copies": ring, "seed": seed,
                    "kernel_events": "second pass of the same steps" if use_events else None,
-                   "ms_per_step_with_events": ms_per_step_events},
+                   "ms_per_step_with_events": ms_per_step_events, "ms_per_step_warm_inputs": ms_per_step_warm},
     }
     if scan_ms is not None:
         gbs = logit_bytes / (scan_ms * 1e-3) / 1e9
         result["roofline"] = {"kernel": "row_scan_kernel", "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS,
                               "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
                               "traffic": SCAN_TRAFFIC_BYTES.get(w.name),
-                              "algorithmic_bytes": logit_bytes, "avg_kernel_us": scan_ms * 1e3}
+                              "algorithmic_bytes": logit_bytes, "avg_kernel_us": scan_ms * 1e3,
+                              "kernel_us_p10_p50_p90": [float(v) * 1e3 for v in np.percentile(scan_all, [10, 50, 90])]}
+        if yard:
+            result["roofline"]["frac_of_measured_read"] = gbs / yard["hbm_read_GBs"]
         agbs = (kv_bytes + qo_bytes) / (attn_ms * 1e-3) / 1e9
         result["roofline_attention"] = {
             "kernel": "attn_mfma_kernel" if w.dtype == "bf16" else "attn_f32_kernel", "bound": "hbm",
             "achieved": agbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": agbs / HBM_PEAK_GBS, "traffic": None,
             "algorithmic_bytes": kv_bytes + qo_bytes, "avg_kernel_us": attn_ms * 1e3,
             "mfma_tflops": attn_flops / (attn_ms * 1e-3) / 1e12,
-            "mfma_frac_of_peak": attn_flops / (attn_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS}
+            "mfma_frac_of_peak": attn_flops / (attn_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+            "kernel_us_p10_p50_p90": [float(v) * 1e3 for v in np.percentile(attn_all, [10, 50, 90])]}
+        if yard:
+            result["roofline_attention"]["frac_of_measured_read"] = agbs / yard["hbm_read_GBs"]
+            result["roofline_attention"]["mfma_frac_of_measured"] = attn_flops / (attn_ms * 1e-3) / 1e12 / yard["mfma_bf16_TFLOPs"]
+    if yard:
+        result["yardsticks"] = yard
 
     # ---- adaptive depth (Algorithm 1's loop) through the streaming entry points, outside the timed region:
     # begin, then per drafting step expand + E_sub query, then finalize; delta = -1 never stops early, so the

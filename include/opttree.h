@@ -234,6 +234,19 @@ OT_API int ot_kv_append(const ot_attn_params* p, void* K_prefix, void* V_prefix,
                  const int32_t* prefix_len, const int32_t* accept_len, const int32_t* accept_node,
                  int32_t* new_prefix_len, void* hip_stream);
 
+/* ------------------------------------------------------------------------
+ * Yardsticks for the measurement (for callers that rate the kernels above against what this GPU reaches,
+ * not only against published peaks).  Both launch OT_YARDSTICK_WORKGROUPS workgroups of 256 threads.
+ *   ot_yardstick_stream_read  reads `bytes` (a multiple of 16, 16-byte aligned) once, 16 bytes per load;
+ *                             bytes / time = achievable HBM read bandwidth for a buffer larger than the caches;
+ *   ot_yardstick_mfma_loop    per wavefront 4 * iters v_mfma_f32_32x32x16_bf16 on register operands:
+ *                             OT_YARDSTICK_WORKGROUPS * 4 wavefronts * 4 * iters * 32768 flop in total.
+ * `sink` is a device buffer of at least OT_YARDSTICK_WORKGROUPS 4-byte words that keeps the work observable.
+ * ---------------------------------------------------------------------- */
+#define OT_YARDSTICK_WORKGROUPS 2048
+OT_API int ot_yardstick_stream_read(const void* src, size_t bytes, void* sink, void* hip_stream);
+OT_API int ot_yardstick_mfma_loop(int32_t iters, void* sink, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

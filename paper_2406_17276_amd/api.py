@@ -88,6 +88,10 @@ def lib():
         L.ot_verify_greedy.argtypes = [C.POINTER(VerifyParams)] + [C.c_void_p] * 5 + [C.c_size_t] + [C.c_void_p] * 4
         L.ot_kv_append.restype = C.c_int
         L.ot_kv_append.argtypes = [C.POINTER(AttnParams)] + [C.c_void_p] * 9
+        L.ot_yardstick_stream_read.restype = C.c_int
+        L.ot_yardstick_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
+        L.ot_yardstick_mfma_loop.restype = C.c_int
+        L.ot_yardstick_mfma_loop.argtypes = [C.c_int32, C.c_void_p, C.c_void_p]
         L.ot_attn_workspace_bytes.restype = C.c_size_t
         L.ot_attn_workspace_bytes.argtypes = [C.POINTER(AttnParams)]
         L.ot_attn_workspace_prepare.restype = C.c_int

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libopttree.so")
-SOURCES = ["api.hip", "row_scan.hip", "tree_select.hip", "tree_attn.hip", "verify.hip"]
+SOURCES = ["api.hip", "row_scan.hip", "tree_select.hip", "tree_attn.hip", "verify.hip", "yardstick.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",

@@ -1,0 +1,74 @@
+// Two yardstick kernels for the measurement: what this GPU reaches on a plain streaming read and on a
+// register-only bf16 MFMA loop, so that the hot kernels can be rated against measured ceilings as well as
+// against the published peaks.
+#include "common.hpp"
+
+namespace ot {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+// every thread reads 16-byte vectors with a grid stride and keeps a running XOR; one word per workgroup is
+// written so that the loads cannot be dropped
+__global__ __launch_bounds__(256) void stream_read_kernel(const u32x4* src, size_t vectors, unsigned int* sink) {
+    u32x4 acc = {0u, 0u, 0u, 0u};
+    const size_t stride = (size_t)gridDim.x * 256 * 4;
+    for (size_t i = (size_t)blockIdx.x * 256 * 4 + threadIdx.x; i < vectors; i += stride) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const size_t j = i + (size_t)u * 256;
+            if (j < vectors) {
+                const u32x4 w = __builtin_nontemporal_load(src + j);
+                acc.x ^= w.x; acc.y ^= w.y; acc.z ^= w.z; acc.w ^= w.w;
+            }
+        }
+    }
+    const unsigned int v = acc.x ^ acc.y ^ acc.z ^ acc.w;
+    if (v == 0x9e3779b9u) sink[blockIdx.x] = v;            // practically never true; keeps the loads alive
+}
+
+// four independent accumulator chains of v_mfma_f32_32x32x16_bf16 per wavefront, operands in registers
+__global__ __launch_bounds__(256) void mfma_loop_kernel(int iters, float* sink) {
+    bf16x8 a, b;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { a[i] = (__bf16)(0.001f * (threadIdx.x + i)); b[i] = (__bf16)(0.002f * (i + 1)); }
+    f32x16 c0, c1, c2, c3;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { c0[i] = 0.f; c1[i] = 1.f; c2[i] = 2.f; c3[i] = 3.f; }
+    for (int it = 0; it < iters; ++it) {
+        c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c0, 0, 0, 0);
+        c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c1, 0, 0, 0);
+        c2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c2, 0, 0, 0);
+        c3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c3, 0, 0, 0);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s += c0[i] + c1[i] + c2[i] + c3[i];
+    if (s == 12345.678f) sink[0] = s;
+}
+
+}  // namespace
+}  // namespace ot
+
+using namespace ot;
+
+extern "C" {
+
+int ot_yardstick_stream_read(const void* src, size_t bytes, void* sink, void* hip_stream) {
+    if (!src || !sink || bytes < 16 || ((uintptr_t)src % 16) || ((uintptr_t)sink % 4)) return OT_ERR_INVALID_ARG;
+    hipLaunchKernelGGL(stream_read_kernel, dim3(OT_YARDSTICK_WORKGROUPS), dim3(256), 0, (hipStream_t)hip_stream,
+                       (const u32x4*)src, bytes / 16, (unsigned int*)sink);
+    OT_HIP_CHECK(hipGetLastError());
+    return OT_OK;
+}
+
+int ot_yardstick_mfma_loop(int32_t iters, void* sink, void* hip_stream) {
+    if (!sink || iters < 1 || iters > (1 << 24) || ((uintptr_t)sink % 4)) return OT_ERR_INVALID_ARG;
+    hipLaunchKernelGGL(mfma_loop_kernel, dim3(OT_YARDSTICK_WORKGROUPS), dim3(256), 0, (hipStream_t)hip_stream, (int)iters,
+                       (float*)sink);
+    OT_HIP_CHECK(hipGetLastError());
+    return OT_OK;
+}
+
+}  // extern "C"

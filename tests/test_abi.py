@@ -141,3 +141,13 @@ def test_verify_rejects_bad_arguments_without_launching():
     assert L.ot_kv_append(C.byref(ap), None, f, f, f, f, f, f, f, None) == -1
     assert L.ot_kv_append(C.byref(ap), C.c_void_p(0x1004), f, f, f, f, f, f, f, None) == -1
     assert L.ot_kv_append(C.byref(_ap(max_prefix=0)), f, f, f, f, f, f, f, f, None) == -1
+
+
+def test_yardsticks_reject_bad_arguments_without_launching():
+    L = api.lib()
+    f = C.c_void_p(0x1000)
+    assert L.ot_yardstick_stream_read(None, 1 << 20, f, None) == -1
+    assert L.ot_yardstick_stream_read(C.c_void_p(0x1008), 1 << 20, f, None) == -1
+    assert L.ot_yardstick_stream_read(f, 8, f, None) == -1
+    assert L.ot_yardstick_mfma_loop(0, f, None) == -1
+    assert L.ot_yardstick_mfma_loop(10, None, None) == -1
