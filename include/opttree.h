@@ -45,6 +45,7 @@ extern "C" {
 #define OT_MAX_TOPK       16   /* k  */
 #define OT_MAX_DEPTH      32   /* d  */
 #define OT_MAX_HEAD_DIM  128
+#define OT_MAX_TREE_KEYS 512      /* tree keys of the attention when they are more than the query rows */
 #define OT_MASK_WORDS(n) (((n) + 63) / 64)
 
 OT_API int ot_version(void);                       /* 100*major + minor */
@@ -135,6 +136,19 @@ OT_API int ot_tree_finalize(const ot_build_params* p, int32_t steps_done,
  * calls return go_on = 0 for it, and ot_tree_finalize selects among the layers it had when it stopped.
  * The caller ends the loop when no go_on is set or the maximum depth p->depth is reached.
  * Returns OT_ERR_INVALID_ARG for steps_done outside 1..depth, a NaN delta, or null / misaligned pointers. */
+/* Drafting-phase attention masks.  The draft model's forward of a drafting step feeds the frontier (at most n
+ * tokens) and attends to the K/V of everything drafted so far (Sec. 4, last paragraph); its tree attention
+ * mask (Algorithm 2's mask, here per drafting step) is kept incrementally by ot_tree_expand: a node's mask is
+ * its parent's plus its own bit.  Pool index of the node in slot s of the layer made by step t (0-based):
+ * t*n + s -- the row where the caller stores that node's K/V in a [batch][kv_heads][depth*n][head_dim]
+ * tree cache.  ot_tree_frontier_mask, called after the expand of step steps_done-1, writes
+ *   mask[b][s][0..W)  W = OT_MASK_WORDS(depth*n): bit j set iff pool node j is frontier node s or one of its
+ *                     ancestors; rows s >= F are zero,
+ * ready for ot_tree_verify_attention with n_keys = depth*n.  Only for depth*n <= OT_MAX_TREE_KEYS
+ * (OT_ERR_UNSUPPORTED otherwise). */
+OT_API int ot_tree_frontier_mask(const ot_build_params* p, int32_t steps_done,
+                          void* workspace, size_t workspace_bytes, uint64_t* mask, void* hip_stream);
+
 OT_API int ot_tree_esub(const ot_build_params* p, int32_t steps_done, double delta,
                  void* workspace, size_t workspace_bytes,
                  double* e_sub, int32_t* go_on, void* hip_stream);
@@ -163,6 +177,10 @@ typedef struct ot_attn_params {
     int32_t dtype;                      /* OT_F32 | OT_BF16, of Q, K, V and O */
     float   softmax_scale;              /* 0 => 1/sqrt(head_dim) */
     int64_t q_strides[3], kp_strides[3], vp_strides[3], kt_strides[3], vt_strides[3], o_strides[3];
+    int32_t n_keys;                     /* rows of K_tree / V_tree; 0 => n.  Larger than n in the drafting phase,
+                                           where the n frontier nodes attend to all nodes drafted so far
+                                           (Sec. 4: every drafting step feeds n tokens and reuses the K/V
+                                           cache); 1..OT_MAX_TREE_KEYS.  mask is then [batch][n][OT_MASK_WORDS(n_keys)] */
 } ot_attn_params;
 
 OT_API size_t ot_attn_workspace_bytes(const ot_attn_params* p);     /* 0 if p is invalid */

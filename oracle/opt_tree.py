@@ -258,3 +258,21 @@ def build_tree_adaptive(logits: np.ndarray, k: int, n: int, max_depth: int, delt
     out["steps"] = len(b.layers)
     out["e_sub_trace"] = trace
     return out
+
+
+def frontier_masks(layers, n: int, depth: int) -> np.ndarray:
+    """Tree attention mask of the drafting phase (Algorithm 2's mask, for the draft model's forward of the next
+    drafting step): row s belongs to the node in slot s of the last layer and has bit j set iff pool node j is
+    that node or one of its ancestors.  Pool index of (layer made by step t, slot s) = t * n + s.
+    Returns uint64 [n, ceil(depth * n / 64)]; rows past the frontier are zero."""
+    W = (depth * n + 63) // 64
+    out = np.zeros((n, W), dtype=np.uint64)
+    last = len(layers) - 1
+    for s in range(layers[last]["token"].shape[0]):
+        t, slot = last, s
+        while t >= 0:                       # walk up to the root
+            j = t * n + slot
+            out[s, j // 64] |= np.uint64(1) << np.uint64(j % 64)
+            slot = int(layers[t]["parent_slot"][slot])
+            t -= 1
+    return out

@@ -24,15 +24,18 @@ def mask_bit(mask_row: np.ndarray, j: int) -> bool:
 
 
 def tree_verify_attention(Q, K_prefix, V_prefix, K_tree, V_tree, prefix_len, mask, scale=None):
-    """Q [B,Hq,n,D]; K/V_prefix [B,Hkv,Lmax,D]; K/V_tree [B,Hkv,n,D];
-    prefix_len [B]; mask [B,n,ceil(n/64)] uint64.  Returns O [B,Hq,n,D] float64."""
+    """Q [B,Hq,n,D]; K/V_prefix [B,Hkv,Lmax,D]; K/V_tree [B,Hkv,nk,D];
+    prefix_len [B]; mask [B,n,ceil(nk/64)] uint64.  Returns O [B,Hq,n,D] float64.
+    nk = n when the target verifies the tree; nk > n in the drafting phase, where the n tokens fed to the
+    draft model attend to the K/V cache of everything drafted so far (Sec. 4, last paragraph)."""
     Q = np.asarray(Q, dtype=np.float64)
     K_prefix = np.asarray(K_prefix, dtype=np.float64)
     V_prefix = np.asarray(V_prefix, dtype=np.float64)
     K_tree = np.asarray(K_tree, dtype=np.float64)
     V_tree = np.asarray(V_tree, dtype=np.float64)
     B, Hq, n, D = Q.shape
-    Hkv = K_prefix.shape[1]
+    nk = K_tree.shape[2]
+    Hkv = K_tree.shape[1]
     if Hq % Hkv:
         raise ValueError("q_heads must be a multiple of kv_heads")
     g = Hq // Hkv
@@ -45,10 +48,10 @@ def tree_verify_attention(Q, K_prefix, V_prefix, K_tree, V_tree, prefix_len, mas
             hk = h // g
             K = np.concatenate([K_prefix[b, hk, :L], K_tree[b, hk]], axis=0)   # [L+n, D]
             V = np.concatenate([V_prefix[b, hk, :L], V_tree[b, hk]], axis=0)
-            logits = scale * (Q[b, h] @ K.T)                                   # [n, L+n]
+            logits = scale * (Q[b, h] @ K.T)                                   # [n, L+nk]
             for i in range(n):
-                visible = np.ones(L + n, dtype=bool)
-                for j in range(n):
+                visible = np.ones(L + nk, dtype=bool)
+                for j in range(nk):
                     visible[L + j] = mask_bit(mask[b, i], j)
                 if not visible.any():
                     continue          # a node with no visible key (empty mask row, no prefix)

@@ -42,7 +42,8 @@ class AttnParams(C.Structure):
     _fields_ = [("batch", C.c_int32), ("q_heads", C.c_int32), ("kv_heads", C.c_int32), ("head_dim", C.c_int32),
                 ("n", C.c_int32), ("max_prefix", C.c_int32), ("dtype", C.c_int32), ("softmax_scale", C.c_float),
                 ("q_strides", C.c_int64 * 3), ("kp_strides", C.c_int64 * 3), ("vp_strides", C.c_int64 * 3),
-                ("kt_strides", C.c_int64 * 3), ("vt_strides", C.c_int64 * 3), ("o_strides", C.c_int64 * 3)]
+                ("kt_strides", C.c_int64 * 3), ("vt_strides", C.c_int64 * 3), ("o_strides", C.c_int64 * 3),
+                ("n_keys", C.c_int32)]
 
 
 class VerifyParams(C.Structure):
@@ -79,6 +80,9 @@ def lib():
         L.ot_tree_finalize.restype = C.c_int
         L.ot_tree_finalize.argtypes = [C.POINTER(BuildParams), C.c_int32, C.c_void_p, C.c_size_t,
                                        C.POINTER(TreeOut), C.c_void_p]
+        L.ot_tree_frontier_mask.restype = C.c_int
+        L.ot_tree_frontier_mask.argtypes = [C.POINTER(BuildParams), C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p,
+                                            C.c_void_p]
         L.ot_tree_esub.restype = C.c_int
         L.ot_tree_esub.argtypes = [C.POINTER(BuildParams), C.c_int32, C.c_double, C.c_void_p, C.c_size_t,
                                    C.c_void_p, C.c_void_p, C.c_void_p]
@@ -207,6 +211,16 @@ class TreeStream:
         self.step += 1
         return self.frontier_token, self.frontier_parent
 
+    def frontier_mask(self):
+        """ot_tree_frontier_mask after the latest expand: int64 [B, n, W] (bit pattern of the uint64 words),
+        W = ceil(depth * n / 64), over pool indices step * n + slot."""
+        import torch
+        W = (self.p.depth * self.p.n + 63) // 64
+        m = torch.empty((self.p.batch, self.p.n, W), dtype=torch.int64, device=self.ws.device)
+        _check(lib().ot_tree_frontier_mask(C.byref(self.p), self.step, self.ws.data_ptr(), self.ws.numel(),
+                                           m.data_ptr(), _stream()), "ot_tree_frontier_mask")
+        return m
+
     def e_sub(self, delta: float):
         """ot_tree_esub after the latest expand: (E_sub per sequence, go-on flag per sequence), device tensors."""
         import torch
@@ -239,8 +253,9 @@ def attn_params(Q, K_prefix, V_prefix, K_tree, V_tree, max_prefix=None, softmax_
             raise ValueError("last dimension must be contiguous")
         return (C.c_int64 * 3)(t.stride(0), t.stride(1), t.stride(2))
 
+    n_keys = K_tree.shape[2]
     return AttnParams(B, Hq, Hkv, D, n, max_prefix, _dtype_code(Q), float(softmax_scale),
-                      st(Q), st(K_prefix), st(V_prefix), st(K_tree), st(V_tree), st(Q))
+                      st(Q), st(K_prefix), st(V_prefix), st(K_tree), st(V_tree), st(Q), 0 if n_keys == n else n_keys)
 
 
 def attn_workspace_bytes(p: AttnParams) -> int:

@@ -54,6 +54,8 @@ struct BuildWorkspace {
     double* seq_E;                  // [batch]             streaming state: E of Algorithm 1's loop
     int32_t* seq_steps;             // [batch]             layers drafted (frozen when the loop has stopped)
     int32_t* seq_active;            // [batch]             0 once E_sub - E <= delta was seen
+    uint64_t* front_mask;           // [2][batch][n][8]    ancestor masks of the last two frontiers over pool
+                                    //                     indices; null when depth * n > OT_MAX_TREE_KEYS
     size_t bytes;
 };
 BuildWorkspace carve_build_workspace(const ot_build_params& p, void* base);
@@ -84,6 +86,8 @@ int launch_tree_step(const SelectGeometry& g, int step, const BuildWorkspace& ws
 int launch_tree_finalize(const SelectGeometry& g, int steps_done, const BuildWorkspace& ws, const ot_tree_out& out,
                          hipStream_t s);
 int launch_tree_begin(const SelectGeometry& g, const BuildWorkspace& ws, hipStream_t s);
+int launch_tree_front_mask(const SelectGeometry& g, int steps_done, const BuildWorkspace& ws, uint64_t* mask_out,
+                           int mask_words, hipStream_t s);
 int launch_tree_esub(const SelectGeometry& g, int steps_done, double delta, const BuildWorkspace& ws, double* e_sub,
                      int32_t* go_on, hipStream_t s);
 

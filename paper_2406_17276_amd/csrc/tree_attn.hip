@@ -40,6 +40,8 @@ namespace {
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr int kMaxSplits = 32;
+constexpr int kMaskWords = OT_MASK_WORDS(OT_MAX_TREE_KEYS);   // 64-bit words of a mask row
+static_assert(kMaskWords == 8, "mask rows are held in eight registers");
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
@@ -54,7 +56,7 @@ struct AttnKArgs {
     unsigned int* counters;   // one ticket counter per (sequence, KV head, row block), zero between launches
     float* part_o;      // per-split partial O   (layout: see the kernel that writes it)
     float* part_ml;     // per-split (m, l)
-    int batch, q_heads, kv_heads, g, n, D, max_prefix, splits, W, dtype, row_blocks;
+    int batch, q_heads, kv_heads, g, n, nk, D, max_prefix, splits, W, dtype, row_blocks;   // n query rows, nk tree keys
     float scale_log2;   // softmax scale * log2(e)
     long long qs[3], kps[3], vps[3], kts[3], vts[3], os[3];
 };
@@ -147,13 +149,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         for (int s = 0; s < SLABS; ++s) qw[s] = *(const u32x4*)(qrow + 16 * s + 8 * h);
     }
     // this lane's ancestor mask row
-    uint64_t mrow[4] = {0ull, 0ull, 0ull, 0ull};
+    uint64_t mrow[kMaskWords] = {0ull, 0ull, 0ull, 0ull, 0ull, 0ull, 0ull, 0ull};
 #pragma unroll
-    for (int w = 0; w < 4; ++w)
+    for (int w = 0; w < kMaskWords; ++w)
         if (w < a.W) mrow[w] = a.mask[((long long)b * n + node) * a.W + w];
 
     const int L = clamp_len(a.prefix_len[b], a.max_prefix);
-    const int ptiles = (L + TK - 1) / TK, ttiles = (n + TK - 1) / TK;
+    const int ptiles = (L + TK - 1) / TK, ttiles = (a.nk + TK - 1) / TK;
     int t0, t1;
     split_range(ptiles + ttiles, a.splits, split, t0, t1);
 
@@ -197,7 +199,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     auto request_tile = [&](int t, int buf) {
         const bool tree = t >= ptiles;
         const int key0 = tree ? (t - ptiles) * TK : t * TK;
-        const int last = (tree ? n : L) - 1;
+        const int last = (tree ? a.nk : L) - 1;
         const long long ks = tree ? a.kts[2] : a.kps[2];
         const long long vs = tree ? a.vts[2] : a.vps[2];
         const unsigned short* kbase = tree ? kt : kp;
@@ -238,7 +240,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
     for (int s = 0; s < SLABS; ++s) asm volatile("" : "+v"(qw[s]));
 #pragma unroll
-    for (int w = 0; w < 4; ++w) asm volatile("" : "+v"(mrow[w]));
+    for (int w = 0; w < kMaskWords; ++w) asm volatile("" : "+v"(mrow[w]));
     bf16x8 qf[SLABS];
 #pragma unroll
     for (int s = 0; s < SLABS; ++s) qf[s] = __builtin_bit_cast(bf16x8, qw[s]);
@@ -264,7 +266,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 
         const bool tree = t >= ptiles;
         const int key0 = tree ? (t - ptiles) * TK : t * TK;
-        const int kend = tree ? n : L;
+        const int kend = tree ? a.nk : L;
 
         // one 32-key block at a time: S^T = K Q^T, online softmax, O^T += V^T P^T
 #pragma unroll
@@ -285,7 +287,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                 for (int v = 0; v < 16; ++v) {
                     const int key = key0 + 32 * kbi + 8 * (v >> 2) + 4 * h + (v & 3);
                     bool ok = key < kend;
-                    if (tree) ok = ok && ((mrow[(key >> 6) & 3] >> (key & 63)) & 1ull);
+                    if (tree) ok = ok && ((mrow[(key >> 6) & (kMaskWords - 1)] >> (key & 63)) & 1ull);
                     sacc[v] = ok ? sacc[v] : -INFINITY;
                 }
             }
@@ -520,7 +522,7 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const AttnKArgs a) {
     const int hk = hq / a.g;
     const int n = a.n;
     const int L = clamp_len(a.prefix_len[b], a.max_prefix);
-    const int ptiles = (L + TK - 1) / TK, ttiles = (n + TK - 1) / TK;
+    const int ptiles = (L + TK - 1) / TK, ttiles = (a.nk + TK - 1) / TK;
     int t0, t1;
     split_range(ptiles + ttiles, a.splits, split, t0, t1);
     const int node = rb * RB + r;
@@ -533,7 +535,7 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const AttnKArgs a) {
         if (rb * RB + rr < n) w = *(const f32x4*)(qbase + (long long)(rb * RB + rr) * a.qs[2] + cc);
         *(f32x4*)(s_q + rr * D + cc) = w;
     }
-    uint64_t mrow[4] = {0ull, 0ull, 0ull, 0ull};
+    uint64_t mrow[kMaskWords] = {0ull, 0ull, 0ull, 0ull, 0ull, 0ull, 0ull, 0ull};
     if (row_ok)
         for (int w = 0; w < a.W; ++w) mrow[w] = a.mask[((long long)b * n + node) * a.W + w];
 
@@ -550,7 +552,7 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const AttnKArgs a) {
     for (int t = t0; t < t1; ++t) {
         const bool tree = t >= ptiles;
         const int key0 = tree ? (t - ptiles) * TK : t * TK;
-        const int kend = tree ? n : L;
+        const int kend = tree ? a.nk : L;
         const float* kb = tree ? kt : kp;
         const float* vb = tree ? vt : vp;
         const long long ks = tree ? a.kts[2] : a.kps[2];
@@ -712,7 +714,8 @@ AttnPlan plan_attention(const ot_attn_params& p) {
         tile = 32;
         splits = (512 + base - 1) / base;
     }
-    const int max_tiles = (p.max_prefix + tile - 1) / tile + (p.n + tile - 1) / tile;
+    const int nk = p.n_keys > 0 ? p.n_keys : p.n;
+    const int max_tiles = (p.max_prefix + tile - 1) / tile + (nk + tile - 1) / tile;
     if (splits > max_tiles) splits = max_tiles;
     if (splits > kMaxSplits) splits = kMaxSplits;
     if (splits < 1) splits = 1;
@@ -738,8 +741,8 @@ int launch_tree_attention(const ot_attn_params& p, const AttnPlan& plan, const v
     a.part_o = (float*)((char*)workspace + OT_ATTN_SYNC_BYTES);
     a.part_ml = (float*)((char*)workspace + OT_ATTN_SYNC_BYTES + plan.part_o_bytes);
     a.batch = p.batch; a.q_heads = p.q_heads; a.kv_heads = p.kv_heads; a.g = p.q_heads / p.kv_heads;
-    a.n = p.n; a.D = p.head_dim; a.max_prefix = p.max_prefix; a.splits = plan.splits;
-    a.W = OT_MASK_WORDS(p.n); a.dtype = p.dtype;
+    a.n = p.n; a.nk = p.n_keys > 0 ? p.n_keys : p.n; a.D = p.head_dim; a.max_prefix = p.max_prefix; a.splits = plan.splits;
+    a.W = OT_MASK_WORDS(a.nk); a.dtype = p.dtype;
     const float scale = p.softmax_scale != 0.f ? p.softmax_scale : 1.0f / sqrtf((float)p.head_dim);
     a.scale_log2 = scale * kLog2e;
     for (int i = 0; i < 3; ++i) {
@@ -798,6 +801,8 @@ static int validate_attn(const ot_attn_params* p) {
     if (!(p->softmax_scale >= 0.f)) return OT_ERR_INVALID_ARG;
     if (p->head_dim != 64 && p->head_dim != 128) return OT_ERR_UNSUPPORTED;
     if (p->n > OT_MAX_NODES) return OT_ERR_UNSUPPORTED;
+    if (p->n_keys < 0) return OT_ERR_INVALID_ARG;
+    if (p->n_keys > OT_MAX_TREE_KEYS) return OT_ERR_UNSUPPORTED;
     if ((long long)p->batch * p->q_heads > 65535 || (long long)p->batch * p->q_heads * p->n > 0x7fffffffLL)
         return OT_ERR_UNSUPPORTED;
     const int vec = p->dtype == OT_BF16 ? 8 : 4;

@@ -31,6 +31,10 @@ struct SelKArgs {
     double* pool_p;                                           // [batch][depth][n]  (streaming state) p^ of every pool node
     double* seq_E; int32_t* seq_steps; int32_t* seq_active;   // [batch]            (streaming state) adaptive depth
     double* e_sub; int32_t* go_on; double delta;              // outputs / threshold of the E_sub query
+    u64* front_mask;                                          // [2][batch][n][8] (streaming state) or null: ancestor
+                                                              // masks of the last two frontiers over pool indices
+    u64* mask_out; int mask_words;                            // output of the frontier-mask query
+    int gridDim_batch;                                        // batch size (the grid of these kernels)
     ot_tree_out out;
     int32_t* frontier_token; int32_t* frontier_parent;        // [batch][n]         (streaming step)
     int step;
@@ -666,6 +670,24 @@ __global__ __launch_bounds__(256) void tree_step_kernel(const SelKArgs a) {
             a.frontier_parent[(size_t)b * n + off + r] = tid;
         }
     }
+    // ancestor masks of the new frontier over pool indices (layer t+1, slot s) -> t n + s: the parent's mask
+    // plus the node's own bit (Algorithm 2's mask, built incrementally for the drafting phase)
+    if (a.front_mask) {
+        const size_t fm = (size_t)a.gridDim_batch * n * 8;
+        const u64* prev = a.front_mask + (size_t)((t & 1) ^ 1) * fm + ((size_t)b * n + tid) * 8;
+        u64* cur = a.front_mask + (size_t)(t & 1) * fm + (size_t)b * n * 8;
+        u64 pm[8];
+#pragma unroll
+        for (int w = 0; w < 8; ++w) pm[w] = (t > 0 && active) ? prev[w] : 0ull;
+#pragma unroll
+        for (int r = 0; r < KMAX; ++r) {
+            if (r < cnt) {
+                const int idx = t * n + off + r;
+#pragma unroll
+                for (int w = 0; w < 8; ++w) cur[(size_t)(off + r) * 8 + w] = pm[w] | (w == (idx >> 6) ? 1ull << (idx & 63) : 0ull);
+            }
+        }
+    }
 }
 
 template <int DMAX, bool SINGLE>
@@ -731,6 +753,19 @@ __global__ __launch_bounds__(256) void tree_esub_kernel(const SelKArgs a) {
             if (go) a.seq_E[b] = e; else a.seq_active[b] = 0;
         }
         a.go_on[b] = go;
+    }
+}
+
+// The frontier's ancestor masks, from the state the step kernel keeps: mask_out [batch][n][mask_words]
+__global__ __launch_bounds__(256) void tree_front_mask_kernel(const SelKArgs a) {
+    const int b = blockIdx.x, n = a.n;
+    const int steps = a.step < a.seq_steps[b] ? a.step : a.seq_steps[b];
+    const int F = steps > 0 ? a.F[steps] : 0;
+    const size_t fm = (size_t)a.gridDim_batch * n * 8;
+    const u64* src = a.front_mask + (size_t)((steps - 1) & 1) * fm + (size_t)b * n * 8;
+    for (int i = threadIdx.x; i < n * a.mask_words; i += blockDim.x) {
+        const int s = i / a.mask_words, w = i - s * a.mask_words;
+        a.mask_out[(size_t)b * n * a.mask_words + i] = (s < F && w < 8) ? src[(size_t)s * 8 + w] : 0ull;
     }
 }
 
@@ -1172,6 +1207,7 @@ SelKArgs make_args(const SelectGeometry& g, const BuildWorkspace& ws) {
     a.pool_key = ws.pool_key; a.pool_tok = ws.pool_tok; a.pool_par = ws.pool_par; a.step_tau = ws.step_tau;
     a.pool_p = ws.pool_p; a.seq_E = ws.seq_E; a.seq_steps = ws.seq_steps; a.seq_active = ws.seq_active;
     a.e_sub = nullptr; a.go_on = nullptr; a.delta = 0.0;
+    a.front_mask = (u64*)ws.front_mask; a.mask_out = nullptr; a.mask_words = 0; a.gridDim_batch = g.batch;
     a.out = ot_tree_out{nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
     a.frontier_token = nullptr; a.frontier_parent = nullptr;
     a.step = 0;
@@ -1318,6 +1354,16 @@ int launch_tree_esub(const SelectGeometry& g, int steps_done, double delta, cons
     if (steps_done <= 8) return launch_esub_t<8, false>(a, g.batch, NT, s);
     if (steps_done <= 16) return launch_esub_t<16, false>(a, g.batch, NT, s);
     return launch_esub_t<32, false>(a, g.batch, NT, s);
+}
+
+int launch_tree_front_mask(const SelectGeometry& g, int steps_done, const BuildWorkspace& ws, uint64_t* mask_out,
+                           int mask_words, hipStream_t s) {
+    SelKArgs a = make_args(g, ws);
+    if (!a.front_mask) return OT_ERR_UNSUPPORTED;
+    a.step = steps_done; a.mask_out = (u64*)mask_out; a.mask_words = mask_words;
+    hipLaunchKernelGGL(tree_front_mask_kernel, dim3(g.batch), dim3(256), 0, s, a);
+    OT_HIP_CHECK(hipGetLastError());
+    return OT_OK;
 }
 
 int launch_tree_finalize(const SelectGeometry& g, int steps_done, const BuildWorkspace& ws, const ot_tree_out& out,

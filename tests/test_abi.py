@@ -82,6 +82,9 @@ def test_attention_rejects_bad_arguments_without_launching():
     assert api.attn_workspace_bytes(_ap(head_dim=96)) == 0
     assert api.attn_workspace_bytes(_ap(n=0)) == 0
     assert api.attn_workspace_bytes(_ap(n=257)) == 0
+    assert api.attn_workspace_bytes(_ap(n_keys=513)) == 0
+    assert api.attn_workspace_bytes(_ap(n_keys=-1)) == 0
+    assert api.attn_workspace_bytes(_ap(n_keys=300)) > 0
     assert api.attn_workspace_bytes(_ap(q_strides=s(4096, 1024, 62))) == 0
     f = C.c_void_p(0x1000)
     p = _ap()
@@ -151,3 +154,15 @@ def test_yardsticks_reject_bad_arguments_without_launching():
     assert L.ot_yardstick_stream_read(f, 8, f, None) == -1
     assert L.ot_yardstick_mfma_loop(0, f, None) == -1
     assert L.ot_yardstick_mfma_loop(10, None, None) == -1
+
+
+def test_frontier_mask_rejects_bad_arguments_without_launching():
+    L = api.lib()
+    L.ot_tree_frontier_mask.restype = C.c_int
+    p = _bp()
+    need = api.build_workspace_bytes(p)
+    f = C.c_void_p(0x1000)
+    assert L.ot_tree_frontier_mask(C.byref(p), 0, f, need, f, None) == -1
+    assert L.ot_tree_frontier_mask(C.byref(p), 1, f, need, None, None) == -1
+    assert L.ot_tree_frontier_mask(C.byref(p), 1, f, need - 1, f, None) == -3
+    assert L.ot_tree_frontier_mask(C.byref(_bp(n=200, depth=4)), 1, f, 1 << 30, f, None) == -2      # 800 pool nodes

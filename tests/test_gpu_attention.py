@@ -177,3 +177,33 @@ def test_one_workspace_serves_consecutive_calls():
         want = _oracle_attention(x, mask, "bf16")
         assert np.abs(U.from_device_f64(out) - want).max() < 2e-2
         assert int(ws[:4096].view(torch.int32).abs().sum().item()) == 0
+
+
+@pytest.mark.parametrize("dtype,B,Hq,Hkv,D,L,k,n,d,upto", [
+    ("f32", 2, 4, 2, 64, 90, 3, 12, 5, 4),          # 60 pool rows, one mask word
+    ("bf16", 1, 8, 8, 128, 700, 10, 50, 10, 10),     # 7B-shaped drafting step: 50 queries, 500 pool keys, 8 words
+    ("bf16", 2, 8, 2, 128, 300, 6, 40, 8, 6),        # packed GQA rows (128-row workgroups), 320 pool keys
+    ("bf16", 1, 4, 4, 64, 0, 4, 64, 8, 3),           # no prefix, 512 pool keys of which 3 layers are filled
+])
+def test_drafting_phase_attention_frontier_against_pool(dtype, B, Hq, Hkv, D, L, k, n, d, upto):
+    """n frontier queries against the prefix and the K/V of all pool nodes (n_keys = depth * n), with the
+    frontier masks of the drafting phase."""
+    import torch
+    from paper_2406_17276_amd import api
+    g = np.random.default_rng(n + d)
+    masks = []
+    for b in range(B):
+        bld = ot_oracle.TreeBuilder(k, n)
+        for t in range(upto):
+            bld.expand(g.standard_normal((bld.frontier_score.shape[0], 200)) * 2.0)
+        masks.append(ot_oracle.frontier_masks(bld.layers, n, d))
+    mask = np.stack(masks)
+    w = _shape(dtype, B, Hq, Hkv, D, L, n, 0.2 if L else 0.0)
+    x = wl.make_attention_inputs(w, 21)
+    nk = d * n
+    x["K_tree"] = wl.store(g.standard_normal((B, Hkv, nk, D)).astype(np.float32), dtype)
+    x["V_tree"] = wl.store(g.standard_normal((B, Hkv, nk, D)).astype(np.float32), dtype)
+    got = _gpu_attention(x, mask, dtype)
+    want = _oracle_attention(x, mask, dtype)
+    assert np.abs(got - want).max() < TOL[dtype]
+    assert np.abs(want).max() > 0.01

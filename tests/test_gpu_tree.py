@@ -227,3 +227,25 @@ def test_adaptive_depth_matches_oracle():
     got = stream.finalize()
     torch.cuda.synchronize()
     U.assert_tree_equal(got, want, n)
+
+
+def test_frontier_masks_of_the_drafting_phase_match_oracle():
+    """ot_tree_frontier_mask after every expand: the incrementally kept ancestor masks over pool indices."""
+    import torch
+    from paper_2406_17276_amd import api
+    V, k, n, d, B = 1500, 4, 40, 7, 3                      # 280 pool indices: five mask words
+    g = np.random.default_rng(5)
+    x = (g.standard_normal((B, d, n, V)) * 3.0).astype(np.float32)
+    builders = [ot_oracle.TreeBuilder(k, n) for _ in range(B)]
+    stream = api.TreeStream(B, V, k, n, d, api.OT_F32)
+    dev = torch.from_numpy(x).cuda()
+    for t in range(d):
+        stream.expand(dev[:, t])
+        m = stream.frontier_mask()
+        torch.cuda.synchronize()
+        m = m.cpu().numpy().view(np.uint64)
+        for b in range(B):
+            F = builders[b].frontier_score.shape[0]
+            builders[b].expand(x[b, t, :F].astype(np.float64))
+            np.testing.assert_array_equal(m[b], ot_oracle.frontier_masks(builders[b].layers, n, d))
+    assert min(min(bld.cut_gaps) for bld in builders) > U.GAP

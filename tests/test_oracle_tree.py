@@ -309,3 +309,44 @@ def test_adaptive_depth_trace_obeys_the_loop_condition():
         assert np.all(gains[:-1] > delta)                       # every step but the last was licensed
         if out["steps"] < dmax:
             assert gains[-1] <= delta                           # stopped because the gain fell to delta or below
+
+
+def test_frontier_masks_agree_with_the_ancestor_mask_of_the_whole_pool():
+    # the pool of all layers is itself a tree; relabel its nodes densely (layer by layer), take the pinned
+    # ancestor_mask of that tree and map the bits back to pool indices t * n + slot
+    V, k, n, d = 30, 3, 7, 5
+    out = ot.build_tree(_random_logits(V, k, n, d, 13), k, n, d)
+    layers = out["layers"]
+    dense, parent = {}, []
+    for t, layer in enumerate(layers):
+        for s in range(layer["token"].shape[0]):
+            dense[(t, s)] = len(parent)
+            parent.append(-1 if t == 0 else dense[(t - 1, int(layer["parent_slot"][s]))])
+    am = ot.ancestor_mask(np.array(parent))
+    pool_index = {v: t * n + s for (t, s), v in dense.items()}
+    for upto in range(1, d + 1):
+        got = ot.frontier_masks(layers[:upto], n, d)
+        F = layers[upto - 1]["token"].shape[0]
+        for s in range(n):
+            want = set()
+            if s < F:
+                row = am[dense[(upto - 1, s)]]
+                want = {pool_index[j] for j in range(len(parent)) if (int(row[j // 64]) >> (j % 64)) & 1}
+            have = {j for j in range(d * n) if (int(got[s, j // 64]) >> (j % 64)) & 1}
+            assert have == want
+            if s < F:
+                assert len(have) == upto            # itself and one ancestor per earlier layer
+
+
+def test_attention_oracle_with_more_tree_keys_than_queries_reduces_to_the_square_case():
+    # padding the tree K/V with rows no mask bit points at must not change anything
+    from oracle import tree_attention as ta
+    g = np.random.default_rng(3)
+    B, H, n, D, L, extra = 1, 2, 5, 8, 6, 9
+    Q, Kp, Vp = g.standard_normal((B, H, n, D)), g.standard_normal((B, H, L, D)), g.standard_normal((B, H, L, D))
+    Kt, Vt = g.standard_normal((B, H, n, D)), g.standard_normal((B, H, n, D))
+    mask = ot.ancestor_mask(np.array([-1, 0, 0, 1, 3]))[None]
+    ref = ta.tree_verify_attention(Q, Kp, Vp, Kt, Vt, [L], mask)
+    Kt2 = np.concatenate([Kt, g.standard_normal((B, H, extra, D))], axis=2)
+    Vt2 = np.concatenate([Vt, g.standard_normal((B, H, extra, D))], axis=2)
+    np.testing.assert_allclose(ta.tree_verify_attention(Q, Kp, Vp, Kt2, Vt2, [L], mask), ref, rtol=0, atol=1e-15)
