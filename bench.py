@@ -351,6 +351,29 @@ def main():
                                    "calls": "ot_verify_greedy + ot_kv_append",
                                    "target_rows": w.batch * (w.n + 1), "target_bytes": w.batch * (w.n + 1) * w.vocab * w.elem_bytes()}
 
+    # ---- drafting-phase attention of the same shape, outside the timed region: the n frontier tokens against the
+    # prefix and the K/V of all depth*n pool nodes (the draft model's attention of the last drafting step)
+    if args.mode == "stream" and not args.main_only and w.depth * w.n <= 512 and w.dtype == "bf16":
+        gd = torch.Generator(device="cuda"); gd.manual_seed(seed + 555)
+        nk = w.depth * w.n
+        ktp = torch.randn((w.batch, w.kv_heads, nk, w.head_dim), generator=gd, device="cuda").to(torch.bfloat16)
+        vtp = torch.randn((w.batch, w.kv_heads, nk, w.head_dim), generator=gd, device="cuda").to(torch.bfloat16)
+        ts2 = api.TreeStream(w.batch, w.vocab, w.k, w.n, w.depth, api.OT_BF16)
+        for t in range(w.depth):
+            ts2.expand(builds[0].logits[:, t])
+        fmask = ts2.frontier_mask()
+        q0 = attns[0].keep[0]
+        pd = api.PreparedAttention(q0, attns[0].keep[1], attns[0].keep[2], ktp, vtp, plen_d, fmask)
+        for _ in range(5):
+            pd(stream)
+        torch.cuda.synchronize()
+        td = time.perf_counter()
+        for _ in range(200):
+            pd(stream)
+        torch.cuda.synchronize()
+        result["draft_phase_attention"] = {"us_per_call": (time.perf_counter() - td) * 1e6 / 200, "queries": w.n,
+                                           "tree_keys": nk, "prefix": w.prefix, "note": "warm inputs"}
+
     # ---- CPU oracle on a bounded sample of the same workload ----------------------------------
     if args.cpu_steps > 0:
         from threadpoolctl import threadpool_limits
