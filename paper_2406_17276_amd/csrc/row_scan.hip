@@ -125,14 +125,17 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu((NT == 1024 
     for (int i = 1; i < VPL; ++i) m = fmaxf(m, vmax[i]);
     const float rmax = row16_max(m);                  // max of this lane's row of 16 lanes
     const float m_w = fmaxf(fmaxf(rl_f(rmax, 0), rl_f(rmax, 16)), fmaxf(rl_f(rmax, 32), rl_f(rmax, 48)));
+    // e^(x - m) = 2^(x log2e - mc) with mc = fl(m log2e): one fma per element.  mc is carried along as the
+    // wave's reference exponent, so its rounding cancels when the partial sums are combined.
+    const float mc_w = m_w * kLog2e;
     float acc[4] = {0.f, 0.f, 0.f, 0.f};
     if (m_w > -INFINITY) {
 #pragma unroll
-        for (int i = 0; i < EPL; ++i) acc[i & 3] += __builtin_amdgcn_exp2f((x[i] - m_w) * kLog2e);
+        for (int i = 0; i < EPL; ++i) acc[i & 3] += __builtin_amdgcn_exp2f(fmaf(x[i], kLog2e, -mc_w));
     }
     const double s_w = wave_sum_d((double)(acc[0] + acc[1]) + (double)(acc[2] + acc[3]));
     const int lane = tid & 63, wave = tid >> 6;
-    if (lane == 0) { s_wm[wave] = m_w; s_ws[wave] = s_w; }
+    if (lane == 0) { s_wm[wave] = mc_w; s_ws[wave] = s_w; }     // (reference exponent in log2 units, sum)
     // 16 group maxima: a group is 1/16th of the workgroup (a wavefront, half of one, or a row of 16 lanes)
     if (NT == 1024)     { if (lane == 0) s_gmax[wave] = m_w; }
     else if (NT == 512) { if (lane == 0) { s_gmax[2 * wave] = fmaxf(rl_f(rmax, 0), rl_f(rmax, 16));
@@ -191,14 +194,16 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu((NT == 1024 
         M = fmaxf(M, __int_as_float(dpp_i<DPP_QUAD_XOR2>(__float_as_int(M), __float_as_int(M))));
         M = fmaxf(M, __int_as_float(dpp_i<DPP_ROW_HALF_MIRROR>(__float_as_int(M), __float_as_int(M))));
         M = fmaxf(M, __int_as_float(dpp_i<DPP_ROW_MIRROR>(__float_as_int(M), __float_as_int(M))));
-        double part_sum = (have && mw > -INFINITY) ? s_ws[lane] * (double)__builtin_amdgcn_exp2f((mw - M) * kLog2e) : 0.0;
+        double part_sum = (have && mw > -INFINITY) ? s_ws[lane] * (double)__builtin_amdgcn_exp2f(mw - M) : 0.0;
         part_sum += dpp_d<DPP_QUAD_XOR1>(part_sum);
         part_sum += dpp_d<DPP_QUAD_XOR2>(part_sum);
         part_sum += dpp_d<DPP_ROW_HALF_MIRROR>(part_sum);
         part_sum += dpp_d<DPP_ROW_MIRROR>(part_sum);
         if (lane == 0) {
             if (a.parts == 1) {
-                a.row_lse[rid] = (double)M + log(part_sum);
+                // the terms are 2^(x c - M) with c = the fp32 constant, i.e. e^((x - M / c) c / log2e): dividing
+                // M by the same c puts the reference back into natural-log units without a bias in the constant
+                a.row_lse[rid] = (double)M / (double)kLog2e + log(part_sum);
             } else {
                 a.part_m[wg] = M;
                 a.part_s[wg] = part_sum;
@@ -305,11 +310,12 @@ __global__ void merge_parts_kernel(int rows, int parts, int k, const float* part
     const int rid = blockIdx.x * blockDim.x + threadIdx.x;
     if (rid >= rows) return;
     const size_t base = (size_t)rid * parts;
+    // part_m is the part's reference exponent in log2 units (fp32 max times the fp32 log2e of the scan kernel)
     float M = part_m[base];
     for (int p = 1; p < parts; ++p) M = fmaxf(M, part_m[base + p]);
     double s = 0.0;
-    for (int p = 0; p < parts; ++p) s += part_s[base + p] * exp((double)part_m[base + p] - (double)M);
-    row_lse[rid] = (double)M + log(s);
+    for (int p = 0; p < parts; ++p) s += part_s[base + p] * exp2((double)part_m[base + p] - (double)M);
+    row_lse[rid] = (double)M / (double)kLog2e + log(s);
     // k-way merge of sorted lists; heads[] are positions inside each part's list
     int head[8];
     for (int p = 0; p < 8; ++p) head[p] = 0;
@@ -349,9 +355,6 @@ int launch_row_scan(const ScanGeometry& g, const void* logits, const BuildWorksp
     const bool aligned = ((uintptr_t)logits % 16 == 0) && (g.stride_seq % vec == 0) && (g.stride_depth % vec == 0) &&
                          (g.stride_row % vec == 0) && (g.vocab % vec == 0);
     const bool small = a.part_elems <= 256 * 32;
-#ifndef OT_SCAN_WIDE
-#define OT_SCAN_WIDE 0
-#endif
     const long long rows = (long long)g.batch * g.rows_per_seq;
     const long long grid = rows * parts;
     if (grid <= 0 || grid > 0x7fffffffLL) return OT_ERR_UNSUPPORTED;
@@ -364,10 +367,6 @@ int launch_row_scan(const ScanGeometry& g, const void* logits, const BuildWorksp
     } while (0)
     if (g.dtype == OT_BF16) {
         if (small) { if (aligned) OT_SCAN_LAUNCH(OT_BF16, 256, true); else OT_SCAN_LAUNCH(OT_BF16, 256, false); }
-        else if (OT_SCAN_WIDE && aligned) {
-            if (ev0 || ev1) hipExtLaunchKernelGGL((row_scan_kernel<OT_BF16, 512, 64, true>), gd, dim3(512), 0, s, ev0, ev1, 0, a);
-            else hipLaunchKernelGGL((row_scan_kernel<OT_BF16, 512, 64, true>), gd, dim3(512), 0, s, a);
-        }
         else       { if (aligned) OT_SCAN_LAUNCH(OT_BF16, 1024, true); else OT_SCAN_LAUNCH(OT_BF16, 1024, false); }
     } else {
         if (small) { if (aligned) OT_SCAN_LAUNCH(OT_F32, 256, true); else OT_SCAN_LAUNCH(OT_F32, 256, false); }

@@ -1,16 +1,18 @@
-// Tree-masked verification attention (Algorithm 2: the target model's forward over the
-// drafted nodes with the tree attention mask).  For node i of sequence b and query head h:
+// Tree-masked attention (Algorithm 2: the target model's forward over the drafted nodes with the tree
+// attention mask; with n_keys > n also the draft model's attention of a drafting step, Sec. 4).
+// For query row i of sequence b and query head h:
 //   O[i] = sum_j softmax_j(scale q_i.k_j) v_j,  j over the cached prefix and the tree rows
-//   that are i itself or an ancestor of i (bit j of mask[b][i]).
+//   whose bit is set in mask[b][i] (the node itself and its ancestors).
 //
 // The keys of one (sequence, KV head) are cut into 64-key tiles: ceil(L_b/64) prefix tiles,
-// then ceil(n/64) tree tiles.  Contiguous tile ranges ("splits") go to different workgroups so
+// then ceil(n_keys/64) tree tiles.  Contiguous tile ranges ("splits") go to different workgroups so
 // that a single small sequence still fills the chip; every split leaves an un-normalised
-// partial (running max m in log2 units, sum l, O) that attn_combine_kernel merges.
+// partial (running max m, sum l, O).  The bf16 kernel merges the partials itself (the last workgroup
+// of a row block to finish does it), the f32 kernel leaves them to attn_combine_kernel.
 //
-// bf16 path (attn_mfma_kernel): one workgroup = 64 packed query rows of one KV head (GQA: the
-// g = q_heads/kv_heads query heads that share the KV head are stacked, row = head*n + node)
-// and 4 wavefronts = 2 query blocks of 32 rows x 2 halves of each 64-key tile.  Each wavefront
+// bf16 path (attn_mfma_kernel): one workgroup = 64 or 128 packed query rows of one KV head (GQA: the
+// g = q_heads/kv_heads query heads that share the KV head are stacked, row = head*n + node), four
+// wavefronts.  Each wavefront
 //   S^T = K Q^T   v_mfma_f32_32x32x16_bf16, A = K rows from LDS, B = Q held in registers;
 //                 the accumulator leaves every lane with 16 scores of ONE query, so the
 //                 online-softmax statistics and the rescale factor are per-lane scalars;
@@ -18,12 +20,12 @@
 //                 inside a 16-key slab is whatever the accumulator layout gives; V is read in
 //                 the same order), A = V gathered from LDS.
 // K/V tiles go from global memory straight into LDS (global_load_lds_dwordx4: 16 bytes per lane, no
-// register staging), one tile ahead of the computation, into the other half of a double buffer.  A
+// register staging), one or two tiles ahead of the computation, into a ring of two or three buffers.  A
 // wavefront's 64 lanes land on 1 KB of consecutive LDS, so rows are unpadded and bank conflicts are
 // avoided by an XOR swizzle instead: lane -> global chunk is chosen such that 16-byte chunk c of key
 // row r sits at chunk position c ^ (r mod 16) (K), and 32-byte segment g of row r at g ^ (r mod 8) (V).
-// Tiles that are not full (prefix tail, tree tiles) take a register path with zero fill into the same
-// layout.  V is the transposed operand (a lane needs 8 keys of ONE column): it is read with the gfx950
+// Tiles that reach past the end of the keys re-read the last valid row for the missing rows (their scores
+// are masked).  V is the transposed operand (a lane needs 8 keys of ONE column): it is read with the gfx950
 // LDS transpose load ds_read_b64_tr_b16, which lets 16 lanes read four 32-byte row segments and hands
 // lane i the i-th column of that 4x16 block -- two such loads per MFMA operand.
 // The ancestor mask is applied as a bit test on tree tiles only; prefix tiles only mask the tail.
