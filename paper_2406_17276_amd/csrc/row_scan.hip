@@ -213,6 +213,21 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu((NT == 1024 
 
     // ---- 5b. rank the candidates -------------------------------------------
     if (ncand <= kCandCap) {
+        constexpr int PR = NT >= 1024 ? 32 : 16;          // PR x PR pairs fit the workgroup
+        if (ncand <= PR && NT >= PR * PR) {
+            // one (candidate i, rival j) pair per thread: rank of i = rivals that precede it, counted with a ballot
+            const int i = tid / PR, j = tid % PR;
+            if (tid < PR * PR) {
+                const float v = s_cv[i < ncand ? i : 0], u = s_cv[j < ncand ? j : 0];
+                const int id = s_ci[i < ncand ? i : 0], ui = s_ci[j < ncand ? j : 0];
+                const unsigned long long bal = __ballot(j < ncand && (u > v || (u == v && ui < id)));
+                // a wavefront holds 64 / PR candidates, PR consecutive lanes each
+                const int rank = __popcll(PR == 32 ? ((lane & 32) ? (bal >> 32) : (bal & 0xffffffffull))
+                                                   : ((bal >> (lane & 48)) & 0xffffull));
+                if (j == 0 && i < ncand && rank < a.k) { outv[rank] = v; outi[rank] = id; }
+            }
+            return;
+        }
         if (ncand <= 64) {
             if (wave == 0) {          // candidate i sits in lane i; the others are broadcast by v_readlane
                 const float v = lane < ncand ? s_cv[lane] : -INFINITY;
