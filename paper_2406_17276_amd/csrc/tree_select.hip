@@ -794,6 +794,23 @@ __device__ __forceinline__ double wave_max_d(double v) {
     return fmax(fmax(rl_d(v, 0), rl_d(v, 16)), fmax(rl_d(v, 32), rl_d(v, 48)));
 }
 
+// Bounds of a bracket do not have to be tight, only safe: a value not above the smallest (not below the
+// largest) of the lanes' doubles, from an fp32 reduction (one DPP instruction per stage) widened by more
+// than the conversion error.  NaN lanes are ignored; all NaN gives NaN.
+__device__ __forceinline__ double wave_lower_bound(double v) {
+    float f = (float)v;
+    f = fminf(f, __int_as_float(dpp_i<DPP_QUAD_XOR1>(__float_as_int(f), __float_as_int(f))));
+    f = fminf(f, __int_as_float(dpp_i<DPP_QUAD_XOR2>(__float_as_int(f), __float_as_int(f))));
+    f = fminf(f, __int_as_float(dpp_i<DPP_ROW_HALF_MIRROR>(__float_as_int(f), __float_as_int(f))));
+    f = fminf(f, __int_as_float(dpp_i<DPP_ROW_MIRROR>(__float_as_int(f), __float_as_int(f))));
+    const float m = fminf(fminf(rl_f(f, 0), rl_f(f, 16)), fminf(rl_f(f, 32), rl_f(f, 48)));
+    return (double)m - (fabs((double)m) * 1.2e-7 + 1e-30);
+}
+__device__ __forceinline__ double wave_upper_bound(double v) {
+    const float m = wave_max_f((float)v);
+    return (double)m + (fabs((double)m) * 1.2e-7 + 1e-30);
+}
+
 // The cut bucket of a 256-bin histogram (one wavefront; lane L scans bins 4L..4L+3 and clears them):
 // B = the bin that holds the T-th largest key, above = keys in higher bins, inb = keys in bin B,
 // total = all keys.  B = -1 if there are fewer than T keys.
@@ -847,7 +864,7 @@ __device__ __forceinline__ SortedCut cut_sorted(const double (&ck)[M], double* k
                                                 int lane, Group<true>& g) {
     SortedCut out;
     out.exact = false; out.tau = lo; out.need = 0; out.total_eq = 0;
-    const double gmax = wave_max_d(ck[0]);
+    const double gmax = wave_upper_bound(ck[0]);       // only the bracket's upper end: need not be a key
     int a = 0, b = 0;
 #pragma unroll
     for (int r = 0; r < M; ++r) b += ck[r] >= lo ? 1 : 0;
@@ -856,7 +873,7 @@ __device__ __forceinline__ SortedCut cut_sorted(const double (&ck)[M], double* k
         // u = (key - lo) * scale lies in [0, 256) for every key in [lo, gmax]; the factor below 256 absorbs
         // the error of the approximate reciprocal.  Keys below lo or absent give u <= 0 or NaN -> bin 0,
         // and are kept out by the prefix length b.
-        const double scale = 255.9 * __builtin_amdgcn_rcp(next_up(gmax) - lo);
+        const double scale = 255.9 * __builtin_amdgcn_rcp(gmax - lo);
         double u[M];
 #pragma unroll
         for (int r = 0; r < M; ++r) u[r] = (ck[r] - lo) * scale;
@@ -915,7 +932,7 @@ __device__ __forceinline__ int step_cut(const double (&ck)[M], double* kt, int* 
 #pragma unroll
         for (int r = 1; r < M; ++r) c0 = (r == r0) ? ck[r] : c0;
     }
-    const SortedCut sc = cut_sorted<M>(ck, kt, hist, want, wave_min_d(c0), lane, g);
+    const SortedCut sc = cut_sorted<M>(ck, kt, hist, want, wave_lower_bound(c0), lane, g);
     if (sc.exact) return sc.cnt;
     int lane_eq = 0;
 #pragma unroll
@@ -1041,12 +1058,12 @@ __global__ __launch_bounds__(256) void tree_fast_kernel(const SelKArgs a) {
         int used = 0;
 #pragma unroll
         for (int t = 0; t < DMAX; ++t)
-            if (t < D && a.F[t + 1] >= n && used < 2) { lo0 = fmax(lo0, wave_min_d(pk[t])); ++used; }
+            if (t < D && a.F[t + 1] >= n && used < 2) { lo0 = fmax(lo0, wave_lower_bound(pk[t])); ++used; }
         if (used == 0) {
             double lmin = nan_d();
 #pragma unroll
             for (int t = 0; t < DMAX; ++t) lmin = fmin(lmin, pk[t]);
-            lo0 = wave_min_d(lmin);
+            lo0 = wave_lower_bound(lmin);
         }
         // Quick search on the unsorted keys: every key >= lo0 gets a 16-bit code, monotone in the key, over
         // [lo0, largest key]; a 256-bin histogram of the high byte finds the bin of the cut, if needed a second
@@ -1057,9 +1074,9 @@ __global__ __launch_bounds__(256) void tree_fast_kernel(const SelKArgs a) {
             double lmax = nan_d();
 #pragma unroll
             for (int t = 0; t < DMAX; ++t) lmax = fmax(lmax, pk[t]);
-            const double gmax = wave_max_d(lmax);
+            const double gmax = wave_upper_bound(lmax);
             if (gmax > lo0) {
-                const double scale = 65535.0 * __builtin_amdgcn_rcp(next_up(gmax) - lo0);
+                const double scale = 65535.0 * __builtin_amdgcn_rcp(gmax - lo0);
                 int code[DMAX];
 #pragma unroll
                 for (int t = 0; t < DMAX; ++t) {
