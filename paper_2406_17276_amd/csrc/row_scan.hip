@@ -25,11 +25,13 @@ namespace {
 
 constexpr int kCandCap = 2048;
 constexpr float kLog2e = 1.4426950408889634f;
+constexpr long long kScanMaxGrid = 16384;      // workgroups per launch; more items are walked with a grid stride
 
 struct ScanKArgs {
     const void* logits;
     int vocab, k, parts, part_elems;
     int nsteps, rows_per_seq;
+    int items;                        // rows x parts
     int row_start[OT_MAX_DEPTH + 2];
     long long stride_seq, stride_depth, stride_row;
     // P == 1: final row results; P > 1: per-part results
@@ -42,8 +44,9 @@ __device__ __forceinline__ unsigned int f32_key(float v) {
     return (u >> 31) ? ~u : (u | 0x80000000u);
 }
 
+// One work item = one row part (a whole row when the vocabulary fits one part).
 template <int DT, int NT, int EPL, bool VECLOAD>
-__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu((NT == 1024 && VECLOAD) ? 8 : 4, 8))) void row_scan_kernel(const ScanKArgs a) {
+__device__ __forceinline__ void scan_item(const ScanKArgs& a, const int wg) {
     constexpr int VEC = (DT == OT_BF16) ? 8 : 4;   // elements per 16-byte vector; EPL = elements per lane
     constexpr int VPL = EPL / VEC;      // 16-byte vectors per lane
     constexpr int NW = NT / 64;
@@ -59,7 +62,6 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu((NT == 1024 
     __shared__ unsigned long long s_best[16];
 
     const int tid = threadIdx.x;
-    const int wg = blockIdx.x;
     const int rid = wg / a.parts;
     const int part = wg - rid * a.parts;
     const int b = rid / a.rows_per_seq;
@@ -228,6 +230,26 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu((NT == 1024 
             }
             return;
         }
+        if (ncand <= 64 && NT >= 1024) {
+            // 64 x 64 pairs: thread = (candidate i, 4 rivals); the 16 threads of a candidate share a row of lanes
+            const int i = tid >> 4, j0 = (tid & 15) * 4;
+            const float v = s_cv[i < ncand ? i : 0];
+            const int id = s_ci[i < ncand ? i : 0];
+            int cnt = 0;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const int jj = j0 + c;
+                const float u = s_cv[jj < ncand ? jj : 0];
+                const int ui = s_ci[jj < ncand ? jj : 0];
+                cnt += (jj < ncand && (u > v || (u == v && ui < id))) ? 1 : 0;
+            }
+            cnt += dpp_i<DPP_QUAD_XOR1>(0, cnt);
+            cnt += dpp_i<DPP_QUAD_XOR2>(0, cnt);
+            cnt += dpp_i<DPP_ROW_HALF_MIRROR>(0, cnt);
+            cnt += dpp_i<DPP_ROW_MIRROR>(0, cnt);
+            if ((tid & 15) == 0 && i < ncand && cnt < a.k) { outv[cnt] = v; outi[cnt] = id; }
+            return;
+        }
         if (ncand <= 64) {
             if (wave == 0) {          // candidate i sits in lane i; the others are broadcast by v_readlane
                 const float v = lane < ncand ? s_cv[lane] : -INFINITY;
@@ -317,6 +339,21 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu((NT == 1024 
     }
 }
 
+// Launches of up to kScanMaxGrid items have one workgroup per item; larger ones (long-vocabulary, large-batch
+// shapes with 10^5..10^6 items) are walked with a grid stride, because starting a workgroup costs about as
+// much as a small item's share of the memory traffic.
+template <int DT, int NT, int EPL, bool VECLOAD>
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu((NT == 1024 && VECLOAD) ? 8 : 4, 8))) void row_scan_kernel(const ScanKArgs a) {
+    scan_item<DT, NT, EPL, VECLOAD>(a, blockIdx.x);
+}
+template <int DT, int NT, int EPL, bool VECLOAD>
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu((NT == 1024 && VECLOAD) ? 8 : 4, 8))) void row_scan_strided_kernel(const ScanKArgs a) {
+    for (int wg = blockIdx.x; wg < a.items; wg += gridDim.x) {
+        scan_item<DT, NT, EPL, VECLOAD>(a, wg);
+        if (wg + (int)gridDim.x < a.items) __syncthreads();      // the next item reuses the shared arrays
+    }
+}
+
 // Rows that span several parts: combine the per-part (max, sum) pairs and merge the
 // per-part sorted top-k lists.  One thread per row.
 __global__ void merge_parts_kernel(int rows, int parts, int k, const float* part_m, const double* part_s,
@@ -373,11 +410,15 @@ int launch_row_scan(const ScanGeometry& g, const void* logits, const BuildWorksp
     const long long rows = (long long)g.batch * g.rows_per_seq;
     const long long grid = rows * parts;
     if (grid <= 0 || grid > 0x7fffffffLL) return OT_ERR_UNSUPPORTED;
-    const dim3 gd((unsigned)grid);
+    a.items = (int)grid;
+    const dim3 gd((unsigned)(grid <= kScanMaxGrid ? grid : kScanMaxGrid));
 
 #define OT_SCAN_LAUNCH(DT, NT, VL)                                                                       \
     do {                                                                                                 \
-        if (ev0 || ev1) hipExtLaunchKernelGGL((row_scan_kernel<DT, NT, 32, VL>), gd, dim3(NT), 0, s, ev0, ev1, 0, a); \
+        if (grid > kScanMaxGrid) {                                                                       \
+            if (ev0 || ev1) hipExtLaunchKernelGGL((row_scan_strided_kernel<DT, NT, 32, VL>), gd, dim3(NT), 0, s, ev0, ev1, 0, a); \
+            else hipLaunchKernelGGL((row_scan_strided_kernel<DT, NT, 32, VL>), gd, dim3(NT), 0, s, a);   \
+        } else if (ev0 || ev1) hipExtLaunchKernelGGL((row_scan_kernel<DT, NT, 32, VL>), gd, dim3(NT), 0, s, ev0, ev1, 0, a); \
         else hipLaunchKernelGGL((row_scan_kernel<DT, NT, 32, VL>), gd, dim3(NT), 0, s, a);               \
     } while (0)
     if (g.dtype == OT_BF16) {

@@ -78,6 +78,7 @@ def _random_case(V, k, n, d, B, dtype, seed, scale=3.0):
     (400, 8, 60, 10, 16, "f32"),       # a batch of 70B-shaped trees
     (300, 16, 40, 2, 2, "f32"),        # depth 2: first cut at the second step
     (300, 3, 64, 7, 3, "f32"),         # frontier grows 1, 3, 9, 27, 64
+    (300, 4, 64, 8, 50, "f32"),        # 17050 rows: more work items than workgroups (grid-stride scan)
 ])
 def test_random_shapes_and_edges(V, k, n, d, B, dtype):
     stored, want = _random_case(V, k, n, d, B, dtype, seed=V + k + n)
