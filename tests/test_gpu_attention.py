@@ -207,3 +207,28 @@ def test_drafting_phase_attention_frontier_against_pool(dtype, B, Hq, Hkv, D, L,
     want = _oracle_attention(x, mask, dtype)
     assert np.abs(got - want).max() < TOL[dtype]
     assert np.abs(want).max() > 0.01
+
+
+def test_repeated_launches_are_bit_identical():
+    """Split-heavy shape, 300 launches on one prepared workspace: the merge inside the kernel adds the splits
+    in a fixed order, so every launch must reproduce the first bit for bit, and the ticket counters end at zero."""
+    import torch
+    from paper_2406_17276_amd import api
+    w = _shape("bf16", 1, 8, 8, 128, 1000, 50)
+    x = wl.make_attention_inputs(w, 31)
+    mask = _random_masks(1, 50, 9)
+    dev = {k: U.to_device(v, "bf16") for k, v in x.items() if k != "prefix_len"}
+    plen = torch.from_numpy(x["prefix_len"].astype(np.int32)).cuda()
+    pa = api.PreparedAttention(dev["Q"], dev["K_prefix"], dev["V_prefix"], dev["K_tree"], dev["V_tree"], plen,
+                               U.mask_to_device(mask))
+    st = torch.cuda.current_stream().cuda_stream
+    pa(st)
+    torch.cuda.synchronize()
+    first = pa.out.clone()
+    assert np.abs(U.from_device_f64(first) - _oracle_attention(x, mask, "bf16")).max() < 2e-2
+    for it in range(300):
+        pa(st)
+        if it % 50 == 49:
+            torch.cuda.synchronize()
+            assert torch.equal(pa.out, first)
+    assert int(pa.ws[:4096].view(torch.int32).abs().sum().item()) == 0
