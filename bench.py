@@ -382,6 +382,25 @@ def main():
         result["draft_phase_attention"] = {"us_per_call": (time.perf_counter() - td) * 1e6 / 200, "queries": w.n,
                                            "tree_keys": nk, "prefix": w.prefix, "note": "warm inputs"}
 
+    # ---- the tree build on fp32 logits of the same shape (the stored dtype of the bf16 workloads is a reading of
+    # the paper, which never states it): second line for the scan, outside the timed region
+    if args.mode == "stream" and not args.main_only and w.dtype == "bf16" and w.batch * w.rows_per_seq() * w.vocab < (1 << 28):
+        pbs = [api.PreparedBuild(builds[i].logits.float(), w.k, w.n, w.depth) for i in range(min(ring, 6))]
+        for pb in pbs:
+            pb(stream)
+        torch.cuda.synchronize()
+        ev32 = [[hip.event(), hip.event()] for _ in range(60)]
+        t32 = time.perf_counter()
+        for i in range(60):
+            pbs[i % len(pbs)].timed(stream, ev32[i][0], ev32[i][1])
+        torch.cuda.synchronize()
+        us32 = (time.perf_counter() - t32) * 1e6 / 60
+        scan32 = float(np.mean([hip.elapsed_ms(a_, b_) for a_, b_ in ev32])) * 1e3
+        result["fp32_logits"] = {"build_tree_us": us32, "row_scan_kernel_us": scan32,
+                                 "row_scan_GBs": 2 * logit_bytes / (scan32 * 1e-6) / 1e9,
+                                 "frac_of_hbm_peak": 2 * logit_bytes / (scan32 * 1e-6) / 1e9 / HBM_PEAK_GBS}
+        del pbs
+
     # ---- CPU oracle on a bounded sample of the same workload ----------------------------------
     if args.cpu_steps > 0 and not args.skip_parity:
         from threadpoolctl import threadpool_limits
