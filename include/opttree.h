@@ -106,6 +106,18 @@ OT_API int ot_build_tree_timed(const ot_build_params* p, const void* logits,
                   const ot_tree_out* out, void* hip_stream,
                   void* scan_begin_event, void* scan_end_event);
 
+/* ot_build_tree with the stopping rule of Algorithm 1 applied inside the kernel: after every drafting step
+ * E_sub(T, n) (the sum of the n largest p^ drafted so far) is compared with its value E one step earlier
+ * (E = 0 at the start), and drafting ends when E_sub - E <= delta or after p->depth steps.  The logits of
+ * all p->depth steps are passed as for ot_build_tree; rows of steps that are not drafted are scanned but not
+ * used.  steps_used[b] (int32, device) receives the number of steps drafted, e_sub[b] (double, device) the
+ * last E_sub.  Only for the shapes that run on the single-wavefront path (n <= 64 and
+ * (rows per sequence + 1) * k within the LDS budget -- the 7B, 13B and 70B shapes): OT_ERR_UNSUPPORTED
+ * otherwise; the streaming calls below with ot_tree_esub cover every shape. */
+OT_API int ot_build_tree_adaptive(const ot_build_params* p, double delta, const void* logits,
+                  void* workspace, size_t workspace_bytes,
+                  const ot_tree_out* out, int32_t* steps_used, double* e_sub, void* hip_stream);
+
 /* Streaming form of the same computation: what a decoder calls between the
  * draft model's forwards (the loop of Algorithm 1).  The strides of `p` are
  * ignored by begin; each expand call passes its own.

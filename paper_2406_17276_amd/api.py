@@ -72,6 +72,9 @@ def lib():
         L.ot_build_tree_timed.restype = C.c_int
         L.ot_build_tree_timed.argtypes = [C.POINTER(BuildParams), C.c_void_p, C.c_void_p, C.c_size_t,
                                           C.POINTER(TreeOut), C.c_void_p, C.c_void_p, C.c_void_p]
+        L.ot_build_tree_adaptive.restype = C.c_int
+        L.ot_build_tree_adaptive.argtypes = [C.POINTER(BuildParams), C.c_double, C.c_void_p, C.c_void_p, C.c_size_t,
+                                             C.POINTER(TreeOut), C.c_void_p, C.c_void_p, C.c_void_p]
         L.ot_tree_begin.restype = C.c_int
         L.ot_tree_begin.argtypes = [C.POINTER(BuildParams), C.c_void_p, C.c_size_t, C.c_void_p]
         L.ot_tree_expand.restype = C.c_int
@@ -184,6 +187,26 @@ def build_tree(logits, k: int, n: int, depth: int, out: Tree | None = None, work
     _check(lib().ot_build_tree(C.byref(p), logits.data_ptr(), workspace.data_ptr(), workspace.numel(),
                                C.byref(o), _stream()), "ot_build_tree")
     return out
+
+
+def build_tree_adaptive(logits, k: int, n: int, depth: int, delta: float, out: Tree | None = None, workspace=None):
+    """ot_build_tree_adaptive on the current stream; returns (tree, steps_used int32 [B], e_sub float64 [B])."""
+    import torch
+    p = build_params(logits, k, n, depth)
+    if out is None:
+        out = alloc_tree(p.batch, n, logits.device)
+    need = build_workspace_bytes(p)
+    if need == 0:
+        raise OptTreeError(-2, "ot_build_workspace_bytes")
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=logits.device)
+    steps = torch.empty(p.batch, dtype=torch.int32, device=logits.device)
+    e_sub = torch.empty(p.batch, dtype=torch.float64, device=logits.device)
+    o = out.c_struct()
+    _check(lib().ot_build_tree_adaptive(C.byref(p), float(delta), logits.data_ptr(), workspace.data_ptr(),
+                                        workspace.numel(), C.byref(o), steps.data_ptr(), e_sub.data_ptr(), _stream()),
+           "ot_build_tree_adaptive")
+    return out, steps, e_sub
 
 
 class TreeStream:

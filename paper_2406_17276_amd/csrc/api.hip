@@ -151,6 +151,34 @@ int ot_build_tree_timed(const ot_build_params* p, const void* logits, void* work
     return build_entry(p, logits, workspace, workspace_bytes, out, hip_stream, scan_begin_event, scan_end_event);
 }
 
+int ot_build_tree_adaptive(const ot_build_params* p, double delta, const void* logits, void* workspace,
+                           size_t workspace_bytes, const ot_tree_out* out, int32_t* steps_used, double* e_sub,
+                           void* hip_stream) {
+    int st = validate_build(p, true);
+    if (st != OT_OK) return st;
+    if (!(delta == delta)) return OT_ERR_INVALID_ARG;
+    if (!logits || !workspace || !steps_used || !e_sub) return OT_ERR_INVALID_ARG;
+    if ((uintptr_t)workspace % 16 || (uintptr_t)steps_used % 4 || (uintptr_t)e_sub % 8) return OT_ERR_INVALID_ARG;
+    const int esize = p->logits_dtype == OT_BF16 ? 2 : 4;
+    if ((uintptr_t)logits % esize) return OT_ERR_INVALID_ARG;
+    st = check_tree_out(out);
+    if (st != OT_OK) return st;
+    const Frontier f = make_frontier(p->k, p->n, p->depth);
+    const SelectGeometry g = select_geometry(*p, f);
+    if (!tree_adaptive_supported(g)) return OT_ERR_UNSUPPORTED;
+    const BuildWorkspace ws = carve_build_workspace(*p, workspace);
+    if (workspace_bytes < ws.bytes) return OT_ERR_WORKSPACE_TOO_SMALL;
+    hipStream_t s = (hipStream_t)hip_stream;
+    ScanGeometry sg;
+    sg.batch = p->batch; sg.vocab = p->vocab; sg.k = p->k; sg.dtype = p->logits_dtype;
+    sg.nsteps = p->depth; sg.rows_per_seq = f.rows;
+    for (int i = 0; i < OT_MAX_DEPTH + 2; ++i) sg.row_start[i] = f.row_start[i];
+    sg.stride_seq = p->stride_seq; sg.stride_depth = p->stride_depth; sg.stride_row = p->stride_row;
+    st = launch_row_scan(sg, logits, ws, s);
+    if (st != OT_OK) return st;
+    return launch_tree_adaptive(g, delta, ws, *out, steps_used, e_sub, s);
+}
+
 int ot_tree_begin(const ot_build_params* p, void* workspace, size_t workspace_bytes, void* hip_stream) {
     int st = validate_build(p, false);
     if (st != OT_OK) return st;

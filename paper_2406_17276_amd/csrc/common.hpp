@@ -86,6 +86,9 @@ int launch_tree_step(const SelectGeometry& g, int step, const BuildWorkspace& ws
 int launch_tree_finalize(const SelectGeometry& g, int steps_done, const BuildWorkspace& ws, const ot_tree_out& out,
                          hipStream_t s);
 int launch_tree_begin(const SelectGeometry& g, const BuildWorkspace& ws, hipStream_t s);
+bool tree_adaptive_supported(const SelectGeometry& g);
+int launch_tree_adaptive(const SelectGeometry& g, double delta, const BuildWorkspace& ws, const ot_tree_out& out,
+                         int32_t* steps_used, double* e_sub, hipStream_t s);
 int launch_tree_front_mask(const SelectGeometry& g, int steps_done, const BuildWorkspace& ws, uint64_t* mask_out,
                            int mask_words, hipStream_t s);
 int launch_tree_esub(const SelectGeometry& g, int steps_done, double delta, const BuildWorkspace& ws, double* e_sub,

@@ -35,6 +35,7 @@ struct SelKArgs {
                                                               // masks of the last two frontiers over pool indices
     u64* mask_out; int mask_words;                            // output of the frontier-mask query
     int gridDim_batch;                                        // batch size (the grid of these kernels)
+    int32_t* steps_used;                                      // [batch] output of the one-shot adaptive build
     ot_tree_out out;
     int32_t* frontier_token; int32_t* frontier_parent;        // [batch][n]         (streaming step)
     int step;
@@ -959,11 +960,24 @@ __host__ __device__ inline size_t fast_lds_bytes(int rows, int KMAX, int DMAX) {
            (size_t)DMAX * 64;
 }
 
-template <int KMAX, int DMAX>
+// p^ = e^key for key <= 0, to about 1e-7 relative: fp32 exp2 of the leading part of key * log2(e), first-order
+// correction for the remainder (an fp64 exp costs an order of magnitude more instructions)
+__device__ __forceinline__ double exp_of_logp(double key) {
+    const double t = key * 1.4426950408889634;
+    const float hi = (float)t;
+    const double lo = t - (double)hi;
+    return (double)__builtin_amdgcn_exp2f(hi) * (1.0 + lo * 0.6931471805599453);
+}
+
+// ADAPT: Algorithm 1 with its stopping rule inside the kernel.  The n best nodes drafted so far are kept as a
+// running set, one (log p^, p^) per lane; after every step the new layer is merged into it (top n of at most
+// 2n keys, two per lane), E_sub(T, n) is the sum of its p^, and drafting stops when E_sub - E <= delta.
+template <int KMAX, int DMAX, bool ADAPT>
 __global__ __launch_bounds__(256) void tree_fast_kernel(const SelKArgs a) {
     extern __shared__ __attribute__((aligned(16))) u64 smem[];
     __shared__ int s_hist[kBuckets + 4];
-    const int tid = threadIdx.x, b = blockIdx.x, D = a.depth, k = a.k, n = a.n;
+    const int tid = threadIdx.x, b = blockIdx.x, k = a.k, n = a.n;
+    int D = a.depth;                                  // ADAPT: becomes the number of steps drafted
     const int rows = a.rows_per_seq;
     FastLds P;
     P.dl = (double*)smem;
@@ -1002,6 +1016,8 @@ __global__ __launch_bounds__(256) void tree_fast_kernel(const SelKArgs a) {
     g.phase = g.bphase = g.dphase = 0;
     g.tid = lane; g.lane = lane; g.wave = 0; g.nw = 1; g.nt = 64;
 
+    double run_key = nan_d(), run_p = 0.0;            // ADAPT: this lane's member of the running top-n set
+    double E_prev = 0.0, E_sub = 0.0;                 // ADAPT: E of Algorithm 1's loop, latest E_sub(T, n)
     // ---- Algorithm 1, step by step ----
     for (int t = 0; t < D; ++t) {
         const int F = a.F[t], Fn = a.F[t + 1];
@@ -1027,7 +1043,51 @@ __global__ __launch_bounds__(256) void tree_fast_kernel(const SelKArgs a) {
             }
         }
         lds_sync<true>();
+        if (ADAPT) {
+            // merge the new layer (slot `lane`, if any) into the running set: this lane's pair, larger key first
+            const bool has_new = lane < Fn;
+            const double nkey = has_new ? P.key[t * 64 + lane] : nan_d();
+            const double np = has_new ? exp_of_logp(nkey) : 0.0;
+            const bool new_first = (nkey == nkey) && !(run_key >= nkey);
+            double pr[2], pp[2];
+            pr[0] = new_first ? nkey : run_key; pp[0] = new_first ? np : run_p;
+            pr[1] = new_first ? run_key : nkey; pp[1] = new_first ? run_p : np;
+            const int have = (pr[0] == pr[0] ? 1 : 0) + (pr[1] == pr[1] ? 1 : 0);
+            const int total = wave_sum_u(have);
+            int keep = have;
+            if (total > n) {
+                const SortedCut sc = cut_sorted<2>(pr, P.kt, s_hist, n, wave_lower_bound(fmin(pr[0], pr[1])), lane, g);
+                keep = sc.cnt;
+                if (!sc.exact) {                      // equal keys at the cut: equal p^, any of them will do (lane order)
+                    int lane_eq = (pr[0] == sc.tau ? 1 : 0) + (pr[1] == sc.tau ? 1 : 0);
+                    int take = lane_eq;
+                    if (sc.total_eq != sc.need) {
+                        const int before = wave_incl_scan(lane_eq, lane) - lane_eq;
+                        take = sc.need - before;
+                        take = take < 0 ? 0 : (take > lane_eq ? lane_eq : take);
+                    }
+                    keep += take;
+                }
+            }
+            E_sub = wave_sum_d((keep > 0 ? pp[0] : 0.0) + (keep > 1 ? pp[1] : 0.0));
+            // back to one member per lane
+            const int koff = wave_incl_scan(keep, lane) - keep;
+            double* rec = P.kt;                       // [64][2]: (log p^, p^)
+            if (keep > 0) { rec[2 * koff] = pr[0]; rec[2 * koff + 1] = pp[0]; }
+            if (keep > 1) { rec[2 * koff + 2] = pr[1]; rec[2 * koff + 3] = pp[1]; }
+            lds_sync<true>();
+            const bool mine = lane < (total < n ? total : n);
+            run_key = mine ? rec[2 * lane] : nan_d();
+            run_p = mine ? rec[2 * lane + 1] : 0.0;
+            lds_sync<true>();
+            // "while the depth is below the maximum and E_sub(T,n) - E > delta: E <- E_sub(T,n); drafting step"
+            if (t + 1 < D) {
+                if (!(E_sub - E_prev > a.delta)) { D = t + 1; break; }
+                E_prev = E_sub;
+            }
+        }
     }
+    if (ADAPT && lane == 0) { a.steps_used[b] = D; a.e_sub[b] = E_sub; }
 
     // ---- last line of Algorithm 1: the n best nodes of the pool ----
     int pool_nodes = 0;
@@ -1224,6 +1284,7 @@ SelKArgs make_args(const SelectGeometry& g, const BuildWorkspace& ws) {
     a.pool_key = ws.pool_key; a.pool_tok = ws.pool_tok; a.pool_par = ws.pool_par; a.step_tau = ws.step_tau;
     a.pool_p = ws.pool_p; a.seq_E = ws.seq_E; a.seq_steps = ws.seq_steps; a.seq_active = ws.seq_active;
     a.e_sub = nullptr; a.go_on = nullptr; a.delta = 0.0;
+    a.steps_used = nullptr;
     a.front_mask = (u64*)ws.front_mask; a.mask_out = nullptr; a.mask_words = 0; a.gridDim_batch = g.batch;
     a.out = ot_tree_out{nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
     a.frontier_token = nullptr; a.frontier_parent = nullptr;
@@ -1296,23 +1357,30 @@ int launch_finalize_t(const SelKArgs& a, int batch, int NT, hipStream_t s) {
 // LDS the fast path may use (of the 160 KB of a compute unit)
 constexpr size_t kFastLdsLimit = 144 * 1024;
 
-template <int KMAX, int DMAX>
+template <int KMAX, int DMAX, bool ADAPT>
 int launch_fast_t(const SelKArgs& a, int batch, hipStream_t s) {
     const size_t lds = fast_lds_bytes(a.rows_per_seq, KMAX, DMAX);
-    int st = set_lds(tree_fast_kernel<KMAX, DMAX>, lds);
+    int st = set_lds(tree_fast_kernel<KMAX, DMAX, ADAPT>, lds);
     if (st != OT_OK) return st;
-    hipLaunchKernelGGL((tree_fast_kernel<KMAX, DMAX>), dim3(batch), dim3(256), lds, s, a);
+    hipLaunchKernelGGL((tree_fast_kernel<KMAX, DMAX, ADAPT>), dim3(batch), dim3(256), lds, s, a);
     OT_HIP_CHECK(hipGetLastError());
     return OT_OK;
 }
-template <int KMAX>
+template <int KMAX, bool ADAPT>
 int launch_fast_k(const SelKArgs& a, int batch, hipStream_t s) {
-    if (a.depth <= 8) return launch_fast_t<KMAX, 8>(a, batch, s);
-    if (a.depth <= 10) return launch_fast_t<KMAX, 10>(a, batch, s);
-    if (a.depth <= 12) return launch_fast_t<KMAX, 12>(a, batch, s);
-    if (a.depth <= 16) return launch_fast_t<KMAX, 16>(a, batch, s);
-    if (a.depth <= 20) return launch_fast_t<KMAX, 20>(a, batch, s);
-    return launch_fast_t<KMAX, 32>(a, batch, s);
+    if (a.depth <= 8) return launch_fast_t<KMAX, 8, ADAPT>(a, batch, s);
+    if (a.depth <= 10) return launch_fast_t<KMAX, 10, ADAPT>(a, batch, s);
+    if (a.depth <= 12) return launch_fast_t<KMAX, 12, ADAPT>(a, batch, s);
+    if (a.depth <= 16) return launch_fast_t<KMAX, 16, ADAPT>(a, batch, s);
+    if (a.depth <= 20) return launch_fast_t<KMAX, 20, ADAPT>(a, batch, s);
+    return launch_fast_t<KMAX, 32, ADAPT>(a, batch, s);
+}
+template <bool ADAPT>
+int launch_fast(const SelKArgs& a, int batch, hipStream_t s) {
+    if (a.k <= 4) return launch_fast_k<4, ADAPT>(a, batch, s);
+    if (a.k <= 8) return launch_fast_k<8, ADAPT>(a, batch, s);
+    if (a.k <= 10) return launch_fast_k<10, ADAPT>(a, batch, s);
+    return launch_fast_k<16, ADAPT>(a, batch, s);
 }
 int fast_kmax(int k) { return k <= 4 ? 4 : (k <= 8 ? 8 : (k <= 10 ? 10 : 16)); }
 int fast_dmax(int d) { return d <= 8 ? 8 : (d <= 10 ? 10 : (d <= 12 ? 12 : (d <= 16 ? 16 : (d <= 20 ? 20 : 32)))); }
@@ -1322,14 +1390,22 @@ int fast_dmax(int d) { return d <= 8 ? 8 : (d <= 10 ? 10 : (d <= 12 ? 12 : (d <=
 int launch_tree_oneshot(const SelectGeometry& g, const BuildWorkspace& ws, const ot_tree_out& out, hipStream_t s) {
     SelKArgs a = make_args(g, ws);
     a.out = out;
-    if (g.n <= 64 && fast_lds_bytes(g.rows_per_seq, fast_kmax(g.k), fast_dmax(g.depth)) <= kFastLdsLimit) {
-        if (g.k <= 4) return launch_fast_k<4>(a, g.batch, s);
-        if (g.k <= 8) return launch_fast_k<8>(a, g.batch, s);
-        if (g.k <= 10) return launch_fast_k<10>(a, g.batch, s);
-        return launch_fast_k<16>(a, g.batch, s);
-    }
+    if (g.n <= 64 && fast_lds_bytes(g.rows_per_seq, fast_kmax(g.k), fast_dmax(g.depth)) <= kFastLdsLimit)
+        return launch_fast<false>(a, g.batch, s);
     const int NT = threads_for(g.n);
     return NT == 64 ? launch_oneshot_s<true>(a, g.batch, NT, s) : launch_oneshot_s<false>(a, g.batch, NT, s);
+}
+
+bool tree_adaptive_supported(const SelectGeometry& g) {
+    return g.n <= 64 && fast_lds_bytes(g.rows_per_seq, fast_kmax(g.k), fast_dmax(g.depth)) <= kFastLdsLimit;
+}
+
+int launch_tree_adaptive(const SelectGeometry& g, double delta, const BuildWorkspace& ws, const ot_tree_out& out,
+                         int32_t* steps_used, double* e_sub, hipStream_t s) {
+    if (!tree_adaptive_supported(g)) return OT_ERR_UNSUPPORTED;
+    SelKArgs a = make_args(g, ws);
+    a.out = out; a.delta = delta; a.steps_used = steps_used; a.e_sub = e_sub;
+    return launch_fast<true>(a, g.batch, s);
 }
 
 int launch_tree_step(const SelectGeometry& g, int step, const BuildWorkspace& ws, int32_t* frontier_token,

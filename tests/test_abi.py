@@ -124,6 +124,22 @@ def test_esub_rejects_bad_arguments_without_launching():
     assert L.ot_tree_esub(C.byref(p), 1, 0.1, f, need - 1, f, f, None) == -3
 
 
+def test_one_shot_adaptive_build_rejects_bad_arguments_without_launching():
+    L = api.lib()
+    p = _bp()
+    need = api.build_workspace_bytes(p)
+    f = C.c_void_p(0x1000)
+    out = api.TreeOut(*([0x1000] * 7))
+    call = lambda p, delta, logits, ws, nb, steps, es: L.ot_build_tree_adaptive(
+        C.byref(p), C.c_double(delta), logits, ws, nb, C.byref(out), steps, es, None)
+    assert call(p, float("nan"), f, f, need, f, f) == -1
+    assert call(p, 0.1, None, f, need, f, f) == -1
+    assert call(p, 0.1, f, f, need, None, f) == -1
+    assert call(p, 0.1, f, f, need, f, C.c_void_p(0x1004)) == -1        # e_sub is double[batch]
+    assert call(p, 0.1, f, f, need - 1, f, f) == -3
+    assert call(_bp(n=100), 0.1, f, f, api.build_workspace_bytes(_bp(n=100)), f, f) == -2   # n beyond one wavefront
+
+
 def test_verify_rejects_bad_arguments_without_launching():
     L = api.lib()
     vp = lambda **kw: api.VerifyParams(**{**dict(batch=2, vocab=1000, n=16, logits_dtype=api.OT_F32, stride_seq=17000,

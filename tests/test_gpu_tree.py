@@ -250,3 +250,40 @@ def test_frontier_masks_of_the_drafting_phase_match_oracle():
             builders[b].expand(x[b, t, :F].astype(np.float64))
             np.testing.assert_array_equal(m[b], ot_oracle.frontier_masks(builders[b].layers, n, d))
     assert min(min(bld.cut_gaps) for bld in builders) > U.GAP
+
+
+@pytest.mark.parametrize("V,k,n,dmax,B,dtype,delta", [
+    (2000, 6, 30, 8, 5, "f32", 0.01),
+    (32000, 10, 50, 10, 2, "bf16", 0.02),      # 7B shape
+    (500, 4, 64, 12, 3, "f32", 0.003),
+])
+def test_one_shot_adaptive_build_matches_oracle(V, k, n, dmax, B, dtype, delta):
+    """ot_build_tree_adaptive: the stopping rule of Algorithm 1 applied inside the kernel."""
+    import torch
+    from paper_2406_17276_amd import api
+    g = np.random.default_rng(V + n)
+    scales = np.linspace(0.6, 7.0, B)
+    for attempt in range(8):
+        x = wl.store((g.standard_normal((B, dmax, n, V)) * scales[:, None, None, None]).astype(np.float32), dtype)
+        x64 = wl.to_f64(x, dtype)
+        full = [ot_oracle.build_tree_adaptive(x64[b], k, n, dmax, -1.0) for b in range(B)]
+        gains = np.concatenate([np.diff([0.0] + f["e_sub_trace"]) for f in full])
+        want = [ot_oracle.build_tree_adaptive(x64[b], k, n, dmax, delta) for b in range(B)]
+        if np.abs(gains - delta).min() > 1e-5 and min(w["min_gap"] for w in want) > U.GAP:
+            break
+    else:
+        raise RuntimeError("no suitable input")
+    print("steps per sequence:", [w["steps"] for w in want], flush=True)
+    got, steps, e_sub = api.build_tree_adaptive(U.to_device(x, dtype), k, n, dmax, delta)
+    torch.cuda.synchronize()
+    assert list(steps.cpu().numpy()) == [w["steps"] for w in want]
+    np.testing.assert_allclose(e_sub.cpu().numpy(), [w["e_sub_trace"][-1] for w in want], rtol=1e-6)
+    U.assert_tree_equal(got, want, n)
+
+
+def test_one_shot_adaptive_build_is_refused_off_the_single_wavefront_path():
+    import torch
+    from paper_2406_17276_amd import api
+    x = torch.zeros((1, 3, 100, 64), dtype=torch.float32, device="cuda")
+    with pytest.raises(api.OptTreeError):
+        api.build_tree_adaptive(x, 2, 100, 3, 0.1)
