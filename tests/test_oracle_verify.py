@@ -96,3 +96,118 @@ def test_kv_append_moves_the_accepted_rows_and_respects_the_capacity():
     Kp, Vp = K0.copy(), V0.copy()
     assert vf.kv_append(Kp, Vp, Kt, Vt, 8, [0, 2, 4]) == cap       # only two rows fit
     np.testing.assert_array_equal(Kp[:, 8:10], Kt[:, [0, 2]])
+
+
+# ---------------------------------------------------------------------------------------------------------
+# Random sampling (Sec. 4, non-greedy settings; the reading stated in oracle/verify.py)
+
+def test_sample_truth_on_a_dyadic_distribution():
+    # q = (1/2, 1/4, 1/8, 1/8): boundaries of the inverse CDF at 0.5, 0.75, 0.875
+    row = np.log(np.array([0.5, 0.25, 0.125, 0.125]))
+    for u, want in [(0.0, 0), (0.49, 0), (0.51, 1), (0.74, 1), (0.76, 2), (0.874, 2), (0.876, 3), (0.999, 3)]:
+        assert vf.sample_truth(row, 1.0, u) == want
+    # temperature 1/2 squares the probabilities: (16, 4, 1, 1) / 22 -> boundaries 16/22, 20/22, 21/22
+    for u, want in [(0.72, 0), (0.73, 1), (0.90, 1), (0.92, 2), (0.95, 2), (0.96, 3)]:
+        assert vf.sample_truth(row, 0.5, u) == want
+    # temperature 2 takes square roots: (2, sqrt 2, 1, 1) / (4 + sqrt 2) -> first boundary at 0.3694
+    assert vf.sample_truth(row, 2.0, 0.36) == 0 and vf.sample_truth(row, 2.0, 0.38) == 1
+    # a shift of the logits changes nothing
+    assert vf.sample_truth(row + 123.0, 0.5, 0.73) == 1
+
+
+def test_sample_truth_counts_follow_the_softmax():
+    # over the regular grid u = (j + 1/2) / N every token is drawn N q_v times, up to one grid point per boundary
+    g = np.random.default_rng(5)
+    row = g.standard_normal(40) * 2.0
+    row[[3, 17]] = -np.inf                      # masked tokens are never drawn
+    for T in (0.3, 1.0, 1.7):
+        z = row / T
+        q = np.exp(z - z[np.isfinite(z)].max())
+        q /= q.sum()
+        N = 20000
+        counts = np.bincount([vf.sample_truth(row, T, (j + 0.5) / N) for j in range(N)], minlength=40)
+        assert counts[3] == 0 and counts[17] == 0
+        assert np.abs(counts - N * q).max() <= 1.0 + 1e-9
+
+
+def test_low_temperature_is_the_greedy_rule_and_u_spans_the_support():
+    g = np.random.default_rng(9)
+    x = g.standard_normal((7, 50))
+    x[np.arange(7), g.integers(0, 50, 7)] += 6.0
+    for r in range(7):
+        for u in (0.0, 0.3, 0.999999):
+            assert vf.sample_truth(x[r], 1e-3, u) == int(np.argmax(x[r]))
+    row = np.array([-np.inf, 0.3, -1.0, 0.1, -np.inf])
+    assert vf.sample_truth(row, 1.0, 0.0) == 1                  # the first token with a positive probability
+    assert vf.sample_truth(row, 1.0, 1.0 - 1e-12) == 3          # the last one
+    with pytest.raises(ValueError):
+        vf.sample_truth(row, 0.0, 0.5)
+
+
+def test_sampled_walk_on_the_golden_tree():
+    # tokens [0,1,0,2,0], parents [-1,-1,0,0,2]; every target row is q = (1/2, 1/4, 1/4)
+    g = json.load(open(os.path.join(GOLDEN, "hand_tree.json")))
+    tok, par = np.array(g["token"]), np.array(g["parent"])
+    rows = np.tile(np.log(np.array([0.5, 0.25, 0.25])), (6, 1))
+    # u per position (root, node 0..4).  root: 0.1 -> token 0 = node 0; after node 0: 0.8 -> token 2 = node 3;
+    # after node 3 (row 4): 0.6 -> token 1, node 3 has no child: 3 tokens, nodes [0, 3]
+    u = np.array([0.1, 0.8, 0.0, 0.0, 0.6, 0.0])
+    assert vf.sampled_verify(rows, 1.0, u, tok, par, 5) == (3, [0, 3], [0, 2, 1])
+    # root: 0.6 -> token 1 = node 1; row 2 (after node 1): 0.9 -> token 2; node 1 is a leaf
+    u = np.array([0.6, 0.0, 0.9, 0.0, 0.0, 0.0])
+    assert vf.sampled_verify(rows, 1.0, u, tok, par, 5) == (2, [1], [1, 2])
+    # root: 0.8 -> token 2: no child of the root carries it
+    assert vf.sampled_verify(rows, 1.0, np.array([0.8, 0, 0, 0, 0, 0.0]), tok, par, 5) == (1, [], [2])
+    # the whole branch 0 - 0 - 0, then the free token
+    u = np.array([0.2, 0.3, 0.0, 0.4, 0.0, 0.7])
+    assert vf.sampled_verify(rows, 1.0, u, tok, par, 5) == (4, [0, 2, 4], [0, 0, 0, 1])
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_sampled_walk_equals_greedy_walk_on_the_drawn_tokens(seed):
+    # replacing every row by one whose arg-max is the drawn token turns the sampled walk into the greedy walk
+    V, k, n, d = 12, 3, 14, 5
+    g = np.random.default_rng(100 + seed)
+    tree = ot.build_tree(g.standard_normal((d, n, V)) * 2.0, k, n, d)
+    tok, par, n_out = np.array(tree["token"]), np.array(tree["parent"]), len(tree["token"])
+    target = g.standard_normal((n + 1, V)) * 3.0
+    for r in range(n + 1):                      # lean towards a child so that branches get accepted
+        kids = [i for i in range(n_out) if par[i] == r - 1]
+        if kids:
+            target[r, tok[kids[g.integers(len(kids))]]] += 4.0
+    u = g.random(n + 1)
+    T = 0.8
+    drawn = [vf.sample_truth(target[r], T, u[r]) for r in range(n + 1)]
+    want = vf.greedy_verify(_rows_with_argmax(drawn, V, seed), tok, par, n_out)
+    assert vf.sampled_verify(target, T, u, tok, par, n_out) == want
+
+
+def test_sampled_verification_reproduces_the_target_distribution():
+    # losslessness: over a regular grid of (u_root, u_next) the first two produced tokens occur as often as
+    # q_root(a) * q_after(a)(b) says, whether or not the tree holds them
+    V = 4
+    tok, par = np.array([1, 2, 0, 3]), np.array([-1, -1, 0, 0])      # root -> {1, 2}; node 0 (token 1) -> {0, 3}
+    g = np.random.default_rng(3)
+    rows = g.standard_normal((5, V))
+    T = 1.3
+    q = np.exp(rows / T)
+    q /= q.sum(1, keepdims=True)
+    N = 120
+    pair = np.zeros((V, V))
+    single = np.zeros(V)
+    for i in range(N):
+        for j in range(N):
+            u = np.array([(i + 0.5) / N] + [(j + 0.5) / N] * 4)
+            A, nodes, out = vf.sampled_verify(rows, T, u, tok, par, 4)
+            if A >= 2:
+                pair[out[0], out[1]] += 1
+            else:
+                single[out[0]] += 1
+    for a in range(V):
+        child = [i for i in range(4) if par[i] == -1 and tok[i] == a]
+        if child:                                                   # a is in the tree: the next token follows
+            np.testing.assert_allclose(pair[a] / N**2, q[0, a] * q[child[0] + 1], atol=2.5 / N)
+            assert single[a] == 0
+        else:                                                       # a is not: the step ends with a alone
+            np.testing.assert_allclose(single[a] / N**2, q[0, a], atol=1.5 / N)
+            assert pair[a].sum() == 0
