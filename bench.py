@@ -372,6 +372,24 @@ def main():
                                    "calls": "ot_verify_greedy + ot_kv_append",
                                    "target_rows": w.batch * (w.n + 1), "target_bytes": w.batch * (w.n + 1) * w.vocab * w.elem_bytes()}
 
+        # the same with the ground truth drawn at temperature 1 (uniform numbers resident on the device)
+        us_d = torch.rand((w.batch, w.n + 1), generator=gt, device="cuda")
+        sws = torch.empty(int(api.lib().ot_verify_sample_workspace_bytes(C.byref(api.VerifyParams(
+            w.batch, w.vocab, w.n, api.OT_BF16 if w.dtype == "bf16" else api.OT_F32, targets[0].stride(0),
+            targets[0].stride(1))))), dtype=torch.uint8, device="cuda")
+        def sample_once(i):
+            alen, anode, _ = api.verify_sample(targets[i % 4], us_d, 1.0, tree0, workspace=sws)
+            api.kv_append(kp, vp, kt, vt, plen_d, alen, anode)
+        sample_once(0)
+        torch.cuda.synchronize()
+        tv = time.perf_counter()
+        for i in range(100):
+            sample_once(i)
+        torch.cuda.synchronize()
+        result["sampled_verify"] = {"us_per_call_pair": (time.perf_counter() - tv) * 1e4,
+                                    "calls": "ot_verify_sample + ot_kv_append", "temperature": 1.0,
+                                    "target_rows": w.batch * (w.n + 1)}
+
     # ---- drafting-phase attention of the same shape, outside the timed region: the n frontier tokens against the
     # prefix and the K/V of all depth*n pool nodes (the draft model's attention of the last drafting step)
     if args.mode == "stream" and not args.main_only and w.depth * w.n <= 512 and w.dtype == "bf16":

@@ -254,6 +254,24 @@ OT_API int ot_verify_greedy(const ot_verify_params* p, const void* target_logits
                      void* workspace, size_t workspace_bytes,
                      int32_t* accept_len, int32_t* accept_node, int32_t* accept_token, void* hip_stream);
 
+/* Verification under random sampling (Sec. 4, "Performance on Non-greedy Settings": only the acceptable
+ * tokens change with respect to the greedy case; the paper gives no rule, this is the reading built here).
+ * The ground truth after a position is DRAWN from q = softmax(row / temperature) of that position's target
+ * row: the smallest token v with q_0 + ... + q_v > u, u = u[b][r] a uniform number in [0, 1) supplied by the
+ * caller per row (device float [batch][n + 1], row index as in target_logits).  The walk and the outputs are
+ * those of ot_verify_greedy.  Every produced token is an exact draw from the target's distribution at its
+ * position, so the output is distributed as plain sampling from the target.  Logits must be finite or -inf
+ * (probability 0; a row without a finite logit draws token 0).  The cumulative sums are taken in fp32 per
+ * 16-byte vector and fp64 above: a u closer than ~1e-6 to a boundary of the CDF may fall on either side.
+ * temperature > 0 (for temperature -> 0 use ot_verify_greedy).  Unsupported (-2): vocab beyond 512
+ * segments of 64 x 16 bytes (131072 f32 / 262144 bf16 logits), batch * (n + 1) > 65535. */
+OT_API size_t ot_verify_sample_workspace_bytes(const ot_verify_params* p);   /* 0 if p is invalid or unsupported */
+
+OT_API int ot_verify_sample(const ot_verify_params* p, float temperature, const void* target_logits, const float* u,
+                     const int32_t* token, const int32_t* parent, const int32_t* n_out,
+                     void* workspace, size_t workspace_bytes,
+                     int32_t* accept_len, int32_t* accept_node, int32_t* accept_token, void* hip_stream);
+
 /* The accepted nodes join the cache ("Concat" of Algorithm 2): for j < A - 1 the K and V rows of tree node
  * accept_node[b][j] are copied to prefix row prefix_len[b] + j of every KV head, and
  * new_prefix_len[b] = min(prefix_len[b] + A - 1, max_prefix); rows that do not fit in max_prefix are dropped.

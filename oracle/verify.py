@@ -57,6 +57,16 @@ def sample_truth(row: np.ndarray, temperature: float, u: float) -> int:
     return int(np.nonzero(e > 0)[0][-1])        # only reachable through rounding when u is next to 1
 
 
+def sample_margin(row: np.ndarray, temperature: float, u: float) -> float:
+    """Distance from u to the nearest boundary of the inverse CDF of softmax(row / temperature) (boundaries
+    at 0 and 1 excluded): a draw with a margin above an implementation's rounding error is the same token in
+    every correct implementation."""
+    z = np.asarray(row, dtype=np.float64) / float(temperature)
+    e = np.exp(z - z.max())
+    cdf = np.cumsum(e)[:-1] / e.sum()
+    return float(np.abs(cdf - float(u)).min()) if len(cdf) else 1.0
+
+
 def sampled_verify(target_logits: np.ndarray, temperature: float, u: np.ndarray, token: np.ndarray,
                    parent: np.ndarray, n_out: int):
     """greedy_verify with the ground truth after position `cur` drawn by sample_truth(target_logits[cur + 1],

@@ -91,6 +91,11 @@ def lib():
                                    C.c_void_p, C.c_void_p, C.c_void_p]
         L.ot_verify_workspace_bytes.restype = C.c_size_t
         L.ot_verify_workspace_bytes.argtypes = [C.POINTER(VerifyParams)]
+        L.ot_verify_sample_workspace_bytes.restype = C.c_size_t
+        L.ot_verify_sample_workspace_bytes.argtypes = [C.POINTER(VerifyParams)]
+        L.ot_verify_sample.restype = C.c_int
+        L.ot_verify_sample.argtypes = ([C.POINTER(VerifyParams), C.c_float] + [C.c_void_p] * 6 + [C.c_size_t] +
+                                       [C.c_void_p] * 4)
         L.ot_verify_greedy.restype = C.c_int
         L.ot_verify_greedy.argtypes = [C.POINTER(VerifyParams)] + [C.c_void_p] * 5 + [C.c_size_t] + [C.c_void_p] * 4
         L.ot_kv_append.restype = C.c_int
@@ -340,6 +345,34 @@ def verify_greedy(target_logits, tree: "Tree", workspace=None):
                                   tree.n_out.data_ptr(), workspace.data_ptr(), workspace.numel(),
                                   accept_len.data_ptr(), accept_node.data_ptr(), accept_token.data_ptr(), _stream()),
            "ot_verify_greedy")
+    return accept_len, accept_node, accept_token
+
+
+def verify_sample(target_logits, u, temperature, tree: "Tree", workspace=None):
+    """ot_verify_sample on the current stream.  target_logits [B, n + 1, V]; u float32 [B, n + 1] uniform
+    numbers in [0, 1), one per target row; returns (accept_len, accept_node, accept_token) as in
+    verify_greedy."""
+    import torch
+    if target_logits.dim() != 3 or target_logits.stride(2) != 1:
+        raise ValueError("target_logits must be [B, n + 1, V] with a contiguous last dimension")
+    B, rows, V = target_logits.shape
+    n = rows - 1
+    if u.dtype != torch.float32 or tuple(u.shape) != (B, rows) or not u.is_contiguous():
+        raise ValueError("u must be a contiguous float32 tensor [B, n + 1]")
+    p = VerifyParams(B, V, n, _dtype_code(target_logits), target_logits.stride(0), target_logits.stride(1))
+    need = int(lib().ot_verify_sample_workspace_bytes(C.byref(p)))
+    if need == 0:
+        raise OptTreeError(-2, "ot_verify_sample_workspace_bytes")
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=target_logits.device)
+    dev = target_logits.device
+    accept_len = torch.empty(B, dtype=torch.int32, device=dev)
+    accept_node = torch.empty((B, n), dtype=torch.int32, device=dev)
+    accept_token = torch.empty((B, n + 1), dtype=torch.int32, device=dev)
+    _check(lib().ot_verify_sample(C.byref(p), C.c_float(temperature), target_logits.data_ptr(), u.data_ptr(),
+                                  tree.token.data_ptr(), tree.parent.data_ptr(), tree.n_out.data_ptr(),
+                                  workspace.data_ptr(), workspace.numel(), accept_len.data_ptr(),
+                                  accept_node.data_ptr(), accept_token.data_ptr(), _stream()), "ot_verify_sample")
     return accept_len, accept_node, accept_token
 
 

@@ -156,6 +156,23 @@ def test_verify_rejects_bad_arguments_without_launching():
     assert L.ot_verify_greedy(C.byref(p), f, f, f, f, f, need - 1, f, f, f, None) == -3
     assert L.ot_verify_greedy(C.byref(p), f, f, f, f, C.c_void_p(0x1008), need, f, f, f, None) == -1
     assert L.ot_verify_greedy(C.byref(vp(logits_dtype=7)), f, f, f, f, f, need, f, f, f, None) == -1
+    # random-sampling verification
+    need_s = L.ot_verify_sample_workspace_bytes(C.byref(p))
+    assert need_s > 0
+    assert L.ot_verify_sample_workspace_bytes(C.byref(vp(n=0))) == 0
+    assert L.ot_verify_sample_workspace_bytes(C.byref(vp(vocab=200000, stride_row=200000))) == 0    # > 512 f32 segments
+    smp = lambda p, T, logits, u, ws, nb: L.ot_verify_sample(C.byref(p), C.c_float(T), logits, u, f, f, f, ws, nb,
+                                                             f, f, f, None)
+    assert smp(p, 0.0, f, f, f, need_s) == -1                       # temperature must be positive
+    assert smp(p, -1.0, f, f, f, need_s) == -1
+    assert smp(p, float("nan"), f, f, f, need_s) == -1
+    assert smp(p, float("inf"), f, f, f, need_s) == -1
+    assert smp(p, 1.0, None, f, f, need_s) == -1
+    assert smp(p, 1.0, f, None, f, need_s) == -1
+    assert smp(p, 1.0, f, C.c_void_p(0x1002), f, need_s) == -1
+    assert smp(p, 1.0, f, f, f, need_s - 1) == -3
+    assert smp(vp(vocab=200000, stride_row=200000), 1.0, f, f, f, 1 << 30) == -2
+    assert smp(vp(batch=4000), 1.0, f, f, f, 1 << 30) == -2         # batch * (n + 1) beyond one grid dimension
     ap = _ap()
     assert L.ot_kv_append(C.byref(ap), None, f, f, f, f, f, f, f, None) == -1
     assert L.ot_kv_append(C.byref(ap), C.c_void_p(0x1004), f, f, f, f, f, f, f, None) == -1

@@ -211,3 +211,15 @@ def test_sampled_verification_reproduces_the_target_distribution():
         else:                                                       # a is not: the step ends with a alone
             np.testing.assert_allclose(single[a] / N**2, q[0, a], atol=1.5 / N)
             assert pair[a].sum() == 0
+
+
+def test_sample_margin_is_the_distance_to_the_nearest_cdf_boundary():
+    row = np.log(np.array([0.5, 0.25, 0.125, 0.125]))
+    assert abs(vf.sample_margin(row, 1.0, 0.6) - 0.1) < 1e-12           # boundaries 0.5, 0.75, 0.875
+    assert abs(vf.sample_margin(row, 1.0, 0.86) - 0.015) < 1e-12
+    # moving u by less than the margin never changes the draw
+    g = np.random.default_rng(2)
+    x = g.standard_normal(30) * 2
+    for u in g.random(50):
+        m = vf.sample_margin(x, 0.9, u)
+        assert vf.sample_truth(x, 0.9, u - 0.99 * m) == vf.sample_truth(x, 0.9, u) == vf.sample_truth(x, 0.9, u + 0.99 * m)
