@@ -1261,7 +1261,7 @@ __global__ __launch_bounds__(256) void tree_fast_kernel(const SelKArgs a) {
         a.out.mask[o] = m;                            // n <= 64: one mask word per node
     }
     // E = sum of p^ (Eq. 3)
-    const double e_sum = wave_sum_d(node ? exp(key) : 0.0);
+    const double e_sum = wave_sum_d(node ? exp_of_logp(key) : 0.0);
     if (lane == 0) {
         a.out.expect[b] = e_sum;
         a.out.n_out[b] = n_out;
