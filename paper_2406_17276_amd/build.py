@@ -15,6 +15,9 @@ FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-command-line-argument", "-Wno-inline-asm",
+    # leading scalar kernel arguments arrive in registers at wavefront start (documented LLVM AMDGPU feature for
+    # gfx940 and later; the compiler keeps a fallback entry that reads them from memory)
+    "-mllvm", "-amdgpu-kernarg-preload-count=12",
     "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
 ]
 

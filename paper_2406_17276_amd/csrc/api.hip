@@ -134,7 +134,7 @@ static int build_entry(const ot_build_params* p, const void* logits, void* works
     ScanGeometry sg;
     sg.batch = p->batch; sg.vocab = p->vocab; sg.k = p->k; sg.dtype = p->logits_dtype;
     sg.nsteps = p->depth; sg.rows_per_seq = f.rows;
-    for (int i = 0; i < OT_MAX_DEPTH + 2; ++i) sg.row_start[i] = f.row_start[i];
+    sg.grow_k = p->k; sg.grow_n = p->n;
     sg.stride_seq = p->stride_seq; sg.stride_depth = p->stride_depth; sg.stride_row = p->stride_row;
     st = launch_row_scan(sg, logits, ws, s, (hipEvent_t)ev0, (hipEvent_t)ev1);
     if (st != OT_OK) return st;
@@ -172,7 +172,7 @@ int ot_build_tree_adaptive(const ot_build_params* p, double delta, const void* l
     ScanGeometry sg;
     sg.batch = p->batch; sg.vocab = p->vocab; sg.k = p->k; sg.dtype = p->logits_dtype;
     sg.nsteps = p->depth; sg.rows_per_seq = f.rows;
-    for (int i = 0; i < OT_MAX_DEPTH + 2; ++i) sg.row_start[i] = f.row_start[i];
+    sg.grow_k = p->k; sg.grow_n = p->n;
     sg.stride_seq = p->stride_seq; sg.stride_depth = p->stride_depth; sg.stride_row = p->stride_row;
     st = launch_row_scan(sg, logits, ws, s);
     if (st != OT_OK) return st;
@@ -209,8 +209,7 @@ int ot_tree_expand(const ot_build_params* p, int32_t step, const void* rows, int
     ScanGeometry sg;
     sg.batch = p->batch; sg.vocab = p->vocab; sg.k = p->k; sg.dtype = p->logits_dtype;
     sg.nsteps = 1; sg.rows_per_seq = f.F[step];
-    memset(sg.row_start, 0, sizeof(sg.row_start));
-    sg.row_start[1] = f.F[step];
+    sg.grow_k = 1; sg.grow_n = 1;
     sg.stride_seq = stride_seq; sg.stride_depth = 0; sg.stride_row = stride_row;
     st = launch_row_scan(sg, rows, ws, s);
     if (st != OT_OK) return st;

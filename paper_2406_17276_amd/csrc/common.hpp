@@ -60,13 +60,14 @@ struct BuildWorkspace {
 };
 BuildWorkspace carve_build_workspace(const ot_build_params& p, void* base);
 
-// Which logits rows a scan launch covers: row id r in [0, batch*rows_per_seq)
-// maps to (b, t, j) through row_start[]; address = base + b*ss + t*sd + j*sr.
+// Which logits rows a scan launch covers: a sequence's rows are those of `nsteps` steps, step t holding F_t rows
+// with F_0 = 1 and F_{t+1} = min(grow_n, grow_k F_t) (the frontier sizes of Algorithm 1; nsteps = 1 with
+// rows_per_seq rows: one plain block of rows).  Row (b, t, j) is at base + b*ss + t*sd + j*sr.
 struct ScanGeometry {
     int batch, vocab, k, dtype;
     int nsteps;                       // steps covered by this launch
     int rows_per_seq;
-    int row_start[OT_MAX_DEPTH + 2];  // prefix sums over the covered steps
+    int grow_k, grow_n;               // frontier growth; unused when nsteps == 1
     long long stride_seq, stride_depth, stride_row;
 };
 

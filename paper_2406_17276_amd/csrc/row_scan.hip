@@ -28,12 +28,8 @@ constexpr float kLog2e = 1.4426950408889634f;
 constexpr long long kScanMaxGrid = 16384;      // workgroups per launch; more items are walked with a grid stride
 
 struct ScanKArgs {
-    const void* logits;
     int vocab, k, parts, part_elems;
-    int nsteps, rows_per_seq;
     int items;                        // rows x parts
-    int row_start[OT_MAX_DEPTH + 2];
-    long long stride_seq, stride_depth, stride_row;
     // P == 1: final row results; P > 1: per-part results
     double* row_lse; float* row_topv; int32_t* row_topi;
     float* part_m; double* part_s; float* part_topv; int32_t* part_topi;
@@ -44,9 +40,21 @@ __device__ __forceinline__ unsigned int f32_key(float v) {
     return (u >> 31) ? ~u : (u | 0x80000000u);
 }
 
+// What a work item needs to find its logits.  The kernels take these as leading scalar arguments, which the
+// hardware hands over in registers at wavefront start (kernel-argument preload): the loads of a work item go out
+// without waiting for a read of the argument block.
+struct ScanHead {
+    const void* logits;
+    long long stride_seq, stride_depth, stride_row;
+    int vocab;
+    int part_geom;                    // parts | part_elems << 4
+    int rows_per_seq;
+    int grow;                         // nsteps | k << 8 | n << 16: step t covers F_t rows, F_0 = 1, F_{t+1} = min(n, k F_t)
+};
+
 // One work item = one row part (a whole row when the vocabulary fits one part).
 template <int DT, int NT, int EPL, bool VECLOAD>
-__device__ __forceinline__ void scan_item(const ScanKArgs& a, const int wg) {
+__device__ __forceinline__ void scan_item(const ScanHead& h, const ScanKArgs& a, const int wg) {
     constexpr int VEC = (DT == OT_BF16) ? 8 : 4;   // elements per 16-byte vector; EPL = elements per lane
     constexpr int VPL = EPL / VEC;      // 16-byte vectors per lane
     constexpr int NW = NT / 64;
@@ -62,16 +70,23 @@ __device__ __forceinline__ void scan_item(const ScanKArgs& a, const int wg) {
     __shared__ unsigned long long s_best[16];
 
     const int tid = threadIdx.x;
-    const int rid = wg / a.parts;
-    const int part = wg - rid * a.parts;
-    const int b = rid / a.rows_per_seq;
-    const int r = rid - b * a.rows_per_seq;
-    int t = 0;
-    while (t + 1 < a.nsteps && r >= a.row_start[t + 1]) ++t;
-    const int j = r - a.row_start[t];
-    const long long row_off = (long long)b * a.stride_seq + (long long)t * a.stride_depth + (long long)j * a.stride_row;
-    const int e_begin = part * a.part_elems;
-    const int e_end = min(a.vocab, e_begin + a.part_elems);
+    const int parts = h.part_geom & 15, part_elems = h.part_geom >> 4;
+    const int rid = wg / parts;
+    const int part = wg - rid * parts;
+    const int b = rid / h.rows_per_seq;
+    const int r = rid - b * h.rows_per_seq;
+    // row r of a sequence is slot j of step t (Algorithm 1: the frontier grows k-fold per step up to n)
+    const int nsteps = h.grow & 255, grow_k = (h.grow >> 8) & 255, grow_n = h.grow >> 16;
+    int t = 0, start = 0, F = 1;
+    while (t + 1 < nsteps && r >= start + F) {
+        start += F;
+        F = min(grow_n, grow_k * F);
+        ++t;
+    }
+    const int j = r - start;
+    const long long row_off = (long long)b * h.stride_seq + (long long)t * h.stride_depth + (long long)j * h.stride_row;
+    const int e_begin = part * part_elems;
+    const int e_end = min(h.vocab, e_begin + part_elems);
 
     if (tid == 0) s_count = 0;
 
@@ -80,7 +95,7 @@ __device__ __forceinline__ void scan_item(const ScanKArgs& a, const int wg) {
     // either wholly inside the part or wholly outside.  Otherwise: guarded scalar loads.
     float x[EPL];
     if (DT == OT_BF16) {
-        const unsigned short* row = (const unsigned short*)a.logits + row_off;
+        const unsigned short* row = (const unsigned short*)h.logits + row_off;
 #pragma unroll
         for (int i = 0; i < VPL; ++i) {
             const int e0 = e_begin + (i * NT + tid) * VEC;
@@ -98,7 +113,7 @@ __device__ __forceinline__ void scan_item(const ScanKArgs& a, const int wg) {
             }
         }
     } else {
-        const float* row = (const float*)a.logits + row_off;
+        const float* row = (const float*)h.logits + row_off;
 #pragma unroll
         for (int i = 0; i < VPL; ++i) {
             const int e0 = e_begin + (i * NT + tid) * VEC;
@@ -311,8 +326,8 @@ __device__ __forceinline__ void scan_item(const ScanKArgs& a, const int wg) {
         unsigned long long best = 0ull;
         for (int e = e_begin + tid; e < e_end; e += NT) {
             float v;
-            if (DT == OT_BF16) v = __uint_as_float((unsigned)((const unsigned short*)a.logits + row_off)[e] << 16);
-            else v = ((const float*)a.logits + row_off)[e];
+            if (DT == OT_BF16) v = __uint_as_float((unsigned)((const unsigned short*)h.logits + row_off)[e] << 16);
+            else v = ((const float*)h.logits + row_off)[e];
             const bool after = (v < prev_v) || (v == prev_v && e > prev_i);
             if (after) {
                 const unsigned long long key =
@@ -343,13 +358,19 @@ __device__ __forceinline__ void scan_item(const ScanKArgs& a, const int wg) {
 // shapes with 10^5..10^6 items) are walked with a grid stride, because starting a workgroup costs about as
 // much as a small item's share of the memory traffic.
 template <int DT, int NT, int EPL, bool VECLOAD>
-__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu((NT == 1024 && VECLOAD) ? 8 : 4, 8))) void row_scan_kernel(const ScanKArgs a) {
-    scan_item<DT, NT, EPL, VECLOAD>(a, blockIdx.x);
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu((NT == 1024 && VECLOAD) ? 8 : 4, 8))) void row_scan_kernel(
+    const void* logits, const long long stride_seq, const long long stride_depth, const long long stride_row,
+    const int vocab, const int part_geom, const int rows_per_seq, const int grow, const ScanKArgs a) {
+    const ScanHead h{logits, stride_seq, stride_depth, stride_row, vocab, part_geom, rows_per_seq, grow};
+    scan_item<DT, NT, EPL, VECLOAD>(h, a, blockIdx.x);
 }
 template <int DT, int NT, int EPL, bool VECLOAD>
-__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu((NT == 1024 && VECLOAD) ? 8 : 4, 8))) void row_scan_strided_kernel(const ScanKArgs a) {
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu((NT == 1024 && VECLOAD) ? 8 : 4, 8))) void row_scan_strided_kernel(
+    const void* logits, const long long stride_seq, const long long stride_depth, const long long stride_row,
+    const int vocab, const int part_geom, const int rows_per_seq, const int grow, const ScanKArgs a) {
+    const ScanHead h{logits, stride_seq, stride_depth, stride_row, vocab, part_geom, rows_per_seq, grow};
     for (int wg = blockIdx.x; wg < a.items; wg += gridDim.x) {
-        scan_item<DT, NT, EPL, VECLOAD>(a, wg);
+        scan_item<DT, NT, EPL, VECLOAD>(h, a, wg);
         if (wg + (int)gridDim.x < a.items) __syncthreads();      // the next item reuses the shared arrays
     }
 }
@@ -394,13 +415,13 @@ int launch_row_scan(const ScanGeometry& g, const void* logits, const BuildWorksp
     const int esize = g.dtype == OT_BF16 ? 2 : 4;
     const int vec = 16 / esize;
     ScanKArgs a;
-    a.logits = logits;
     a.vocab = g.vocab; a.k = g.k; a.parts = parts;
     const int per = (g.vocab + parts - 1) / parts;
     a.part_elems = (per + vec - 1) / vec * vec;
-    a.nsteps = g.nsteps; a.rows_per_seq = g.rows_per_seq;
-    for (int i = 0; i < OT_MAX_DEPTH + 2; ++i) a.row_start[i] = g.row_start[i];
-    a.stride_seq = g.stride_seq; a.stride_depth = g.stride_depth; a.stride_row = g.stride_row;
+    if (g.nsteps < 1 || g.nsteps > 255 || g.grow_k < 1 || g.grow_k > 255 || g.grow_n < 1 || g.grow_n > 32767)
+        return OT_ERR_INVALID_ARG;
+    const int part_geom = parts | (a.part_elems << 4);
+    const int grow = g.nsteps | (g.grow_k << 8) | (g.grow_n << 16);
     a.row_lse = ws.row_lse; a.row_topv = ws.row_topv; a.row_topi = ws.row_topi;
     a.part_m = ws.part_m; a.part_s = ws.part_s; a.part_topv = ws.part_topv; a.part_topi = ws.part_topi;
 
@@ -413,13 +434,14 @@ int launch_row_scan(const ScanGeometry& g, const void* logits, const BuildWorksp
     a.items = (int)grid;
     const dim3 gd((unsigned)(grid <= kScanMaxGrid ? grid : kScanMaxGrid));
 
+#define OT_SCAN_ARGS logits, g.stride_seq, g.stride_depth, g.stride_row, g.vocab, part_geom, g.rows_per_seq, grow, a
 #define OT_SCAN_LAUNCH(DT, NT, VL)                                                                       \
     do {                                                                                                 \
         if (grid > kScanMaxGrid) {                                                                       \
-            if (ev0 || ev1) hipExtLaunchKernelGGL((row_scan_strided_kernel<DT, NT, 32, VL>), gd, dim3(NT), 0, s, ev0, ev1, 0, a); \
-            else hipLaunchKernelGGL((row_scan_strided_kernel<DT, NT, 32, VL>), gd, dim3(NT), 0, s, a);   \
-        } else if (ev0 || ev1) hipExtLaunchKernelGGL((row_scan_kernel<DT, NT, 32, VL>), gd, dim3(NT), 0, s, ev0, ev1, 0, a); \
-        else hipLaunchKernelGGL((row_scan_kernel<DT, NT, 32, VL>), gd, dim3(NT), 0, s, a);               \
+            if (ev0 || ev1) hipExtLaunchKernelGGL((row_scan_strided_kernel<DT, NT, 32, VL>), gd, dim3(NT), 0, s, ev0, ev1, 0, OT_SCAN_ARGS); \
+            else hipLaunchKernelGGL((row_scan_strided_kernel<DT, NT, 32, VL>), gd, dim3(NT), 0, s, OT_SCAN_ARGS);   \
+        } else if (ev0 || ev1) hipExtLaunchKernelGGL((row_scan_kernel<DT, NT, 32, VL>), gd, dim3(NT), 0, s, ev0, ev1, 0, OT_SCAN_ARGS); \
+        else hipLaunchKernelGGL((row_scan_kernel<DT, NT, 32, VL>), gd, dim3(NT), 0, s, OT_SCAN_ARGS);               \
     } while (0)
     if (g.dtype == OT_BF16) {
         if (small) { if (aligned) OT_SCAN_LAUNCH(OT_BF16, 256, true); else OT_SCAN_LAUNCH(OT_BF16, 256, false); }
@@ -429,6 +451,7 @@ int launch_row_scan(const ScanGeometry& g, const void* logits, const BuildWorksp
         else       { if (aligned) OT_SCAN_LAUNCH(OT_F32, 1024, true); else OT_SCAN_LAUNCH(OT_F32, 1024, false); }
     }
 #undef OT_SCAN_LAUNCH
+#undef OT_SCAN_ARGS
     OT_HIP_CHECK(hipGetLastError());
     if (parts > 1) {
         const int threads = 128;

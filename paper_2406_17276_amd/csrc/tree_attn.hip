@@ -103,7 +103,12 @@ __device__ __forceinline__ void split_range(int T, int S, int s, int& t0, int& t
 #define OT_ATTN_NBUF_NARROW 3
 #endif
 template <int D, bool WIDE>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_mfma_kernel(const AttnKArgs a) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_mfma_kernel(
+    // what the first loads need, as leading scalar arguments: the hardware hands these over in registers at
+    // wavefront start (kernel-argument preload); they repeat fields of `a`
+    const int32_t* a_prefix_len, const uint64_t* a_mask, const void* a_Q, const int a_row_blocks, const int a_splits,
+    const int a_kv_heads, const int a_g, const int a_n, const int a_max_prefix, const int a_nk, const int a_W,
+    const AttnKArgs a) {
     constexpr int TK = 64;                 // keys per tile
     constexpr int CPR = D / 8;             // 16-byte chunks per row
     constexpr int SPR = D / 16;            // 32-byte segments per row
@@ -129,24 +134,24 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const int l32 = lane & 31, h = lane >> 5;
     // workgroup numbering: see above
     const int xcd = blockIdx.x & 7, q = blockIdx.x >> 3;
-    const int unit = (q / a.row_blocks) * 8 + xcd, rb = q % a.row_blocks;
-    if (unit >= a.batch * a.kv_heads * a.splits) return;
-    const int bz = unit / a.splits, split = unit - bz * a.splits;
-    const int b = bz / a.kv_heads, hk = bz - b * a.kv_heads;
-    const int n = a.n;
+    const int unit = (q / a_row_blocks) * 8 + xcd, rb = q % a_row_blocks;
+    if (unit >= a.batch * a_kv_heads * a_splits) return;
+    const int bz = unit / a_splits, split = unit - bz * a_splits;
+    const int b = bz / a_kv_heads, hk = bz - b * a_kv_heads;
+    const int n = a_n;
 
     // this lane's query row; lanes past the last row work on a copy of it and store nothing
     const int rho = rb * ROWS + qb * 32 + l32;         // packed row inside the KV head
-    const bool row_ok = rho < a.g * n;
-    const int rho_c = row_ok ? rho : a.g * n - 1;
-    const int hq = hk * a.g + rho_c / n;
+    const bool row_ok = rho < a_g * n;
+    const int rho_c = row_ok ? rho : a_g * n - 1;
+    const int hq = hk * a_g + rho_c / n;
     const int node = rho_c % n;
 
     // Q fragments: B operand of S^T = K Q^T; lane holds Q[row][16 s + 8 h .. +7]
     u32x4 qw[SLABS];
     {
         const unsigned short* qrow =
-            (const unsigned short*)a.Q + (long long)b * a.qs[0] + (long long)hq * a.qs[1] + (long long)node * a.qs[2];
+            (const unsigned short*)a_Q + (long long)b * a.qs[0] + (long long)hq * a.qs[1] + (long long)node * a.qs[2];
 #pragma unroll
         for (int s = 0; s < SLABS; ++s) qw[s] = *(const u32x4*)(qrow + 16 * s + 8 * h);
     }
@@ -154,12 +159,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     uint64_t mrow[kMaskWords] = {0ull, 0ull, 0ull, 0ull, 0ull, 0ull, 0ull, 0ull};
 #pragma unroll
     for (int w = 0; w < kMaskWords; ++w)
-        if (w < a.W) mrow[w] = a.mask[((long long)b * n + node) * a.W + w];
+        if (w < a_W) mrow[w] = a_mask[((long long)b * n + node) * a_W + w];
 
-    const int L = clamp_len(a.prefix_len[b], a.max_prefix);
-    const int ptiles = (L + TK - 1) / TK, ttiles = (a.nk + TK - 1) / TK;
+    const int L = clamp_len(a_prefix_len[b], a_max_prefix);
+    const int ptiles = (L + TK - 1) / TK, ttiles = (a_nk + TK - 1) / TK;
     int t0, t1;
-    split_range(ptiles + ttiles, a.splits, split, t0, t1);
+    split_range(ptiles + ttiles, a_splits, split, t0, t1);
 
     const unsigned short* kp = (const unsigned short*)a.Kp + (long long)b * a.kps[0] + (long long)hk * a.kps[1];
     const unsigned short* vp = (const unsigned short*)a.Vp + (long long)b * a.vps[0] + (long long)hk * a.vps[1];
@@ -201,7 +206,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     auto request_tile = [&](int t, int buf) {
         const bool tree = t >= ptiles;
         const int key0 = tree ? (t - ptiles) * TK : t * TK;
-        const int last = (tree ? a.nk : L) - 1;
+        const int last = (tree ? a_nk : L) - 1;
         const long long ks = tree ? a.kts[2] : a.kps[2];
         const long long vs = tree ? a.vts[2] : a.vps[2];
         const unsigned short* kbase = tree ? kt : kp;
@@ -268,7 +273,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 
         const bool tree = t >= ptiles;
         const int key0 = tree ? (t - ptiles) * TK : t * TK;
-        const int kend = tree ? a.nk : L;
+        const int kend = tree ? a_nk : L;
 
         // one 32-key block at a time: S^T = K Q^T, online softmax, O^T += V^T P^T
 #pragma unroll
@@ -377,7 +382,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     }
     const bool holder = WIDE || kh == 0;         // this wavefront holds finished (O, m, l) of its 32 rows
 
-    if (a.splits == 1) {
+    if (a_splits == 1) {
         if (holder && row_ok) {
             const float inv = l_run > 0.f ? 1.f / l_run : 0.f;
             unsigned short* orow =
@@ -409,9 +414,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     // part_ml [group][split][query block][row] (m c, l)
     typedef unsigned long long u64;
     auto pack2 = [](float x, float y) -> u64 { return (u64)__float_as_uint(x) | ((u64)__float_as_uint(y) << 32); };
-    const int group = bz * a.row_blocks + rb;
+    const int group = bz * a_row_blocks + rb;
     if (holder) {
-        u64* po = (u64*)a.part_o + (((size_t)group * a.splits + split) * NQB + qb) * (DB * 8 * 64) + lane;
+        u64* po = (u64*)a.part_o + (((size_t)group * a_splits + split) * NQB + qb) * (DB * 8 * 64) + lane;
 #pragma unroll
         for (int d = 0; d < DB; ++d)
 #pragma unroll
@@ -419,7 +424,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                 __hip_atomic_store(po + (d * 8 + v2) * 64, pack2(oacc[d][2 * v2], oacc[d][2 * v2 + 1]), __ATOMIC_RELAXED,
                                    __HIP_MEMORY_SCOPE_AGENT);
         if (h == 0)                                                  // lanes l and l + 32 hold the same row
-            __hip_atomic_store((u64*)a.part_ml + (((size_t)group * a.splits + split) * NQB + qb) * 32 + l32,
+            __hip_atomic_store((u64*)a.part_ml + (((size_t)group * a_splits + split) * NQB + qb) * 32 + l32,
                                pack2(m_run == -INFINITY ? -INFINITY : m_run * c /* log2 units */, l_run),
                                __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
@@ -427,7 +432,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     __syncthreads();
     if (tid == 0)
         s_last = __hip_atomic_fetch_add(a.counters + group, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
-                         (unsigned)(a.splits - 1) ? 1 : 0;
+                         (unsigned)(a_splits - 1) ? 1 : 0;
     __syncthreads();
     if (!s_last) return;
     if (tid == 0) __hip_atomic_store(a.counters + group, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // for the next launch
@@ -439,19 +444,19 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     // CHUNK splits at a time: all their loads are issued before the first one is used (each is a trip to
     // memory), and the running maximum M is carried from chunk to chunk like in the main loop.
     constexpr int CHUNK = 48 / (DC * 8) > 4 ? 4 : (48 / (DC * 8) < 1 ? 1 : 48 / (DC * 8));   // register budget
-    const u64* mlp = (const u64*)a.part_ml + ((size_t)group * a.splits * NQB + cq) * 32 + l32;
-    const u64* pp = (const u64*)a.part_o + ((size_t)group * a.splits * NQB + cq) * (DB * 8 * 64) + d0 * 8 * 64 + lane;
+    const u64* mlp = (const u64*)a.part_ml + ((size_t)group * a_splits * NQB + cq) * 32 + l32;
+    const u64* pp = (const u64*)a.part_o + ((size_t)group * a_splits * NQB + cq) * (DB * 8 * 64) + d0 * 8 * 64 + lane;
     float M = -INFINITY, Ls = 0.f;
     f32x16 acc[DC];
 #pragma unroll
     for (int d = 0; d < DC; ++d)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[d][v] = 0.f;
-    for (int s0 = 0; s0 < a.splits; s0 += CHUNK) {
+    for (int s0 = 0; s0 < a_splits; s0 += CHUNK) {
         u64 ml[CHUNK], x[CHUNK][DC * 8];
 #pragma unroll
         for (int i = 0; i < CHUNK; ++i) {
-            const int si = s0 + i < a.splits ? s0 + i : a.splits - 1;      // past the end: a copy, weight 0
+            const int si = s0 + i < a_splits ? s0 + i : a_splits - 1;      // past the end: a copy, weight 0
             ml[i] = __hip_atomic_load(mlp + (size_t)si * NQB * 32, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             const u64* ps = pp + (size_t)si * NQB * (DB * 8 * 64);
 #pragma unroll
@@ -461,7 +466,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         float mi[CHUNK], m_new = M;
 #pragma unroll
         for (int i = 0; i < CHUNK; ++i) {
-            mi[i] = s0 + i < a.splits ? __uint_as_float((unsigned)ml[i]) : -INFINITY;
+            mi[i] = s0 + i < a_splits ? __uint_as_float((unsigned)ml[i]) : -INFINITY;
             m_new = fmaxf(m_new, mi[i]);
         }
         if (m_new == -INFINITY) continue;                                    // nothing visible so far
@@ -484,8 +489,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         M = m_new;
     }
     const int rho2 = rb * ROWS + cq * 32 + l32;
-    if (rho2 < a.g * n) {
-        const int hq2 = hk * a.g + rho2 / n, node2 = rho2 % n;
+    if (rho2 < a_g * n) {
+        const int hq2 = hk * a_g + rho2 / n, node2 = rho2 % n;
         const float inv = Ls > 0.f ? 1.f / Ls : 0.f;
         unsigned short* orow =
             (unsigned short*)a.O + (long long)b * a.os[0] + (long long)hq2 * a.os[1] + (long long)node2 * a.os[2];
@@ -760,18 +765,20 @@ int launch_tree_attention(const ot_attn_params& p, const AttnPlan& plan, const v
         if (plan.splits > 1 && (long long)p.batch * p.kv_heads * plan.row_blocks * 4 > OT_ATTN_SYNC_BYTES)
             return OT_ERR_UNSUPPORTED;      // cannot happen: splits > 1 only with few workgroups
         const dim3 grid((unsigned)wgs);
+#define OT_ATTN_ARGS a.prefix_len, a.mask, a.Q, a.row_blocks, a.splits, a.kv_heads, a.g, a.n, a.max_prefix, a.nk, a.W, a
 #define OT_ATTN_LAUNCH(DD, WW)                                                                             \
     do {                                                                                                   \
         const size_t lds = (size_t)((WW) ? 2 : OT_ATTN_NBUF_NARROW) * 64 * DD * sizeof(unsigned int);      \
         if (lds > 64 * 1024)                                                                               \
             OT_HIP_CHECK(hipFuncSetAttribute((const void*)attn_mfma_kernel<DD, WW>,                        \
                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));       \
-        if (ev0 || ev1) hipExtLaunchKernelGGL((attn_mfma_kernel<DD, WW>), grid, dim3(256), lds, s, ev0, ev1, 0, a); \
-        else hipLaunchKernelGGL((attn_mfma_kernel<DD, WW>), grid, dim3(256), lds, s, a);                   \
+        if (ev0 || ev1) hipExtLaunchKernelGGL((attn_mfma_kernel<DD, WW>), grid, dim3(256), lds, s, ev0, ev1, 0, OT_ATTN_ARGS); \
+        else hipLaunchKernelGGL((attn_mfma_kernel<DD, WW>), grid, dim3(256), lds, s, OT_ATTN_ARGS);        \
     } while (0)
         if (p.head_dim == 128) { if (wide) OT_ATTN_LAUNCH(128, true); else OT_ATTN_LAUNCH(128, false); }
         else                   { if (wide) OT_ATTN_LAUNCH(64, true); else OT_ATTN_LAUNCH(64, false); }
 #undef OT_ATTN_LAUNCH
+#undef OT_ATTN_ARGS
     } else {
         const dim3 grid(plan.splits, plan.row_blocks, p.batch * p.q_heads);
         if (ev0 || ev1) {

@@ -39,6 +39,7 @@ struct SelKArgs {
     ot_tree_out out;
     int32_t* frontier_token; int32_t* frontier_parent;        // [batch][n]         (streaming step)
     int step;
+    int rehearse;                                             // fast kernel: 1 if the launch has LDS for the rehearsing wavefront
 };
 
 __device__ __forceinline__ double nan_d() { return __longlong_as_double(0x7ff8000000000000ll); }   // "absent"
@@ -954,10 +955,14 @@ struct FastLds {
     unsigned short* meta;     // [DMAX][64]        pool: parent slot | rank << 8
     unsigned char* oidx;      // [DMAX][64]        output index of a selected pool node
 };
-__host__ __device__ inline size_t fast_lds_bytes(int rows, int KMAX, int DMAX) {
+// pool keys, key table, meta, output indices: the part of the LDS layout the final selection works on
+__host__ __device__ inline size_t fast_pool_bytes(int KMAX, int DMAX) {
     const int km = KMAX < 4 ? 4 : KMAX;               // the table doubles as 64 x 16 bytes of node records
-    return (size_t)(rows + 1) * KMAX * 8 + (size_t)DMAX * 64 * 8 + (size_t)km * 64 * 8 + (size_t)DMAX * 64 * 2 +
-           (size_t)DMAX * 64;
+    return (size_t)DMAX * 64 * 8 + (size_t)km * 64 * 8 + (size_t)DMAX * 64 * 2 + (size_t)DMAX * 64;
+}
+// rehearse: a second copy of the pool part for the wavefront that rehearses the final selection
+__host__ __device__ inline size_t fast_lds_bytes(int rows, int KMAX, int DMAX, bool rehearse) {
+    return (size_t)(rows + 1) * KMAX * 8 + fast_pool_bytes(KMAX, DMAX) * (rehearse ? 2 : 1);
 }
 
 // p^ = e^key for key <= 0, to about 1e-7 relative: fp32 exp2 of the leading part of key * log2(e), first-order
@@ -973,12 +978,15 @@ __device__ __forceinline__ double exp_of_logp(double key) {
 // running set, one (log p^, p^) per lane; after every step the new layer is merged into it (top n of at most
 // 2n keys, two per lane), E_sub(T, n) is the sum of its p^, and drafting stops when E_sub - E <= delta.
 template <int KMAX, int DMAX, bool ADAPT>
-__global__ __launch_bounds__(256) void tree_fast_kernel(const SelKArgs a) {
+// The leading scalar arguments repeat fields of `a`: they are what the prologue's loads need, and as separate
+// arguments the hardware hands them over in registers at wavefront start (kernel-argument preload), so the loads
+// go out without waiting for a read of the argument block.
+__global__ __launch_bounds__(256) void tree_fast_kernel(const float* row_topv, const double* row_lse, const int k,
+                                                        const int rows, const SelKArgs a) {
     extern __shared__ __attribute__((aligned(16))) u64 smem[];
-    __shared__ int s_hist[kBuckets + 4];
-    const int tid = threadIdx.x, b = blockIdx.x, k = a.k, n = a.n;
+    __shared__ int s_hist2[2][kBuckets + 4];
+    const int tid = threadIdx.x, b = blockIdx.x, n = a.n;
     int D = a.depth;                                  // ADAPT: becomes the number of steps drafted
-    const int rows = a.rows_per_seq;
     FastLds P;
     P.dl = (double*)smem;
     P.key = P.dl + (size_t)(rows + 1) * KMAX;
@@ -988,11 +996,11 @@ __global__ __launch_bounds__(256) void tree_fast_kernel(const SelKArgs a) {
     const size_t rbase = (size_t)b * rows;
 
     // ---- prologue, all four wavefronts ----
-    for (int i = tid; i < kBuckets + 4; i += 256) s_hist[i] = 0;
+    for (int i = tid; i < 2 * (kBuckets + 4); i += 256) (&s_hist2[0][0])[i] = 0;
     // one row per thread and pass: lse once, the k logits of the row, k subtractions; row `rows` is all NaN
     {
-        const float* tv = a.row_topv + rbase * k;
-        const double* tl = a.row_lse + rbase;
+        const float* tv = row_topv + rbase * k;
+        const double* tl = row_lse + rbase;
         for (int row = tid; row <= rows; row += 256) {
             const bool real = row < rows;
             const double lse = real ? tl[row] : nan_d();
@@ -1009,8 +1017,28 @@ __global__ __launch_bounds__(256) void tree_fast_kernel(const SelKArgs a) {
         }
     }
     __syncthreads();
-    if (tid >= 64) return;
-    const int lane = tid;
+    // Wavefront 0 builds the tree.  The kernel's one workgroup lands on a different compute unit from launch to
+    // launch, and the first pass through the final selection then waits about 2 us for its instructions.  So while
+    // wavefront 0 is drafting, wavefront 1 rehearses the final selection once on made-up keys in an LDS region of
+    // its own: the same instructions, no global memory access, results discarded.  (Rehearsing a drafting step in
+    // a third wavefront was tried: wavefront 0 reaches that code too soon for it to help.)
+    const bool live = __builtin_amdgcn_readfirstlane(tid) < 64;
+    if (tid >= (a.rehearse ? 128 : 64)) return;
+    const int lane = tid & 63;
+    int* const s_hist = s_hist2[live ? 0 : 1];
+    if (!live) {
+        char* sh = (char*)smem + (size_t)(rows + 1) * KMAX * 8 + fast_pool_bytes(KMAX, DMAX);
+        P.key = (double*)sh;
+        P.kt = P.key + DMAX * 64;
+        P.meta = (unsigned short*)(P.kt + (KMAX < 4 ? 4 : KMAX) * 64);
+        P.oidx = (unsigned char*)(P.meta + DMAX * 64);
+#pragma unroll
+        for (int t = 0; t < DMAX; ++t) {              // distinct keys, every node a first child of the slot above it
+            P.key[t * 64 + lane] = -0.5 - 0.01 * (double)(t * 64 + lane);
+            P.meta[t * 64 + lane] = (unsigned short)lane;
+        }
+        lds_sync<true>();
+    }
     Group<true> g;
     g.red = nullptr; g.bc = nullptr; g.redd = nullptr;
     g.phase = g.bphase = g.dphase = 0;
@@ -1019,7 +1047,7 @@ __global__ __launch_bounds__(256) void tree_fast_kernel(const SelKArgs a) {
     double run_key = nan_d(), run_p = 0.0;            // ADAPT: this lane's member of the running top-n set
     double E_prev = 0.0, E_sub = 0.0;                 // ADAPT: E of Algorithm 1's loop, latest E_sub(T, n)
     // ---- Algorithm 1, step by step ----
-    for (int t = 0; t < D; ++t) {
+    for (int t = 0; live && t < D; ++t) {
         const int F = a.F[t], Fn = a.F[t + 1];
         const bool active = lane < F;
         const double* drow = P.dl + (size_t)(active ? a.row_start[t] + lane : rows) * KMAX;
@@ -1087,7 +1115,7 @@ __global__ __launch_bounds__(256) void tree_fast_kernel(const SelKArgs a) {
             }
         }
     }
-    if (ADAPT && lane == 0) { a.steps_used[b] = D; a.e_sub[b] = E_sub; }
+    if (ADAPT && live && lane == 0) { a.steps_used[b] = D; a.e_sub[b] = E_sub; }
 
     // ---- last line of Algorithm 1: the n best nodes of the pool ----
     int pool_nodes = 0;
@@ -1105,7 +1133,7 @@ __global__ __launch_bounds__(256) void tree_fast_kernel(const SelKArgs a) {
 #pragma unroll
     for (int t = 0; t < DMAX; ++t) {                  // token ids: in flight during the selection
         tk[t] = 0;
-        if (t < D && lane < a.F[t + 1]) tk[t] = ti[(a.row_start[t] + (mt[t] & 255)) * k + (mt[t] >> 8)];
+        if (live && t < D && lane < a.F[t + 1]) tk[t] = ti[(a.row_start[t] + (mt[t] & 255)) * k + (mt[t] >> 8)];
     }
     unsigned int sel = 0;                             // bit t: pool node (layer t+1, slot lane) is in the tree
     if (pool_nodes <= n) {
@@ -1252,7 +1280,7 @@ __global__ __launch_bounds__(256) void tree_fast_kernel(const SelKArgs a) {
         m |= (u64)lo32 | ((u64)hi32 << 32);
         anc = __shfl(anc, anc);
     }
-    if (lane < n) {
+    if (live && lane < n) {
         const size_t o = (size_t)b * n + lane;
         a.out.token[o] = tok;
         a.out.parent[o] = par;
@@ -1262,7 +1290,7 @@ __global__ __launch_bounds__(256) void tree_fast_kernel(const SelKArgs a) {
     }
     // E = sum of p^ (Eq. 3)
     const double e_sum = wave_sum_d(node ? exp_of_logp(key) : 0.0);
-    if (lane == 0) {
+    if (live && lane == 0) {
         a.out.expect[b] = e_sum;
         a.out.n_out[b] = n_out;
     }
@@ -1289,6 +1317,7 @@ SelKArgs make_args(const SelectGeometry& g, const BuildWorkspace& ws) {
     a.out = ot_tree_out{nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
     a.frontier_token = nullptr; a.frontier_parent = nullptr;
     a.step = 0;
+    a.rehearse = 0;
     return a;
 }
 
@@ -1359,10 +1388,13 @@ constexpr size_t kFastLdsLimit = 144 * 1024;
 
 template <int KMAX, int DMAX, bool ADAPT>
 int launch_fast_t(const SelKArgs& a, int batch, hipStream_t s) {
-    const size_t lds = fast_lds_bytes(a.rows_per_seq, KMAX, DMAX);
+    SelKArgs k = a;
+    k.rehearse = fast_lds_bytes(a.rows_per_seq, KMAX, DMAX, true) <= kFastLdsLimit ? 1 : 0;
+    const size_t lds = fast_lds_bytes(a.rows_per_seq, KMAX, DMAX, k.rehearse != 0);
     int st = set_lds(tree_fast_kernel<KMAX, DMAX, ADAPT>, lds);
     if (st != OT_OK) return st;
-    hipLaunchKernelGGL((tree_fast_kernel<KMAX, DMAX, ADAPT>), dim3(batch), dim3(256), lds, s, a);
+    hipLaunchKernelGGL((tree_fast_kernel<KMAX, DMAX, ADAPT>), dim3(batch), dim3(256), lds, s, k.row_topv, k.row_lse, k.k,
+                       k.rows_per_seq, k);
     OT_HIP_CHECK(hipGetLastError());
     return OT_OK;
 }
@@ -1390,14 +1422,14 @@ int fast_dmax(int d) { return d <= 8 ? 8 : (d <= 10 ? 10 : (d <= 12 ? 12 : (d <=
 int launch_tree_oneshot(const SelectGeometry& g, const BuildWorkspace& ws, const ot_tree_out& out, hipStream_t s) {
     SelKArgs a = make_args(g, ws);
     a.out = out;
-    if (g.n <= 64 && fast_lds_bytes(g.rows_per_seq, fast_kmax(g.k), fast_dmax(g.depth)) <= kFastLdsLimit)
+    if (g.n <= 64 && fast_lds_bytes(g.rows_per_seq, fast_kmax(g.k), fast_dmax(g.depth), false) <= kFastLdsLimit)
         return launch_fast<false>(a, g.batch, s);
     const int NT = threads_for(g.n);
     return NT == 64 ? launch_oneshot_s<true>(a, g.batch, NT, s) : launch_oneshot_s<false>(a, g.batch, NT, s);
 }
 
 bool tree_adaptive_supported(const SelectGeometry& g) {
-    return g.n <= 64 && fast_lds_bytes(g.rows_per_seq, fast_kmax(g.k), fast_dmax(g.depth)) <= kFastLdsLimit;
+    return g.n <= 64 && fast_lds_bytes(g.rows_per_seq, fast_kmax(g.k), fast_dmax(g.depth), false) <= kFastLdsLimit;
 }
 
 int launch_tree_adaptive(const SelectGeometry& g, double delta, const BuildWorkspace& ws, const ot_tree_out& out,

@@ -381,8 +381,7 @@ int ot_verify_greedy(const ot_verify_params* p, const void* target_logits, const
     ScanGeometry sg;
     sg.batch = p->batch; sg.vocab = p->vocab; sg.k = 1; sg.dtype = p->logits_dtype;
     sg.nsteps = 1; sg.rows_per_seq = p->n + 1;
-    memset(sg.row_start, 0, sizeof(sg.row_start));
-    sg.row_start[1] = p->n + 1;
+    sg.grow_k = 1; sg.grow_n = 1;
     sg.stride_seq = p->stride_seq; sg.stride_depth = 0; sg.stride_row = p->stride_row;
     st = launch_row_scan(sg, target_logits, ws, s);
     if (st != OT_OK) return st;
