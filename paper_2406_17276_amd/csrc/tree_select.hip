@@ -997,22 +997,35 @@ __global__ __launch_bounds__(256) void tree_fast_kernel(const float* row_topv, c
 
     // ---- prologue, all four wavefronts ----
     for (int i = tid; i < 2 * (kBuckets + 4); i += 256) (&s_hist2[0][0])[i] = 0;
-    // one row per thread and pass: lse once, the k logits of the row, k subtractions; row `rows` is all NaN
+    // one row per thread and pass: lse once, the k logits of the row, k subtractions; row `rows` is all NaN.  The
+    // loads of two passes go out together and unconditionally (indices clamped to valid entries, results
+    // discarded where they do not apply): each trip to memory costs more than the arithmetic of a pass.
     {
         const float* tv = row_topv + rbase * k;
         const double* tl = row_lse + rbase;
-        for (int row = tid; row <= rows; row += 256) {
-            const bool real = row < rows;
-            const double lse = real ? tl[row] : nan_d();
-            float x[KMAX];
+        for (int row0 = tid; row0 <= rows; row0 += 512) {
+            float x[2][KMAX];
+            double lse[2];
 #pragma unroll
-            for (int r = 0; r < KMAX; ++r) x[r] = (real && r < k) ? tv[row * k + r] : 0.f;
+            for (int u = 0; u < 2; ++u) {
+                const int rc = min(row0 + 256 * u, rows - 1);
+                lse[u] = tl[rc];
 #pragma unroll
-            for (int r = 0; r < KMAX; r += 2) {
-                double2 d2;
-                d2.x = r < k ? (double)x[r] - lse : nan_d();            // log p = x - lse (Eq. 2, log space); NaN = absent
-                d2.y = r + 1 < k ? (double)x[r + 1] - lse : nan_d();
-                *(double2*)(P.dl + (size_t)row * KMAX + r) = d2;
+                for (int r = 0; r < KMAX; ++r) x[u][r] = tv[rc * k + min(r, k - 1)];
+            }
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int row = row0 + 256 * u;
+                if (row <= rows) {
+                    const bool real = row < rows;
+#pragma unroll
+                    for (int r = 0; r < KMAX; r += 2) {
+                        double2 d2;                   // log p = x - lse (Eq. 2, log space); NaN = absent
+                        d2.x = (real && r < k) ? (double)x[u][r] - lse[u] : nan_d();
+                        d2.y = (real && r + 1 < k) ? (double)x[u][r + 1] - lse[u] : nan_d();
+                        *(double2*)(P.dl + (size_t)row * KMAX + r) = d2;
+                    }
+                }
             }
         }
     }
