@@ -67,3 +67,30 @@ def assert_tree_equal(got, want_list, n, score_atol=1e-5):
         np.testing.assert_allclose(sc[b, :m], want["score"][:m], rtol=0, atol=score_atol, err_msg=f"seq {b}: score")
         assert np.all(np.isneginf(sc[b, m:]))
         np.testing.assert_allclose(ex[b], want["expect"], rtol=1e-6, err_msg=f"seq {b}: E")
+
+
+def assert_tree_invariants(got, n, depth):
+    """What holds for every tree of Algorithm 1 whatever the input (used where the oracle cannot follow, at full
+    sizes): nodes in (depth, slot) order with parents first, depth = parent's + 1, p^ never grows along a branch
+    (Thm. 3.1), siblings carry distinct tokens, mask = parent's mask + own bit, E = sum of p^ (Eq. 3)."""
+    tok = got.token.cpu().numpy(); par = got.parent.cpu().numpy(); dep = got.depth.cpu().numpy()
+    sc = got.score.cpu().numpy().astype(np.float64); nout = got.n_out.cpu().numpy(); ex = got.expect.cpu().numpy()
+    msk = got.mask.cpu().numpy().view(np.uint64).reshape(tok.shape[0], n, -1)
+    for b in range(tok.shape[0]):
+        m = int(nout[b])
+        assert 1 <= m <= n
+        assert np.all(np.diff(dep[b, :m]) >= 0) and dep[b, 0] == 1 and dep[b, m - 1] <= depth
+        seen = set()
+        for i in range(m):
+            p = int(par[b, i])
+            assert -1 <= p < i, (b, i, p)
+            assert dep[b, i] == (1 if p < 0 else dep[b, p] + 1)
+            assert p < 0 or sc[b, i] <= sc[b, p] + 1e-6
+            assert sc[b, i] <= 1e-6
+            assert (p, int(tok[b, i])) not in seen, "two children of one node carry the same token"
+            seen.add((p, int(tok[b, i])))
+            want = np.zeros(msk.shape[2], dtype=np.uint64) if p < 0 else msk[b, p].copy()
+            want[i // 64] |= np.uint64(1) << np.uint64(i % 64)
+            np.testing.assert_array_equal(msk[b, i], want)
+        assert np.all(par[b, m:] == -1) and np.all(tok[b, m:] == -1) and not msk[b, m:].any()
+        np.testing.assert_allclose(ex[b], np.exp(sc[b, :m]).sum(), rtol=5e-6)      # score is stored as float32

@@ -39,6 +39,38 @@ def test_70b_shape_batched_subset():
     U.assert_tree_equal(got, want, w.n)
 
 
+def test_70b_full_batch_as_the_bench_launches_it():
+    # all 16 sequences in one launch; sequences 0, 5, 10, 15 against the oracle, the invariants on every one
+    w = wl.WORKLOADS["70b"]
+    seed, _, want = U.gapped_logits(w, 0, seqs=[0, 5, 10, 15])
+    logits = wl.make_logits(w, seed)
+    got = _run(logits, w.dtype, w.k, w.n, w.depth)
+    U.assert_tree_invariants(got, w.n, w.depth)
+    import torch
+    from paper_2406_17276_amd import api
+    sub = api.alloc_tree(4, w.n)
+    idx = torch.tensor([0, 5, 10, 15], device="cuda")
+    for name in ("token", "parent", "depth", "score", "mask", "n_out", "expect"):
+        getattr(sub, name).copy_(getattr(got, name)[idx])
+    U.assert_tree_equal(sub, want, w.n)
+
+
+def test_large_budget_shape_full_depth_invariants():
+    # n = 256, k = 16, 20 drafting steps, vocabulary 128256 (four scan parts): two sequences drawn on the device;
+    # the oracle cannot follow at this size, the invariants of Algorithm 1's output must hold
+    import torch
+    from paper_2406_17276_amd import api
+    w = wl.WORKLOADS["large"]
+    g = torch.Generator(device="cuda"); g.manual_seed(5)
+    x = torch.empty((2, w.depth, w.n, w.vocab), dtype=torch.bfloat16, device="cuda")
+    for t in range(w.depth):                                          # step by step: keeps the fp32 temporary small
+        x[:, t] = (torch.randn((2, w.n, w.vocab), generator=g, device="cuda") * 3.0).to(torch.bfloat16)
+    got = api.build_tree(x, w.k, w.n, w.depth)
+    torch.cuda.synchronize()
+    assert int(got.n_out.min()) == w.n
+    U.assert_tree_invariants(got, w.n, w.depth)
+
+
 def test_large_budget_shape_reduced_depth():
     # n=256 (4 mask words, 4 wavefronts), k=16, vocab 128256 split over 4 scan parts; 1 sequence, and
     # 6 instead of 20 drafting steps so that the oracle finishes in ~20 s
