@@ -91,6 +91,45 @@ def test_large_budget_shape_one_kv_group():
     assert np.abs(got[:, qh] - want).max() < TOL[w.dtype]
 
 
+def _stored(t):
+    """Device bf16 tensor -> host array of bf16 bit patterns (the stored form the oracle helpers take)."""
+    import torch
+    return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+@pytest.mark.parametrize("name,groups", [
+    ("70b", [(0, 0), (3, 5), (9, 2), (15, 7)]),        # 16 sequences, GQA 64/8, ragged prefixes around 4096, n = 60
+    ("large", [(0, 3), (31, 6)]),                      # 32 sequences, 32/8 heads, prefix 8192, n = 256
+])
+def test_full_batch_as_the_bench_launches_it_sampled_groups(name, groups):
+    """The whole batch in one launch, inputs drawn on the device; the oracle recomputes sampled (sequence, KV head)
+    groups from the slices it needs."""
+    import torch
+    from paper_2406_17276_amd import api
+    w = wl.WORKLOADS[name]
+    B, g = w.batch, w.q_heads // w.kv_heads
+    gen = torch.Generator(device="cuda"); gen.manual_seed(17)
+    draw = lambda *shape: torch.randn(shape, generator=gen, device="cuda").to(torch.bfloat16)
+    Lmax = w.max_prefix()
+    Q = draw(B, w.q_heads, w.n, w.head_dim)
+    Kp, Vp = draw(B, w.kv_heads, Lmax, w.head_dim), draw(B, w.kv_heads, Lmax, w.head_dim)
+    Kt, Vt = draw(B, w.kv_heads, w.n, w.head_dim), draw(B, w.kv_heads, w.n, w.head_dim)
+    plen = wl.prefix_lengths(w, 4).astype(np.int32)
+    mask = _random_masks(B, w.n, 23)
+    out = api.tree_verify_attention(Q, Kp, Vp, Kt, Vt, torch.from_numpy(plen).cuda(), U.mask_to_device(mask))
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(out.float()).all())
+    for b, kvh in groups:
+        qh = slice(kvh * g, kvh * g + g)
+        sub = dict(Q=_stored(Q[b:b + 1, qh]), K_prefix=_stored(Kp[b:b + 1, kvh:kvh + 1]),
+                   V_prefix=_stored(Vp[b:b + 1, kvh:kvh + 1]), K_tree=_stored(Kt[b:b + 1, kvh:kvh + 1]),
+                   V_tree=_stored(Vt[b:b + 1, kvh:kvh + 1]), prefix_len=plen[b:b + 1])
+        want = _oracle_attention(sub, mask[b:b + 1], "bf16")
+        got = U.from_device_f64(out[b:b + 1, qh])
+        print(f"{name}: sequence {b}, KV head {kvh}: max-abs err {np.abs(got - want).max():.2e}", flush=True)
+        assert np.abs(got - want).max() < TOL["bf16"]
+
+
 @pytest.mark.parametrize("dtype,B,Hq,Hkv,D,L,n,ragged,shape", [
     ("f32", 2, 4, 4, 64, 128, 16, 0.0, "random"),
     ("f32", 2, 6, 2, 128, 77, 37, 0.3, "random"),      # GQA, ragged, n not a multiple of 16
