@@ -48,7 +48,22 @@ def build(verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed")
     cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
     subprocess.run(cmd, check=True)
+    build_abi_client()
     return LIB
+
+
+def build_abi_client() -> str:
+    """The plain-C caller of the library that the GPU tests run (tests/abi_client.c): gcc, the public header and
+    the HIP runtime only."""
+    src = os.path.join(ROOT, "tests", "abi_client.c")
+    exe = os.path.join(ROOT, "tests", "abi_client")
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    cmd = ["gcc", "-std=c11", "-O2", "-Wall", "-D__HIP_PLATFORM_AMD__", "-I" + os.path.join(ROOT, "include"),
+           "-I" + os.path.join(rocm, "include"), src, "-o", exe, "-L" + HERE, "-lopttree",
+           "-L" + os.path.join(rocm, "lib"), "-lamdhip64", "-Wl,-rpath,$ORIGIN/../paper_2406_17276_amd",
+           "-Wl,-rpath," + os.path.join(rocm, "lib")]
+    subprocess.run(cmd, check=True)
+    return exe
 
 
 if __name__ == "__main__":
