@@ -106,7 +106,7 @@ def main():
                     help="draw every input on the device and skip the oracle check and the CPU baseline (for shapes "
                          "whose oracle run takes hours, e.g. --workload large; the line then says parity_checked: false)")
     ap.add_argument("--main-only", action="store_true", help="skip the adaptive-depth and greedy-verification legs")
-    ap.add_argument("--cpu-steps", type=int, default=4, help="oracle steps timed for cpu_baseline (0 = skip)")
+    ap.add_argument("--cpu-steps", type=int, default=16, help="oracle steps timed for cpu_baseline (0 = skip)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (reference dispatch for scaling rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings)")
