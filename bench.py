@@ -311,6 +311,25 @@ def main():
     if yard:
         result["yardsticks"] = yard
 
+    def graph_us(fn, reps=40):
+        """GPU time per call of fn(i) with the host out of the way: reps calls replayed from one HIP graph."""
+        try:
+            side = torch.cuda.Stream()
+            gr = torch.cuda.CUDAGraph()
+            with torch.cuda.stream(side):
+                with torch.cuda.graph(gr, stream=side):
+                    for i in range(reps):
+                        fn(i)
+            torch.cuda.synchronize()
+            gr.replay()
+            torch.cuda.synchronize()
+            t0g = time.perf_counter()
+            gr.replay()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0g) * 1e6 / reps
+        except Exception:                                       # a measurement aid: never in the way of the line
+            return None
+
     # ---- adaptive depth (Algorithm 1's loop) through the streaming entry points, outside the timed region:
     # begin, then per drafting step expand + E_sub query, then finalize; delta = -1 never stops early, so the
     # figure is the cost of a full-depth loop without the host reading the go-on flags in between.
@@ -319,7 +338,7 @@ def main():
         ts = api.TreeStream(w.batch, w.vocab, w.k, w.n, w.depth, dcode)
         reps = 20
         def adaptive_loop(lg):
-            api._check(api.lib().ot_tree_begin(C.byref(ts.p), ts.ws.data_ptr(), ts.ws.numel(), stream), "ot_tree_begin")
+            api._check(api.lib().ot_tree_begin(C.byref(ts.p), ts.ws.data_ptr(), ts.ws.numel(), api._stream()), "ot_tree_begin")
             ts.step = 0
             for t in range(w.depth):
                 ts.expand(lg[:, t])
@@ -345,7 +364,9 @@ def main():
             one_shot_us = (time.perf_counter() - ta) * 1e4
         except api.OptTreeError:
             pass                                  # shape off the single-wavefront path
-        result["adaptive_depth"] = {"one_shot_us_per_tree": one_shot_us, "us_per_tree": us_loop, "us_per_drafting_step": us_loop / w.depth, "steps": w.depth,
+        loop_graph_us = graph_us(lambda i: adaptive_loop(builds[i % ring].logits), reps=8)
+        result["adaptive_depth"] = {"one_shot_us_per_tree": one_shot_us, "us_per_tree": us_loop,
+                                    "us_per_tree_graph_replay": loop_graph_us, "us_per_drafting_step": us_loop / w.depth, "steps": w.depth,
                                     "delta": -1.0, "calls_per_step": "ot_tree_expand + ot_tree_esub"}
 
     # ---- greedy verification + K/V append of the same shape, outside the timed region: target rows for the root
@@ -369,6 +390,7 @@ def main():
             verify_once(i)
         torch.cuda.synchronize()
         result["greedy_verify"] = {"us_per_call_pair": (time.perf_counter() - tv) * 1e4,
+                                   "us_per_call_pair_graph_replay": graph_us(verify_once),
                                    "calls": "ot_verify_greedy + ot_kv_append",
                                    "target_rows": w.batch * (w.n + 1), "target_bytes": w.batch * (w.n + 1) * w.vocab * w.elem_bytes()}
 
@@ -387,6 +409,7 @@ def main():
             sample_once(i)
         torch.cuda.synchronize()
         result["sampled_verify"] = {"us_per_call_pair": (time.perf_counter() - tv) * 1e4,
+                                    "us_per_call_pair_graph_replay": graph_us(sample_once),
                                     "calls": "ot_verify_sample + ot_kv_append", "temperature": 1.0,
                                     "target_rows": w.batch * (w.n + 1)}
 
