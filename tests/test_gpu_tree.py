@@ -111,6 +111,7 @@ def _random_case(V, k, n, d, B, dtype, seed, scale=3.0):
     (300, 16, 40, 2, 2, "f32"),        # depth 2: first cut at the second step
     (300, 3, 64, 7, 3, "f32"),         # frontier grows 1, 3, 9, 27, 64
     (300, 4, 64, 8, 50, "f32"),        # 17050 rows: more work items than workgroups (grid-stride scan)
+    (262144, 16, 6, 2, 1, "bf16"),     # maximum vocabulary: eight scan parts per row, maximum k
 ])
 def test_random_shapes_and_edges(V, k, n, d, B, dtype):
     stored, want = _random_case(V, k, n, d, B, dtype, seed=V + k + n)
