@@ -134,6 +134,7 @@ def test_sampled_verification_matches_oracle(V, k, n, d, B, dtype, agree, T):
 @pytest.mark.parametrize("V,n,B,dtype,T,scale,masked", [
     (32000, 50, 2, "bf16", 1.0, 2.0, 0),           # 7B shape
     (128256, 12, 1, "bf16", 0.8, 3.0, 0),          # 251 segments: four per lane of the picking wavefront
+    (262144, 3, 1, "bf16", 1.0, 3.0, 0),           # the largest supported row: 512 segments, eight per lane
     (1001, 20, 2, "f32", 1.3, 1.0, 0),             # rows not 16-byte aligned: element loads, ragged last vector
     (1003, 7, 1, "bf16", 0.9, 2.0, 0),             # the same for bf16 rows (2006 bytes apart)
     (5000, 9, 1, "bf16", 0.25, 1.5, 3000),         # 3000 tokens masked with -inf, among them whole segments
