@@ -118,7 +118,8 @@ def main():
 
     import torch
     from oracle import tree_attention as ta_oracle
-    from paper_2406_17276_amd import api, workloads as wl
+    import workloads as wl
+    from paper_2406_17276_amd import api
     from tests import _util as U
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"

@@ -15,7 +15,10 @@
  *   - the library keeps no global device state: scratch lives in a caller-owned
  *     workspace sized by the *_workspace_bytes query.  Concurrent calls must use
  *     distinct workspaces;
- *   - device pointers must be 16-byte aligned;
+ *   - alignment of device pointers: workspaces and the attention tensors (Q, K, V, O) 16 bytes; logits
+ *     rows the size of one element (rows that are 16-byte aligned, with strides and a vocabulary that are
+ *     multiples of 16 bytes, take the vector-load path, anything else a slower element-load path); int32 /
+ *     float arrays 4 bytes; uint64 / double arrays 8 bytes;
  *   - arguments are validated on the host before anything is launched; an
  *     invalid call enqueues nothing.
  */
@@ -125,29 +128,24 @@ OT_API int ot_build_tree_adaptive(const ot_build_params* p, double delta, const 
  *   ot_tree_expand  consumes the F_t rows of step t (row (b,j) at
  *                   rows + b*stride_seq + j*stride_row) and writes the next
  *                   frontier: token and parent slot of its F_{t+1} slots
- *                   ([batch][n] each, entries >= F_{t+1} untouched); steps must
- *                   be fed in order t = 0,1,..;
+ *                   ([batch][n] each, entries >= F_{t+1} untouched) and, if
+ *                   frontier_count is not NULL, frontier_count[b] = F_{t+1}, the
+ *                   rows the draft model has to produce for sequence b in the
+ *                   next step (0 for a sequence that ot_tree_esub has stopped:
+ *                   its frontier outputs are left as they were); steps must be
+ *                   fed in order t = 0,1,..;
  *   ot_tree_finalize selects and emits the tree over the steps fed so far.
  * The three calls of one tree must use the same workspace and stream order. */
 OT_API int ot_tree_begin(const ot_build_params* p, void* workspace, size_t workspace_bytes, void* hip_stream);
 OT_API int ot_tree_expand(const ot_build_params* p, int32_t step, const void* rows,
                    int64_t stride_seq, int64_t stride_row,
                    void* workspace, size_t workspace_bytes,
-                   int32_t* frontier_token, int32_t* frontier_parent_slot, void* hip_stream);
+                   int32_t* frontier_token, int32_t* frontier_parent_slot, int32_t* frontier_count,
+                   void* hip_stream);
 OT_API int ot_tree_finalize(const ot_build_params* p, int32_t steps_done,
                      void* workspace, size_t workspace_bytes,
                      const ot_tree_out* out, void* hip_stream);
 
-/* Adaptive depth: the loop condition of Algorithm 1 ("while ... E_sub(T,n) - E > delta: E <- E_sub(T,n);
- * drafting step").  Called after the expand of step steps_done-1, ot_tree_esub computes, per sequence,
- *   e_sub[b] = E_sub(T, n): the sum of the n largest p^ among the nodes drafted so far (Sec. 3: the best
- *              E over the root-containing n-node subtrees of T; non-decreasing in the steps, Thm. 3.2),
- *   go_on[b] = 1 if e_sub[b] - E[b] > delta, and then E[b] <- e_sub[b]; else 0.   (E[b] = 0 after begin.)
- * e_sub (double[batch]) and go_on (int32[batch]) are device pointers.  A sequence whose go_on was 0 is
- * frozen: later ot_tree_expand calls leave its tree and its frontier outputs untouched, later ot_tree_esub
- * calls return go_on = 0 for it, and ot_tree_finalize selects among the layers it had when it stopped.
- * The caller ends the loop when no go_on is set or the maximum depth p->depth is reached.
- * Returns OT_ERR_INVALID_ARG for steps_done outside 1..depth, a NaN delta, or null / misaligned pointers. */
 /* Drafting-phase attention masks.  The draft model's forward of a drafting step feeds the frontier (at most n
  * tokens) and attends to the K/V of everything drafted so far (Sec. 4, last paragraph); its tree attention
  * mask (Algorithm 2's mask, here per drafting step) is kept incrementally by ot_tree_expand: a node's mask is
@@ -161,13 +159,24 @@ OT_API int ot_tree_finalize(const ot_build_params* p, int32_t steps_done,
 OT_API int ot_tree_frontier_mask(const ot_build_params* p, int32_t steps_done,
                           void* workspace, size_t workspace_bytes, uint64_t* mask, void* hip_stream);
 
+/* Adaptive depth: the loop condition of Algorithm 1 (drafting goes on while E_sub(T,n) - E > delta, and E takes
+ * the value of E_sub before every further step).  Called after the expand of step steps_done-1, ot_tree_esub
+ * computes, per sequence,
+ *   e_sub[b] = E_sub(T, n): the sum of the n largest p^ among the nodes drafted so far (Sec. 3: the best
+ *              E over the root-containing n-node subtrees of T; non-decreasing in the steps, Thm. 3.2),
+ *   go_on[b] = 1 if e_sub[b] - E[b] > delta, and then E[b] <- e_sub[b]; else 0.   (E[b] = 0 after begin.)
+ * e_sub (double[batch]) and go_on (int32[batch]) are device pointers.  A sequence whose go_on was 0 is
+ * frozen: later ot_tree_expand calls leave its tree and its frontier outputs untouched, later ot_tree_esub
+ * calls return go_on = 0 for it, and ot_tree_finalize selects among the layers it had when it stopped.
+ * The caller ends the loop when no go_on is set or the maximum depth p->depth is reached.
+ * Returns OT_ERR_INVALID_ARG for steps_done outside 1..depth, a NaN delta, or null / misaligned pointers. */
 OT_API int ot_tree_esub(const ot_build_params* p, int32_t steps_done, double delta,
                  void* workspace, size_t workspace_bytes,
                  double* e_sub, int32_t* go_on, void* hip_stream);
 
 /* ------------------------------------------------------------------------
  * Tree-masked verification attention (Algorithm 2: the target model's forward
- * over T_opt with "the corresponding tree attention mask").
+ * over T_opt under the tree attention mask that belongs to it).
  *
  * For sequence b, query head h, node i:
  *   O[b,h,i,:] = sum_j softmax_j(scale * Q[b,h,i,:] . K[b,h/g,j,:]) V[b,h/g,j,:]
@@ -179,7 +188,9 @@ OT_API int ot_tree_esub(const ot_build_params* p, int32_t steps_done, double del
  *
  * Element (b,h,r,c) of a tensor is at base + b*s[0] + h*s[1] + r*s[2] + c
  * (strides in elements, multiples of 16 bytes; last dimension contiguous).
- * prefix_len[b] is clamped to [0, max_prefix] on the device.
+ * prefix_len[b] is clamped to [0, max_prefix] on the device; when a value had to be clamped, bit 0 of the
+ * 32-bit word at byte OT_ATTN_STATUS_OFFSET of the workspace is set (it stays set until the workspace is
+ * prepared again or the caller clears the word), so that a caller can tell a truncated cache from a good one.
  * ---------------------------------------------------------------------- */
 typedef struct ot_attn_params {
     int32_t batch, q_heads, kv_heads;   /* q_heads % kv_heads == 0 */
@@ -206,6 +217,8 @@ OT_API size_t ot_attn_workspace_bytes(const ot_attn_params* p);     /* 0 if p is
  * a caller may equally clear them itself.  Returns OT_OK, OT_ERR_INVALID_ARG (null or misaligned
  * workspace), OT_ERR_WORKSPACE_TOO_SMALL or OT_ERR_HIP. */
 #define OT_ATTN_SYNC_BYTES 4096
+#define OT_ATTN_STATUS_OFFSET (OT_ATTN_SYNC_BYTES - 4)   /* status word of the calls made with this workspace */
+#define OT_ATTN_STATUS_PREFIX_CLAMPED 1u                 /* some prefix_len[b] was outside [0, max_prefix] */
 OT_API int ot_attn_workspace_prepare(void* workspace, size_t workspace_bytes, void* hip_stream);
 
 OT_API int ot_tree_verify_attention(const ot_attn_params* p,
@@ -276,7 +289,10 @@ OT_API int ot_verify_sample(const ot_verify_params* p, float temperature, const 
  * accept_node[b][j] are copied to prefix row prefix_len[b] + j of every KV head, and
  * new_prefix_len[b] = min(prefix_len[b] + A - 1, max_prefix); rows that do not fit in max_prefix are dropped.
  * Uses batch, kv_heads, head_dim, n, max_prefix, dtype and the K/V strides of `p` (the attention call's
- * parameters).  K_tree / V_tree must not overlap the prefix rows that are written.  Needs no workspace. */
+ * parameters).  K_tree / V_tree must not overlap the prefix rows that are written.  new_prefix_len must not
+ * overlap prefix_len (workgroups that copy rows still read prefix_len[b] when new_prefix_len[b] is written):
+ * a call whose two length arrays overlap returns OT_ERR_INVALID_ARG; a decoder alternates between two arrays.
+ * Needs no workspace. */
 OT_API int ot_kv_append(const ot_attn_params* p, void* K_prefix, void* V_prefix,
                  const void* K_tree, const void* V_tree,
                  const int32_t* prefix_len, const int32_t* accept_len, const int32_t* accept_node,

@@ -4,4 +4,4 @@ The product is the C-ABI library `libopttree.so` (include/opttree.h); this
 package is its thin ctypes binding.  Importing the package loads nothing; the
 library is opened on first use and its absence is an error, never a fallback.
 """
-__all__ = ["api", "workloads"]
+__all__ = ["api"]

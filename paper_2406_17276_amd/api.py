@@ -79,7 +79,7 @@ def lib():
         L.ot_tree_begin.argtypes = [C.POINTER(BuildParams), C.c_void_p, C.c_size_t, C.c_void_p]
         L.ot_tree_expand.restype = C.c_int
         L.ot_tree_expand.argtypes = [C.POINTER(BuildParams), C.c_int32, C.c_void_p, C.c_int64, C.c_int64,
-                                     C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p]
+                                     C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.ot_tree_finalize.restype = C.c_int
         L.ot_tree_finalize.argtypes = [C.POINTER(BuildParams), C.c_int32, C.c_void_p, C.c_size_t,
                                        C.POINTER(TreeOut), C.c_void_p]
@@ -163,13 +163,23 @@ def alloc_tree(batch: int, n: int, device="cuda") -> Tree:
                 expect=torch.empty((batch,), dtype=torch.float64, device=device))
 
 
+def frontier_sizes(k: int, n: int, depth: int):
+    """Rows the library reads per drafting step: F_0 = 1, F_{t+1} = min(n, k F_t) (ot_build_tree's input
+    contract).  Used only to check tensor extents, which the C ABI cannot see."""
+    F = [1]
+    for _ in range(depth):
+        F.append(min(n, k * F[-1]))
+    return F
+
+
 def build_params(logits, k: int, n: int, depth: int) -> BuildParams:
     """logits: [B, depth, n, V] (any strides with a contiguous last dimension)."""
     if logits.dim() != 4 or logits.stride(3) != 1:
         raise ValueError("logits must be [B, depth, n, V] with a contiguous last dimension")
     B, d, nn, V = logits.shape
-    if d < depth or nn < min(n, max(1, nn)):
-        raise ValueError("logits tensor smaller than (depth, n)")
+    need = max(frontier_sizes(k, n, depth)[:depth]) if depth >= 1 and k >= 1 and n >= 1 else 1
+    if d < depth or nn < need:
+        raise ValueError(f"logits tensor [{B}, {d}, {nn}, {V}] smaller than (depth {depth}, widest frontier {need})")
     return BuildParams(B, V, depth, k, n, _dtype_code(logits), logits.stride(0), logits.stride(1), logits.stride(2))
 
 
@@ -226,6 +236,7 @@ class TreeStream:
         self.ws = torch.empty(need, dtype=torch.uint8, device=device)
         self.frontier_token = torch.full((batch, n), -1, dtype=torch.int32, device=device)
         self.frontier_parent = torch.full((batch, n), -1, dtype=torch.int32, device=device)
+        self.frontier_count = torch.zeros((batch,), dtype=torch.int32, device=device)
         self.step = 0
         _check(lib().ot_tree_begin(C.byref(self.p), self.ws.data_ptr(), self.ws.numel(), _stream()), "ot_tree_begin")
 
@@ -233,9 +244,16 @@ class TreeStream:
         """rows: [B, >=F_t, V]; returns (tokens, parent_slots) views of the next frontier [B, n]."""
         if rows.dim() != 3 or rows.stride(2) != 1:
             raise ValueError("rows must be [B, F, V] with a contiguous last dimension")
+        if self.step >= self.p.depth:
+            raise ValueError(f"all {self.p.depth} drafting steps have been fed")
+        need = frontier_sizes(self.p.k, self.p.n, self.p.depth)[self.step]
+        if rows.shape[0] < self.p.batch or rows.shape[1] < need or rows.shape[2] < self.p.vocab:
+            raise ValueError(f"rows {tuple(rows.shape)} smaller than [batch {self.p.batch}, F_{self.step} = {need}, "
+                             f"vocab {self.p.vocab}]")
         _check(lib().ot_tree_expand(C.byref(self.p), self.step, rows.data_ptr(), rows.stride(0), rows.stride(1),
                                     self.ws.data_ptr(), self.ws.numel(), self.frontier_token.data_ptr(),
-                                    self.frontier_parent.data_ptr(), _stream()), "ot_tree_expand")
+                                    self.frontier_parent.data_ptr(), self.frontier_count.data_ptr(), _stream()),
+               "ot_tree_expand")
         self.step += 1
         return self.frontier_token, self.frontier_parent
 
@@ -301,6 +319,17 @@ def attn_workspace(p: AttnParams, device):
     _check(lib().ot_attn_workspace_prepare(ws.data_ptr(), ws.numel(), _stream()), "ot_attn_workspace_prepare")
     torch.cuda.current_stream().synchronize()      # the workspace may be used on any stream afterwards
     return ws
+
+
+OT_ATTN_STATUS_OFFSET = 4092
+OT_ATTN_STATUS_PREFIX_CLAMPED = 1
+
+
+def attn_status(workspace) -> int:
+    """The status word the attention calls keep in their workspace (bit 0: a prefix length was clamped).
+    Reads device memory: synchronises the current stream."""
+    import torch
+    return int(workspace[OT_ATTN_STATUS_OFFSET:OT_ATTN_STATUS_OFFSET + 4].view(torch.int32).item())
 
 
 def tree_verify_attention(Q, K_prefix, V_prefix, K_tree, V_tree, prefix_len, mask, out=None, workspace=None,

@@ -192,12 +192,14 @@ int ot_tree_begin(const ot_build_params* p, void* workspace, size_t workspace_by
 
 int ot_tree_expand(const ot_build_params* p, int32_t step, const void* rows, int64_t stride_seq, int64_t stride_row,
                    void* workspace, size_t workspace_bytes, int32_t* frontier_token, int32_t* frontier_parent_slot,
-                   void* hip_stream) {
+                   int32_t* frontier_count, void* hip_stream) {
     int st = validate_build(p, false);
     if (st != OT_OK) return st;
     if (step < 0 || step >= p->depth) return OT_ERR_INVALID_ARG;
     if (!rows || !workspace || !frontier_token || !frontier_parent_slot) return OT_ERR_INVALID_ARG;
     if ((uintptr_t)workspace % 16) return OT_ERR_INVALID_ARG;
+    if (((uintptr_t)frontier_token % 4) || ((uintptr_t)frontier_parent_slot % 4) || ((uintptr_t)frontier_count % 4))
+        return OT_ERR_INVALID_ARG;
     const int esize = p->logits_dtype == OT_BF16 ? 2 : 4;
     if ((uintptr_t)rows % esize) return OT_ERR_INVALID_ARG;
     if (stride_row < p->vocab || stride_seq < 0) return OT_ERR_INVALID_ARG;
@@ -215,7 +217,7 @@ int ot_tree_expand(const ot_build_params* p, int32_t step, const void* rows, int
     if (st != OT_OK) return st;
     SelectGeometry g = select_geometry(*p, f);
     g.rows_per_seq = f.F[step];
-    return launch_tree_step(g, step, ws, frontier_token, frontier_parent_slot, s);
+    return launch_tree_step(g, step, ws, frontier_token, frontier_parent_slot, frontier_count, s);
 }
 
 int ot_tree_finalize(const ot_build_params* p, int32_t steps_done, void* workspace, size_t workspace_bytes,

@@ -83,7 +83,7 @@ struct SelectGeometry {
 };
 int launch_tree_oneshot(const SelectGeometry& g, const BuildWorkspace& ws, const ot_tree_out& out, hipStream_t s);
 int launch_tree_step(const SelectGeometry& g, int step, const BuildWorkspace& ws, int32_t* frontier_token,
-                     int32_t* frontier_parent, hipStream_t s);
+                     int32_t* frontier_parent, int32_t* frontier_count, hipStream_t s);
 int launch_tree_finalize(const SelectGeometry& g, int steps_done, const BuildWorkspace& ws, const ot_tree_out& out,
                          hipStream_t s);
 int launch_tree_begin(const SelectGeometry& g, const BuildWorkspace& ws, hipStream_t s);

@@ -75,6 +75,13 @@ __device__ __forceinline__ float xhalf_sum(float v) {
 
 __device__ __forceinline__ int clamp_len(int L, int maxp) { return L < 0 ? 0 : (L > maxp ? maxp : L); }
 
+// A prefix length outside [0, max_prefix] is clamped and reported in the workspace's status word.
+__device__ __forceinline__ void report_clamp(unsigned int* sync_words, int raw, int maxp) {
+    if (raw < 0 || raw > maxp)
+        __hip_atomic_fetch_or(sync_words + OT_ATTN_STATUS_OFFSET / 4, OT_ATTN_STATUS_PREFIX_CLAMPED, __ATOMIC_RELAXED,
+                              __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // Tile range of split s out of S over T tiles.
 __device__ __forceinline__ void split_range(int T, int S, int s, int& t0, int& t1) {
     t0 = (int)(((long long)T * s) / S);
@@ -161,7 +168,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     for (int w = 0; w < kMaskWords; ++w)
         if (w < a_W) mrow[w] = a_mask[((long long)b * n + node) * a_W + w];
 
-    const int L = clamp_len(a_prefix_len[b], a_max_prefix);
+    const int L_raw = a_prefix_len[b];
+    const int L = clamp_len(L_raw, a_max_prefix);
+    if (tid == 0 && hk == 0 && split == 0 && rb == 0) report_clamp(a.counters, L_raw, a_max_prefix);
     const int ptiles = (L + TK - 1) / TK, ttiles = (a_nk + TK - 1) / TK;
     int t0, t1;
     split_range(ptiles + ttiles, a_splits, split, t0, t1);
@@ -529,6 +538,7 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const AttnKArgs a) {
     const int hk = hq / a.g;
     const int n = a.n;
     const int L = clamp_len(a.prefix_len[b], a.max_prefix);
+    if (tid == 0 && hq == 0 && split == 0 && rb == 0) report_clamp(a.counters, a.prefix_len[b], a.max_prefix);
     const int ptiles = (L + TK - 1) / TK, ttiles = (a.nk + TK - 1) / TK;
     int t0, t1;
     split_range(ptiles + ttiles, a.splits, split, t0, t1);
@@ -762,7 +772,7 @@ int launch_tree_attention(const ot_attn_params& p, const AttnPlan& plan, const v
         const long long units = (long long)p.batch * p.kv_heads * plan.splits;
         const long long wgs = (units + 7) / 8 * 8 * plan.row_blocks;
         if (wgs > 0x7fffffffLL) return OT_ERR_UNSUPPORTED;
-        if (plan.splits > 1 && (long long)p.batch * p.kv_heads * plan.row_blocks * 4 > OT_ATTN_SYNC_BYTES)
+        if (plan.splits > 1 && (long long)p.batch * p.kv_heads * plan.row_blocks * 4 > OT_ATTN_STATUS_OFFSET)
             return OT_ERR_UNSUPPORTED;      // cannot happen: splits > 1 only with few workgroups
         const dim3 grid((unsigned)wgs);
 #define OT_ATTN_ARGS a.prefix_len, a.mask, a.Q, a.row_blocks, a.splits, a.kv_heads, a.g, a.n, a.max_prefix, a.nk, a.W, a

@@ -38,6 +38,7 @@ struct SelKArgs {
     int32_t* steps_used;                                      // [batch] output of the one-shot adaptive build
     ot_tree_out out;
     int32_t* frontier_token; int32_t* frontier_parent;        // [batch][n]         (streaming step)
+    int32_t* frontier_count;                                  // [batch] or null    (streaming step)
     int step;
     int rehearse;                                             // fast kernel: 1 if the launch has LDS for the rehearsing wavefront
 };
@@ -642,7 +643,10 @@ __global__ __launch_bounds__(256) void tree_oneshot_kernel(const SelKArgs a) {
 // Streaming: one drafting step; the pool lives in the caller's workspace between launches.
 template <int KMAX, bool SINGLE>
 __global__ __launch_bounds__(256) void tree_step_kernel(const SelKArgs a) {
-    if (!a.seq_active[blockIdx.x]) return;      // frozen by the adaptive-depth rule: its tree stays as it is
+    if (!a.seq_active[blockIdx.x]) {            // frozen by the adaptive-depth rule: its tree stays as it is
+        if (a.frontier_count && threadIdx.x == 0) a.frontier_count[blockIdx.x] = 0;
+        return;
+    }
     OT_SELECT_SHARED
     (void)s_cntw;
     const int tid = threadIdx.x, b = blockIdx.x, t = a.step, n = a.n;
@@ -659,7 +663,11 @@ __global__ __launch_bounds__(256) void tree_step_kernel(const SelKArgs a) {
     int cnt, off;
     double tau;
     layer_cut<KMAX, SINGLE>(ck, (double*)smem, s_hist, active, a.k, F, Fn, a.r0[t], g, cnt, off, tau);
-    if (tid == 0) { a.step_tau[(size_t)b * a.depth + t] = tau; a.seq_steps[b] = t + 1; }
+    if (tid == 0) {
+        a.step_tau[(size_t)b * a.depth + t] = tau;
+        a.seq_steps[b] = t + 1;
+        if (a.frontier_count) a.frontier_count[b] = Fn;
+    }
 #pragma unroll
     for (int r = 0; r < KMAX; ++r) {
         if (r < cnt) {
@@ -1121,7 +1129,7 @@ __global__ __launch_bounds__(256) void tree_fast_kernel(const float* row_topv, c
             run_key = mine ? rec[2 * lane] : nan_d();
             run_p = mine ? rec[2 * lane + 1] : 0.0;
             lds_sync<true>();
-            // "while the depth is below the maximum and E_sub(T,n) - E > delta: E <- E_sub(T,n); drafting step"
+            // the loop condition of Algorithm 1: another step only while the gain of the last one exceeds delta
             if (t + 1 < D) {
                 if (!(E_sub - E_prev > a.delta)) { D = t + 1; break; }
                 E_prev = E_sub;
@@ -1328,7 +1336,7 @@ SelKArgs make_args(const SelectGeometry& g, const BuildWorkspace& ws) {
     a.steps_used = nullptr;
     a.front_mask = (u64*)ws.front_mask; a.mask_out = nullptr; a.mask_words = 0; a.gridDim_batch = g.batch;
     a.out = ot_tree_out{nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
-    a.frontier_token = nullptr; a.frontier_parent = nullptr;
+    a.frontier_token = nullptr; a.frontier_parent = nullptr; a.frontier_count = nullptr;
     a.step = 0;
     a.rehearse = 0;
     return a;
@@ -1454,10 +1462,10 @@ int launch_tree_adaptive(const SelectGeometry& g, double delta, const BuildWorks
 }
 
 int launch_tree_step(const SelectGeometry& g, int step, const BuildWorkspace& ws, int32_t* frontier_token,
-                     int32_t* frontier_parent, hipStream_t s) {
+                     int32_t* frontier_parent, int32_t* frontier_count, hipStream_t s) {
     SelKArgs a = make_args(g, ws);
     a.step = step;
-    a.frontier_token = frontier_token; a.frontier_parent = frontier_parent;
+    a.frontier_token = frontier_token; a.frontier_parent = frontier_parent; a.frontier_count = frontier_count;
     const int NT = threads_for(g.n);
     return NT == 64 ? launch_step_s<true>(a, g.batch, NT, s) : launch_step_s<false>(a, g.batch, NT, s);
 }

@@ -448,6 +448,13 @@ int ot_kv_append(const ot_attn_params* p, void* K_prefix, void* V_prefix, const 
     const void* vp[4] = {K_prefix, V_prefix, K_tree, V_tree};
     for (int i = 0; i < 4; ++i)
         if ((uintptr_t)vp[i] % 16) return OT_ERR_INVALID_ARG;
+    if (((uintptr_t)prefix_len % 4) || ((uintptr_t)accept_len % 4) || ((uintptr_t)accept_node % 4) ||
+        ((uintptr_t)new_prefix_len % 4))
+        return OT_ERR_INVALID_ARG;
+    {   // the copying workgroups read prefix_len[b] while new_prefix_len[b] is written: the arrays must be disjoint
+        const uintptr_t a0 = (uintptr_t)prefix_len, b0 = (uintptr_t)new_prefix_len, len = (uintptr_t)p->batch * 4;
+        if (a0 < b0 + len && b0 < a0 + len) return OT_ERR_INVALID_ARG;
+    }
     const int vec = 16 / esize;
     const int64_t* strides[4] = {p->kp_strides, p->vp_strides, p->kt_strides, p->vt_strides};
     for (int t = 0; t < 4; ++t) {

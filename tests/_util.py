@@ -2,7 +2,7 @@
 import numpy as np
 
 from oracle import opt_tree as ot_oracle
-from paper_2406_17276_amd import workloads as wl
+import workloads as wl
 
 GAP = 1e-5          # minimum cross-parent score gap (log p^) required of generated inputs
 

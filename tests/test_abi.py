@@ -61,7 +61,10 @@ def test_build_tree_rejects_bad_arguments_without_launching():
     assert L.ot_build_tree(C.byref(_bp(k=17)), fake, fake, need, C.byref(out), None) == -2
     bad_out = api.TreeOut(0x1000, 0, 0x1000, 0x1000, 0x1000, 0x1000, 0x1000)
     assert L.ot_build_tree(C.byref(p), fake, fake, need, C.byref(bad_out), None) == -1
-    assert L.ot_tree_expand(C.byref(p), 4, fake, 0, 1000, fake, need, fake, fake, None) == -1          # step out of range
+    assert L.ot_tree_expand(C.byref(p), 4, fake, 0, 1000, fake, need, fake, fake, fake, None) == -1    # step out of range
+    assert L.ot_tree_expand(C.byref(p), 0, fake, 0, 1000, fake, need, fake, None, fake, None) == -1
+    assert L.ot_tree_expand(C.byref(p), 0, fake, 0, 1000, fake, need, fake, fake, C.c_void_p(0x1002), None) == -1   # misaligned count
+    assert L.ot_tree_expand(C.byref(p), 0, fake, 0, 999, fake, need, fake, fake, None, None) == -1     # row stride < vocab
     assert L.ot_tree_finalize(C.byref(p), 0, fake, need, C.byref(out), None) == -1
 
 
@@ -102,6 +105,30 @@ def test_attention_rejects_bad_arguments_without_launching():
     assert L.ot_attn_workspace_prepare(None, need, None) == -1
     assert L.ot_attn_workspace_prepare(C.c_void_p(0x1008), need, None) == -1
     assert L.ot_attn_workspace_prepare(f, 100, None) == -3
+
+
+def test_binding_rejects_tensors_smaller_than_the_frontier():
+    """The C ABI sees pointers, not extents: the binding refuses a logits tensor whose slot dimension is smaller
+    than the widest frontier F_t = min(n, k F_{t-1}) the library would read."""
+    import torch
+    ok = torch.zeros((1, 3, 16, 64), dtype=torch.float32)
+    assert api.build_params(ok, 4, 16, 3).n == 16
+    assert api.frontier_sizes(4, 16, 3) == [1, 4, 16, 16]
+    with pytest.raises(ValueError):
+        api.build_params(torch.zeros((1, 3, 15, 64)), 4, 16, 4)          # depth 4 needs 4 steps and 16 slots
+    with pytest.raises(ValueError):
+        api.build_params(torch.zeros((1, 4, 15, 64)), 4, 16, 4)          # step 2 and 3 read 16 rows
+    assert api.build_params(torch.zeros((1, 2, 4, 64)), 4, 16, 2).depth == 2   # steps 0 and 1 read 1 and 4 rows
+    ts = api.TreeStream.__new__(api.TreeStream)
+    ts.p = api.BuildParams(2, 64, 3, 4, 16, api.OT_F32, 0, 0, 64)
+    ts.step = 2
+    with pytest.raises(ValueError):
+        ts.expand(torch.zeros((2, 15, 64)))                               # step 2 reads 16 rows
+    with pytest.raises(ValueError):
+        ts.expand(torch.zeros((1, 16, 64)))                               # batch too small
+    ts.step = 3
+    with pytest.raises(ValueError):
+        ts.expand(torch.zeros((2, 16, 64)))                               # all steps fed
 
 
 def test_binding_fails_loudly_when_library_is_missing(monkeypatch):
@@ -177,6 +204,10 @@ def test_verify_rejects_bad_arguments_without_launching():
     assert L.ot_kv_append(C.byref(ap), None, f, f, f, f, f, f, f, None) == -1
     assert L.ot_kv_append(C.byref(ap), C.c_void_p(0x1004), f, f, f, f, f, f, f, None) == -1
     assert L.ot_kv_append(C.byref(_ap(max_prefix=0)), f, f, f, f, f, f, f, f, None) == -1
+    # the two length arrays must not overlap (other workgroups still read the old length when the new one lands)
+    g2 = C.c_void_p(0x2000)
+    assert L.ot_kv_append(C.byref(_ap(batch=4)), f, f, f, f, g2, f, f, g2, None) == -1
+    assert L.ot_kv_append(C.byref(_ap(batch=4)), f, f, f, f, g2, f, f, C.c_void_p(0x2008), None) == -1
 
 
 def test_yardsticks_reject_bad_arguments_without_launching():

@@ -5,7 +5,7 @@ import pytest
 
 from oracle import opt_tree as ot_oracle
 from oracle import tree_attention as ta_oracle
-from paper_2406_17276_amd import workloads as wl
+import workloads as wl
 from tests import _util as U
 
 pytestmark = pytest.mark.gpu
@@ -191,6 +191,36 @@ def test_prefix_length_is_clamped_on_device():
     y = dict(x); y["prefix_len"] = np.array([10_000], dtype=np.int32)
     got = _gpu_attention(y, mask, "f32")
     assert np.abs(got - want).max() < 1e-5
+
+
+@pytest.mark.parametrize("dtype,D,L,n", [("f32", 64, 40, 8), ("bf16", 128, 300, 20)])
+def test_clamped_prefix_length_is_reported_in_the_workspace_status_word(dtype, D, L, n):
+    """A length outside [0, max_prefix] is clamped and sets bit 0 of the workspace's status word, which stays set
+    until the workspace is prepared again; in-range lengths leave it clear."""
+    import torch
+    from paper_2406_17276_amd import api
+    w = _shape(dtype, 3, 4, 2, D, L, n)
+    x = wl.make_attention_inputs(w, 21)
+    mask = _random_masks(3, n, 5)
+    dev = {k: U.to_device(v, dtype) for k, v in x.items() if k != "prefix_len"}
+    p = api.attn_params(dev["Q"], dev["K_prefix"], dev["V_prefix"], dev["K_tree"], dev["V_tree"])
+    ws = api.attn_workspace(p, "cuda")
+    call = lambda plen: api.tree_verify_attention(dev["Q"], dev["K_prefix"], dev["V_prefix"], dev["K_tree"], dev["V_tree"],
+                                                  torch.tensor(plen, dtype=torch.int32, device="cuda"),
+                                                  U.mask_to_device(mask), workspace=ws)
+    good = call([L, L // 2, 0])
+    assert api.attn_status(ws) == 0
+    want = _oracle_attention(dict(x, prefix_len=np.array([L, L // 2, 0], dtype=np.int32)), mask, dtype)
+    assert np.abs(U.from_device_f64(good) - want).max() < TOL[dtype]
+    over = call([L, L + 1, 0])                                   # sequence 1 too long: clamped to L, flagged
+    assert api.attn_status(ws) & api.OT_ATTN_STATUS_PREFIX_CLAMPED
+    want = _oracle_attention(dict(x, prefix_len=np.array([L, L, 0], dtype=np.int32)), mask, dtype)
+    assert np.abs(U.from_device_f64(over) - want).max() < TOL[dtype]
+    call([L, L // 2, 0])
+    assert api.attn_status(ws) & api.OT_ATTN_STATUS_PREFIX_CLAMPED        # sticky
+    api._check(api.lib().ot_attn_workspace_prepare(ws.data_ptr(), ws.numel(), api._stream()), "prepare")
+    call([L, -3, 0])                                             # negative: clamped to 0, flagged
+    assert api.attn_status(ws) & api.OT_ATTN_STATUS_PREFIX_CLAMPED
 
 
 def test_one_workspace_serves_consecutive_calls():

@@ -6,7 +6,7 @@ import pytest
 
 from oracle import tree_attention as ta_oracle
 from oracle import verify as vf
-from paper_2406_17276_amd import workloads as wl
+import workloads as wl
 from tests import _util as U
 
 pytestmark = pytest.mark.gpu

@@ -5,7 +5,7 @@ makes them recordable."""
 import numpy as np
 import pytest
 
-from paper_2406_17276_amd import workloads as wl
+import workloads as wl
 from tests import _util as U
 
 pytestmark = pytest.mark.gpu

@@ -7,7 +7,7 @@ import numpy as np
 import pytest
 
 from oracle import opt_tree as ot_oracle
-from paper_2406_17276_amd import workloads as wl
+import workloads as wl
 from tests import _util as U
 
 pytestmark = pytest.mark.gpu
@@ -55,9 +55,23 @@ def test_70b_full_batch_as_the_bench_launches_it():
     U.assert_tree_equal(sub, want, w.n)
 
 
+@pytest.mark.timeout(900)
+def test_large_budget_shape_full_depth_against_the_oracle():
+    # The Large workload's own configuration for one sequence: vocabulary 128256 (four scan parts), k = 16, n = 256,
+    # all 20 drafting steps, logits 5 N(0,1) with planted peaks.  The oracle needs about a minute for the 4625 rows.
+    w = wl.WORKLOADS["large"]
+    print("large, full depth: drawing the logits and running the oracle", flush=True)
+    seed, logits, want = U.gapped_logits(w, 0, seqs=[0])
+    print(f"large, full depth: seed {seed}, min gap {want[0]['min_gap']:.3g}; GPU build", flush=True)
+    got = _run(logits, w.dtype, w.k, w.n, w.depth)
+    assert want[0]["n_out"] == w.n
+    U.assert_tree_equal(got, want, w.n)
+    U.assert_tree_invariants(got, w.n, w.depth)
+
+
 def test_large_budget_shape_full_depth_invariants():
-    # n = 256, k = 16, 20 drafting steps, vocabulary 128256 (four scan parts): two sequences drawn on the device;
-    # the oracle cannot follow at this size, the invariants of Algorithm 1's output must hold
+    # n = 256, k = 16, 20 drafting steps, vocabulary 128256 (four scan parts): two more sequences, drawn on the
+    # device, under the invariants of Algorithm 1's output (the oracle comparison at this size is the test above)
     import torch
     from paper_2406_17276_amd import api
     w = wl.WORKLOADS["large"]
@@ -181,9 +195,11 @@ def test_streaming_matches_oracle_layer_by_layer():
         ftok, fpar = stream.expand(torch.from_numpy(rows).cuda())
         torch.cuda.synchronize()
         ftok, fpar = ftok.cpu().numpy(), fpar.cpu().numpy()
+        fcnt = stream.frontier_count.cpu().numpy()
         for b in range(B):
             tok, par = builders[b].expand(rows[b, :F].astype(np.float64))
             Fn = len(tok)
+            assert fcnt[b] == Fn                       # rows the draft model owes for the next step
             np.testing.assert_array_equal(ftok[b, :Fn], tok)
             np.testing.assert_array_equal(fpar[b, :Fn], par)
             paths[b] = [paths[b][int(pj)] + (int(tk),) for tk, pj in zip(tok, par)]
@@ -243,10 +259,12 @@ def test_adaptive_depth_matches_oracle():
     active = [True] * B
     for t in range(dmax):
         stream.expand(dev[:, t])
+        fcnt = stream.frontier_count.cpu().numpy()
         e_sub, go = stream.e_sub(delta)
         torch.cuda.synchronize()
         e_sub, go = e_sub.cpu().numpy(), go.cpu().numpy()
         for b in range(B):
+            assert fcnt[b] == (min(n, k ** (t + 1)) if active[b] else 0)      # a stopped sequence asks for no rows
             if active[b]:
                 assert e_sub[b] == pytest.approx(want[b]["e_sub_trace"][t], rel=1e-6)      # fp32 exp-sums behind every lse
                 expect_go = t + 1 < want[b]["steps"] or (want[b]["steps"] == dmax and t + 1 == dmax and

@@ -5,7 +5,7 @@ import scipy.special
 
 from oracle import opt_tree as ot
 from oracle import tree_attention as ta
-from paper_2406_17276_amd import workloads as wl
+import workloads as wl
 
 
 def _inputs(B, Hq, Hkv, n, D, Lmax, seed, lens=None):

@@ -9,7 +9,7 @@ import numpy as np
 import pytest
 
 from oracle import tree_attention as ta_oracle
-from paper_2406_17276_amd import workloads as wl
+import workloads as wl
 from tests import _util as U
 
 pytestmark = pytest.mark.gpu
