@@ -39,6 +39,7 @@ extern "C" {
 #define OT_ERR_UNSUPPORTED        (-2)  /* outside the limits below */
 #define OT_ERR_WORKSPACE_TOO_SMALL (-3)
 #define OT_ERR_HIP                (-4)  /* a HIP runtime call failed; see ot_last_hip_error() */
+#define OT_ERR_SCRATCH_LIMIT      (-5)  /* the call needs more scratch memory than a *_noalloc entry point owns */
 
 #define OT_F32   0   /* IEEE binary32 */
 #define OT_BF16  1   /* bfloat16 */
@@ -229,6 +230,26 @@ OT_API int ot_tree_verify_attention(const ot_attn_params* p,
                              const uint64_t* mask,                   /* [batch][n][OT_MASK_WORDS(n)] */
                              void* O,                                /* [batch][q_heads][n][head_dim] */
                              void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* ot_tree_verify_attention for callers that cannot allocate device memory or keep a workspace (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc): the same kernels, with the workspace in
+ * a library-owned device array of OT_ATTN_SCRATCH_BYTES that every GPU the library runs on holds until the
+ * process ends.  Neither this call nor anything it calls allocates or frees memory, and no
+ * ot_attn_workspace_prepare is needed.  The first call on a device looks the array's address up and clears its
+ * ticket counters on `hip_stream` (that first call must not be made inside a graph capture; later calls may).
+ * The device of `hip_stream` must be the current device.  All calls on one GPU share the one array: calls that
+ * may overlap on a GPU (different streams without an ordering between them, or several host threads) race and
+ * must use ot_tree_verify_attention with workspaces of their own.  The status word of a clamped prefix length
+ * is not observable through this entry point (lengths are still clamped).
+ * Returns OT_ERR_SCRATCH_LIMIT when ot_attn_workspace_bytes(p) exceeds OT_ATTN_SCRATCH_BYTES (the split
+ * partials of few, short sequences with many query heads are the large case; batches that fill the chip without
+ * splitting need only the first OT_ATTN_SYNC_BYTES); other errors as ot_tree_verify_attention. */
+#define OT_ATTN_SCRATCH_BYTES (16u << 20)
+OT_API int ot_tree_verify_attention_noalloc(const ot_attn_params* p,
+                             const void* Q, const void* K_prefix, const void* V_prefix,
+                             const void* K_tree, const void* V_tree,
+                             const int32_t* prefix_len, const uint64_t* mask,
+                             void* O, void* hip_stream);
 
 /* Measurement aid: ot_tree_verify_attention that also records the begin and the end of its
  * K/V-streaming kernel (Algorithm 2's tree-masked attention; for bf16 it includes the split merge) in two

@@ -110,6 +110,8 @@ def lib():
         L.ot_attn_workspace_prepare.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p]
         L.ot_tree_verify_attention.restype = C.c_int
         L.ot_tree_verify_attention.argtypes = [C.POINTER(AttnParams)] + [C.c_void_p] * 9 + [C.c_size_t, C.c_void_p]
+        L.ot_tree_verify_attention_noalloc.restype = C.c_int
+        L.ot_tree_verify_attention_noalloc.argtypes = [C.POINTER(AttnParams)] + [C.c_void_p] * 9
         L.ot_tree_verify_attention_timed.restype = C.c_int
         L.ot_tree_verify_attention_timed.argtypes = ([C.POINTER(AttnParams)] + [C.c_void_p] * 9 +
                                                      [C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p])
@@ -349,6 +351,18 @@ def tree_verify_attention(Q, K_prefix, V_prefix, K_tree, V_tree, prefix_len, mas
         C.byref(p), ptr(Q), ptr(K_prefix), ptr(V_prefix), ptr(K_tree), ptr(V_tree), ptr(prefix_len), ptr(mask),
         ptr(out), ptr(workspace), 0 if workspace is None else workspace.numel(), _stream()),
         "ot_tree_verify_attention")
+    return out
+
+
+def tree_verify_attention_noalloc(Q, K_prefix, V_prefix, K_tree, V_tree, prefix_len, mask, out, softmax_scale=0.0):
+    """ot_tree_verify_attention_noalloc on the current stream: as tree_verify_attention, with the library's own
+    scratch array as workspace; `out` is supplied by the caller (nothing is allocated)."""
+    p = attn_params(Q, K_prefix, V_prefix, K_tree, V_tree, softmax_scale=softmax_scale)
+    p.o_strides = (C.c_int64 * 3)(out.stride(0), out.stride(1), out.stride(2))
+    ptr = lambda t: None if t is None else t.data_ptr()
+    _check(lib().ot_tree_verify_attention_noalloc(
+        C.byref(p), ptr(Q), ptr(K_prefix), ptr(V_prefix), ptr(K_tree), ptr(V_tree), ptr(prefix_len), ptr(mask),
+        ptr(out), _stream()), "ot_tree_verify_attention_noalloc")
     return out
 
 

@@ -105,6 +105,7 @@ const char* ot_status_string(int status) {
         case OT_ERR_UNSUPPORTED: return "unsupported size or type";
         case OT_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
         case OT_ERR_HIP: return "HIP runtime error";
+        case OT_ERR_SCRATCH_LIMIT: return "needs more scratch memory than the no-allocation entry point owns";
         default: return "unknown status";
     }
 }

@@ -33,6 +33,7 @@
 // f32 path (attn_f32_kernel): plain fp32 FMA arithmetic, 16 query rows x 32-key tiles.
 #include <math.h>
 
+#include <mutex>
 #include <type_traits>
 
 #include "common.hpp"
@@ -872,6 +873,48 @@ int ot_tree_verify_attention(const ot_attn_params* p, const void* Q, const void*
                              const void* K_tree, const void* V_tree, const int32_t* prefix_len, const uint64_t* mask,
                              void* O, void* workspace, size_t workspace_bytes, void* hip_stream) {
     return attention_entry(p, Q, K_prefix, V_prefix, K_tree, V_tree, prefix_len, mask, O, workspace, workspace_bytes,
+                           hip_stream, nullptr, nullptr);
+}
+
+// ---------------------------------------------------------------------------
+// Entry point for callers that cannot allocate: the workspace (ticket counters, status word, split partials) is a
+// library-owned array in device memory.  Every GPU holds its own copy at its own address; host code never uses
+// the array's name except to look that address up, once per device.
+// ---------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[OT_ATTN_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices];       // device address of `scratch` on device i, null until looked up
+}  // namespace
+
+int ot_tree_verify_attention_noalloc(const ot_attn_params* p, const void* Q, const void* K_prefix, const void* V_prefix,
+                                     const void* K_tree, const void* V_tree, const int32_t* prefix_len,
+                                     const uint64_t* mask, void* O, void* hip_stream) {
+    int st = validate_attn(p);
+    if (st != OT_OK) return st;
+    if (plan_attention(*p).bytes > (size_t)OT_ATTN_SCRATCH_BYTES) return OT_ERR_SCRATCH_LIMIT;
+    int dev = -1;
+    OT_HIP_CHECK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return OT_ERR_UNSUPPORTED;
+    void* ptr;
+    {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        if (!g_scratch_ptr[dev]) {
+            // set-up, once per device, with that device current: the address of this device's copy of the array,
+            // and its ticket counters and status word cleared (by a kernel, which a graph capture could record)
+            void* found = nullptr;
+            OT_HIP_CHECK(hipGetSymbolAddress(&found, HIP_SYMBOL(scratch)));
+            if (!found || ((uintptr_t)found % 256)) return OT_ERR_HIP;
+            hipLaunchKernelGGL(attn_clear_sync_kernel, dim3(OT_ATTN_SYNC_BYTES / 4 / 256), dim3(256), 0,
+                               (hipStream_t)hip_stream, (unsigned int*)found);
+            OT_HIP_CHECK(hipGetLastError());
+            g_scratch_ptr[dev] = found;
+        }
+        ptr = g_scratch_ptr[dev];
+    }
+    return attention_entry(p, Q, K_prefix, V_prefix, K_tree, V_tree, prefix_len, mask, O, ptr, OT_ATTN_SCRATCH_BYTES,
                            hip_stream, nullptr, nullptr);
 }
 

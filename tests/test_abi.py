@@ -107,6 +107,23 @@ def test_attention_rejects_bad_arguments_without_launching():
     assert L.ot_attn_workspace_prepare(f, 100, None) == -3
 
 
+def test_no_allocation_entry_point_validates_before_touching_the_gpu():
+    L = api.lib()
+    f = C.c_void_p(0x1000)
+    assert L.ot_tree_verify_attention_noalloc(None, *([f] * 8), None) == -1
+    assert L.ot_tree_verify_attention_noalloc(C.byref(_ap(head_dim=96)), *([f] * 8), None) == -2
+    # one sequence, 64 query heads on 8 KV heads, a long prefix: many key splits of 512 packed rows each, whose
+    # partial results exceed the library's scratch array
+    s = (C.c_int64 * 3)
+    big = _ap(q_heads=64, kv_heads=8, head_dim=128, n=64, max_prefix=4096, dtype=1,
+              q_strides=s(524288, 8192, 128), o_strides=s(524288, 8192, 128),
+              kt_strides=s(65536, 8192, 128), vt_strides=s(65536, 8192, 128),
+              kp_strides=s(4194304, 524288, 128), vp_strides=s(4194304, 524288, 128))
+    assert api.attn_workspace_bytes(big) > (16 << 20)
+    assert L.ot_tree_verify_attention_noalloc(C.byref(big), *([f] * 8), None) == -5
+    assert L.ot_status_string(-5).startswith(b"needs more scratch")
+
+
 def test_binding_rejects_tensors_smaller_than_the_frontier():
     """The C ABI sees pointers, not extents: the binding refuses a logits tensor whose slot dimension is smaller
     than the widest frontier F_t = min(n, k F_{t-1}) the library would read."""
