@@ -49,7 +49,8 @@ extern "C" {
 #define OT_MAX_TOPK       16   /* k  */
 #define OT_MAX_DEPTH      32   /* d  */
 #define OT_MAX_HEAD_DIM  128
-#define OT_MAX_TREE_KEYS 512      /* tree keys of the attention when they are more than the query rows */
+#define OT_MAX_TREE_KEYS 8192     /* tree keys of the attention when they are more than the query rows (bf16) */
+#define OT_MAX_TREE_KEYS_F32 512  /* the same for f32 tensors */
 #define OT_MASK_WORDS(n) (((n) + 63) / 64)
 
 OT_API int ot_version(void);                       /* 100*major + minor */
@@ -242,9 +243,10 @@ OT_API int ot_tree_verify_attention(const ot_attn_params* p,
  * must use ot_tree_verify_attention with workspaces of their own.  The status word of a clamped prefix length
  * is not observable through this entry point (lengths are still clamped).
  * Returns OT_ERR_SCRATCH_LIMIT when ot_attn_workspace_bytes(p) exceeds OT_ATTN_SCRATCH_BYTES (the split
- * partials of few, short sequences with many query heads are the large case; batches that fill the chip without
- * splitting need only the first OT_ATTN_SYNC_BYTES); other errors as ot_tree_verify_attention. */
-#define OT_ATTN_SCRATCH_BYTES (16u << 20)
+ * partials of a single sequence with many grouped query heads are the large case, up to 17 MB; a batch-1
+ * multi-head shape needs 3-4 MB, batches that fill the chip without splitting only the first
+ * OT_ATTN_SYNC_BYTES); other errors as ot_tree_verify_attention. */
+#define OT_ATTN_SCRATCH_BYTES (8u << 20)
 OT_API int ot_tree_verify_attention_noalloc(const ot_attn_params* p,
                              const void* Q, const void* K_prefix, const void* V_prefix,
                              const void* K_tree, const void* V_tree,

@@ -33,6 +33,9 @@ struct Frontier {
 };
 Frontier make_frontier(int k, int n, int depth);
 
+// Pool nodes (depth * n) up to which the streaming builder keeps the frontier's ancestor masks.
+constexpr int kFrontMaskKeys = 512;
+
 // Elements of one vocabulary row handled by one workgroup of the row scan.
 constexpr int kScanPartElems = 32768;
 inline int scan_parts(int vocab) { return (vocab + kScanPartElems - 1) / kScanPartElems; }
@@ -55,7 +58,7 @@ struct BuildWorkspace {
     int32_t* seq_steps;             // [batch]             layers drafted (frozen when the loop has stopped)
     int32_t* seq_active;            // [batch]             0 once E_sub - E <= delta was seen
     uint64_t* front_mask;           // [2][batch][n][8]    ancestor masks of the last two frontiers over pool
-                                    //                     indices; null when depth * n > OT_MAX_TREE_KEYS
+                                    //                     indices; null when depth * n > kFrontMaskKeys
     size_t bytes;
 };
 BuildWorkspace carve_build_workspace(const ot_build_params& p, void* base);

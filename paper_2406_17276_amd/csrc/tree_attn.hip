@@ -20,7 +20,8 @@
 //                 inside a 16-key slab is whatever the accumulator layout gives; V is read in
 //                 the same order), A = V gathered from LDS.
 // K/V tiles go from global memory straight into LDS (global_load_lds_dwordx4: 16 bytes per lane, no
-// register staging), one or two tiles ahead of the computation, into a ring of two or three buffers.  A
+// register staging), one or two tiles ahead of the computation, into a ring of two or three buffers; a tree
+// tile's mask words (one 64-bit word per query row) travel the same way, just ahead of the tile.  A
 // wavefront's 64 lanes land on 1 KB of consecutive LDS, so rows are unpadded and bank conflicts are
 // avoided by an XOR swizzle instead: lane -> global chunk is chosen such that 16-byte chunk c of key
 // row r sits at chunk position c ^ (r mod 16) (K), and 32-byte segment g of row r at g ^ (r mod 8) (V).
@@ -28,7 +29,10 @@
 // are masked).  V is the transposed operand (a lane needs 8 keys of ONE column): it is read with the gfx950
 // LDS transpose load ds_read_b64_tr_b16, which lets 16 lanes read four 32-byte row segments and hands
 // lane i the i-th column of that 4x16 block -- two such loads per MFMA operand.
-// The ancestor mask is applied as a bit test on tree tiles only; prefix tiles only mask the tail.
+// The ancestor mask is applied bit by bit on tree tiles only (any number of tree keys: a tile needs one word per
+// row); prefix tiles only mask the tail.  The kernel's first memory requests decide its length at the small
+// shapes, so the prologue is kept short: divisions are multiplications by constants prepared on the host, the
+// prefix length is fetched first, Q is requested before and the first tiles right after it is known.
 //
 // f32 path (attn_f32_kernel): plain fp32 FMA arithmetic, 16 query rows x 32-key tiles.
 #include <math.h>
@@ -43,8 +47,7 @@ namespace {
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr int kMaxSplits = 32;
-constexpr int kMaskWords = OT_MASK_WORDS(OT_MAX_TREE_KEYS);   // 64-bit words of a mask row
-static_assert(kMaskWords == 8, "mask rows are held in eight registers");
+constexpr int kMaskWordsF32 = 8;                              // the f32 kernel holds a mask row in eight registers
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
@@ -60,6 +63,7 @@ struct AttnKArgs {
     float* part_o;      // per-split partial O   (layout: see the kernel that writes it)
     float* part_ml;     // per-split (m, l)
     int batch, q_heads, kv_heads, g, n, nk, D, max_prefix, splits, W, dtype, row_blocks;   // n query rows, nk tree keys
+    unsigned int inv_splits, inv_kv_heads, inv_n;   // division by multiplication (fast_div): ceil(2^32 / d), unused for d = 1
     float scale_log2;   // softmax scale * log2(e)
     long long qs[3], kps[3], vps[3], kts[3], vts[3], os[3];
 };
@@ -83,10 +87,30 @@ __device__ __forceinline__ void report_clamp(unsigned int* sync_words, int raw, 
                               __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// Tile range of split s out of S over T tiles.
-__device__ __forceinline__ void split_range(int T, int S, int s, int& t0, int& t1) {
-    t0 = (int)(((long long)T * s) / S);
-    t1 = (int)(((long long)T * (s + 1)) / S);
+// Wait until all but the N youngest memory requests of this lane have landed.  The Q fragments were requested
+// with assembly the compiler does not track; they are in/out operands here, which places whatever reads them
+// after this wait.  Executed once, ahead of the tile loop (straight-line code: the operands stay where they are).
+template <int N, int SLABS>
+__device__ __forceinline__ void wait_q(u32x4 (&q)[SLABS]) {
+    static_assert(SLABS == 4 || SLABS == 8, "head_dim 64 or 128");
+    if constexpr (SLABS == 8)
+        asm volatile("s_waitcnt vmcnt(%8)"
+                     : "+v"(q[0]), "+v"(q[1]), "+v"(q[2]), "+v"(q[3]), "+v"(q[4]), "+v"(q[5]), "+v"(q[6]), "+v"(q[7])
+                     : "n"(N) : "memory");
+    else
+        asm volatile("s_waitcnt vmcnt(%4)" : "+v"(q[0]), "+v"(q[1]), "+v"(q[2]), "+v"(q[3]) : "n"(N) : "memory");
+}
+
+// x / d for x d < 2^32 as one multiplication by M = ceil(2^32 / d), prepared on the host (an integer division
+// costs some forty instructions here, and the kernel's first memory requests wait for several of them).
+__device__ __forceinline__ int fast_div(int x, int d, unsigned int M) {
+    return d == 1 ? x : (int)__umulhi((unsigned int)x, M);
+}
+
+// Tile range of split s out of S over T tiles (T s < 2^32 / S).
+__device__ __forceinline__ void split_range(int T, int S, unsigned int inv_S, int s, int& t0, int& t1) {
+    t0 = fast_div(T * s, S, inv_S);
+    t1 = fast_div(T * (s + 1), S, inv_S);
 }
 
 // ---------------------------------------------------------------------------
@@ -110,13 +134,19 @@ __device__ __forceinline__ void split_range(int T, int S, int s, int& t0, int& t
 #ifndef OT_ATTN_NBUF_NARROW
 #define OT_ATTN_NBUF_NARROW 3
 #endif
+// Partial results of the key splits travel as bf16 (0) or as fp32 (define to 0): bf16 halves the exchange and lets the
+// merging workgroup hold all of a row block's partials in registers at once, one trip to memory instead of two; the
+// extra rounding is of the size of the output's own (the output is bf16).
+#ifndef OT_ATTN_PART_BF16
+#define OT_ATTN_PART_BF16 1
+#endif
 template <int D, bool WIDE>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_mfma_kernel(
     // what the first loads need, as leading scalar arguments: the hardware hands these over in registers at
     // wavefront start (kernel-argument preload); they repeat fields of `a`
-    const int32_t* a_prefix_len, const uint64_t* a_mask, const void* a_Q, const int a_row_blocks, const int a_splits,
-    const int a_kv_heads, const int a_g, const int a_n, const int a_max_prefix, const int a_nk, const int a_W,
-    const AttnKArgs a) {
+    const int32_t* a_prefix_len, const uint64_t* a_mask, const void* a_Q, const int a_splits, const unsigned a_inv_splits,
+    const int a_kv_heads, const unsigned a_inv_kv_heads, const int a_n, const unsigned a_inv_n, const AttnKArgs a) {
+    const int a_g = a.g, a_max_prefix = a.max_prefix, a_nk = a.nk, a_W = a.W, a_row_blocks = a.row_blocks;
     constexpr int TK = 64;                 // keys per tile
     constexpr int CPR = D / 8;             // 16-byte chunks per row
     constexpr int SPR = D / 16;            // 32-byte segments per row
@@ -134,47 +164,48 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     constexpr int BUF = TK * D;            // dwords of one staged tile: K [64][D] bf16, then V [64][D] bf16
     extern __shared__ __attribute__((aligned(16))) unsigned int s_buf[];   // [NBUF][BUF]
     __shared__ int s_last;
-    constexpr int MST = DB * 16 + 2;       // floats per lane in the half-merge scratch
+    constexpr int MST = DB * 16 + 4;       // floats per lane in the half-merge scratch (a multiple of four)
     static_assert(sizeof(unsigned int) * NBUF * BUF >= 2 * 64 * MST * 4, "merge scratch fits");
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int qb = WIDE ? wave : (wave & 1), kh = WIDE ? 0 : (wave >> 1);
     const int l32 = lane & 31, h = lane >> 5;
     // workgroup numbering: see above
-    const int xcd = blockIdx.x & 7, q = blockIdx.x >> 3;
-    const int unit = (q / a_row_blocks) * 8 + xcd, rb = q % a_row_blocks;
+    // grid (8 x row blocks, units / 8): hardware hands workgroups out with x running fastest
+    const int xcd = blockIdx.x & 7, rb = blockIdx.x >> 3;
+    const int unit = blockIdx.y * 8 + xcd;
     if (unit >= a.batch * a_kv_heads * a_splits) return;
-    const int bz = unit / a_splits, split = unit - bz * a_splits;
-    const int b = bz / a_kv_heads, hk = bz - b * a_kv_heads;
+    const int bz = fast_div(unit, a_splits, a_inv_splits), split = unit - bz * a_splits;
+    const int b = fast_div(bz, a_kv_heads, a_inv_kv_heads), hk = bz - b * a_kv_heads;
     const int n = a_n;
+    // the prefix length decides which tiles this workgroup streams: fetched first (a scalar load, ahead of the
+    // hand-issued loads below), used only when the tile requests are built
+    const int L_raw = a_prefix_len[b];
 
     // this lane's query row; lanes past the last row work on a copy of it and store nothing
     const int rho = rb * ROWS + qb * 32 + l32;         // packed row inside the KV head
     const bool row_ok = rho < a_g * n;
     const int rho_c = row_ok ? rho : a_g * n - 1;
-    const int hq = hk * a_g + rho_c / n;
-    const int node = rho_c % n;
+    const int head = fast_div(rho_c, n, a_inv_n);
+    const int hq = hk * a_g + head;
+    const int node = rho_c - head * n;
 
-    // Q fragments: B operand of S^T = K Q^T; lane holds Q[row][16 s + 8 h .. +7]
+    // Q fragments (B operand of S^T = K Q^T; lane holds Q[row][16 s + 8 h .. +7]) are requested first, as
+    // assembly like the tile requests below: the compiler does not know that they are in flight, so nothing
+    // waits for them until the first tile does (s_waitcnt in tile_step; loads complete in order, Q is the
+    // oldest).  The registers are handed to that wait as in/out operands, which keeps every use behind it.
     u32x4 qw[SLABS];
     {
-        const unsigned short* qrow =
-            (const unsigned short*)a_Q + (long long)b * a.qs[0] + (long long)hq * a.qs[1] + (long long)node * a.qs[2];
+        const unsigned short* qrow = (const unsigned short*)a_Q + (long long)b * a.qs[0] + (long long)hq * a.qs[1] +
+                                     (long long)node * a.qs[2] + 8 * h;
 #pragma unroll
-        for (int s = 0; s < SLABS; ++s) qw[s] = *(const u32x4*)(qrow + 16 * s + 8 * h);
+        for (int s = 0; s < SLABS; ++s)
+            asm volatile("global_load_dwordx4 %0, %1, off offset:%2" : "=&v"(qw[s]) : "v"(qrow), "n"(32 * s) : "memory");
     }
-    // this lane's ancestor mask row
-    uint64_t mrow[kMaskWords] = {0ull, 0ull, 0ull, 0ull, 0ull, 0ull, 0ull, 0ull};
-#pragma unroll
-    for (int w = 0; w < kMaskWords; ++w)
-        if (w < a_W) mrow[w] = a_mask[((long long)b * n + node) * a_W + w];
-
-    const int L_raw = a_prefix_len[b];
-    const int L = clamp_len(L_raw, a_max_prefix);
-    if (tid == 0 && hk == 0 && split == 0 && rb == 0) report_clamp(a.counters, L_raw, a_max_prefix);
-    const int ptiles = (L + TK - 1) / TK, ttiles = (a_nk + TK - 1) / TK;
-    int t0, t1;
-    split_range(ptiles + ttiles, a_splits, split, t0, t1);
+    // this lane's ancestor mask row: one 64-bit word per 64-key tree tile, requested with the tile and, like it,
+    // delivered straight into LDS (s_mw: per buffer and wavefront the low words of the 64 lanes, then the high words)
+    const uint64_t* const mask_row = a_mask + ((long long)b * n + node) * a_W;
+    unsigned int* const s_mw = s_buf + NBUF * BUF;                      // [NBUF][4 waves][2][64]
 
     const unsigned short* kp = (const unsigned short*)a.Kp + (long long)b * a.kps[0] + (long long)hk * a.kps[1];
     const unsigned short* vp = (const unsigned short*)a.Vp + (long long)b * a.vps[0] + (long long)hk * a.vps[1];
@@ -202,7 +233,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const int kkey0 = tid / CPR, pc = tid % CPR;
     const int kcol = (pc ^ (kkey0 & (CPR - 1))) * 8;                                         // K: chunk c = pc ^ (r % 16)
     const int vcol = (2 * ((pc >> 1) ^ (kkey0 & (SPR - 1))) + (pc & 1)) * 8;                 // V: segment g = (pc/2) ^ (r % 8)
-    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    const int wave_u = wave;
     // Request tile t: global memory -> LDS buffer `buf`, 16 bytes per lane and instruction, no registers in
     // between.  Full tiles address memory as (uniform base of the tile's rows) + (this lane's fixed 32-bit
     // offset), which costs no vector arithmetic.  Tiles that reach past the end of the keys (prefix tail,
@@ -213,8 +244,21 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     // with s_waitcnt vmcnt (loads complete in order) ahead of the barrier that publishes the buffer.
     const unsigned kofs_p = (unsigned)(kkey0 * (int)a.kps[2] + kcol) * 2u, vofs_p = (unsigned)(kkey0 * (int)a.vps[2] + vcol) * 2u;
     const unsigned kofs_t = (unsigned)(kkey0 * (int)a.kts[2] + kcol) * 2u, vofs_t = (unsigned)(kkey0 * (int)a.vts[2] + vcol) * 2u;
-    auto request_tile = [&](int t, int buf) {
+    const int L = clamp_len(L_raw, a_max_prefix);
+    const int ptiles = (L + TK - 1) / TK, ttiles = (a_nk + TK - 1) / TK;
+    int t0, t1;
+    split_range(ptiles + ttiles, a_splits, a_inv_splits, split, t0, t1);
+    auto request_tile = [&](int t, auto buf_c) {
+        constexpr int buf = decltype(buf_c)::value;
         const bool tree = t >= ptiles;
+        // the mask word of a tree tile travels ahead of the tile's K/V (older, so it has landed when the tile's
+        // wait is over)
+        if (tree) {
+            const unsigned lds_w = (unsigned)(size_t)(__attribute__((address_space(3))) void*)(s_mw + (buf * 4 + wave) * 128);
+            const unsigned int* const wp = (const unsigned int*)(mask_row + (t - ptiles));
+            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, off" ::"s"(lds_w), "v"(wp) : "m0", "memory");
+            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, off" ::"s"(lds_w + 256), "v"(wp + 1) : "m0", "memory");
+        }
         const int key0 = tree ? (t - ptiles) * TK : t * TK;
         const int last = (tree ? a_nk : L) - 1;
         const long long ks = tree ? a.kts[2] : a.kps[2];
@@ -252,19 +296,25 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         }
     };
 
-    // Q and the mask row must have arrived before the first tile request: the compiler waits for its own
-    // loads with a counter that would otherwise also cover the (younger) tile requests.
+    // The first PD tiles are requested at once.  A split with fewer tiles issues the same number of loads all the
+    // same (one word each, into the unused buffer's mask-word slots: a load without a destination register): the
+    // wait for Q below can then name a fixed count of younger requests.
+    auto pad_requests = [&](int buf) {
+        const unsigned lds_w = (unsigned)(size_t)(__attribute__((address_space(3))) void*)(s_mw + (buf * 4 + wave) * 128);
 #pragma unroll
-    for (int s = 0; s < SLABS; ++s) asm volatile("" : "+v"(qw[s]));
-#pragma unroll
-    for (int w = 0; w < kMaskWords; ++w) asm volatile("" : "+v"(mrow[w]));
+        for (int i = 0; i < LPT; ++i)
+            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, off" ::"s"(lds_w), "v"(a_prefix_len) : "m0", "memory");
+    };
+    if (t0 < t1) request_tile(t0, std::integral_constant<int, 0>{}); else pad_requests(0);
+    if (PD > 1) { if (t0 + 1 < t1) request_tile(t0 + 1, std::integral_constant<int, (PD > 1 ? 1 : 0)>{}); else pad_requests(1); }
+    if (PD > 2) { if (t0 + 2 < t1) request_tile(t0 + 2, std::integral_constant<int, (PD > 2 ? 2 : 0)>{}); else pad_requests(2); }
+    if (tid == 0 && hk == 0 && split == 0 && rb == 0) report_clamp(a.counters, L_raw, a_max_prefix);
+    // Q has landed when at most the PD request groups issued behind it are outstanding (a tree tile's two mask
+    // words are not counted: the wait is then on the safe side)
+    wait_q<PD * LPT, SLABS>(qw);
     bf16x8 qf[SLABS];
 #pragma unroll
     for (int s = 0; s < SLABS; ++s) qf[s] = __builtin_bit_cast(bf16x8, qw[s]);
-
-#pragma unroll
-    for (int i = 0; i < PD; ++i)
-        if (t0 + i < t1) request_tile(t0 + i, i);
     // One tile, out of buffer CUR.  The buffer index is a compile-time constant (the loop below is unrolled
     // NBUF times), so that every LDS address of the operand reads is a loop-invariant per-lane value plus an
     // immediate offset.
@@ -273,17 +323,25 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         constexpr int PREV = (CUR + NBUF - 1) % NBUF;      // buffer of tile t - 1 (= of tile t + PD)
         // my requests for tile t have landed (younger ones may still be in flight); after the barrier
         // everybody's have, and everybody is done reading the buffer of tile t - 1
+        // (a request group holds LPT tile loads, plus one mask word for a tree tile: allowing only
+        // ahead * LPT younger loads to be outstanding is then on the safe side)
         const int ahead = t1 - 1 - t < PD - 1 ? t1 - 1 - t : PD - 1;
         if (ahead <= 0)      asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
         else if (ahead == 1) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(LPT) : "memory");
         else                 asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(2 * LPT) : "memory");
-        if (t + PD < t1) request_tile(t + PD, PREV);
+        if (t + PD < t1) request_tile(t + PD, std::integral_constant<int, PREV>{});
+
         const unsigned short* const s_k = (const unsigned short*)(s_buf + CUR * BUF);
         const unsigned short* const s_v = s_k + TK * D;
 
         const bool tree = t >= ptiles;
         const int key0 = tree ? (t - ptiles) * TK : t * TK;
         const int kend = tree ? a_nk : L;
+        // visibility of the tile's 64 keys for this lane's query: keys that exist (a uniform bit run), and on
+        // tree tiles the row's ancestor bits
+        const bool masked = tree || key0 + TK > kend;
+        uint64_t vis = kend - key0 >= TK ? ~0ull : ((1ull << (kend - key0)) - 1ull);
+        if (tree) vis &= (uint64_t)s_mw[(CUR * 4 + wave) * 128 + lane] | ((uint64_t)s_mw[(CUR * 4 + wave) * 128 + 64 + lane] << 32);
 
         // one 32-key block at a time: S^T = K Q^T, online softmax, O^T += V^T P^T
 #pragma unroll
@@ -299,13 +357,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             for (int s = 0; s < SLABS; ++s)
                 sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kfr[s]), qf[s], sacc, 0, 0, 0);
             // visibility; accumulator element v is key 32 kbi + 8 (v/4) + 4 h + v%4
-            if (tree || key0 + TK > kend) {
+            if (masked) {
+                const unsigned int vw32 = (unsigned int)(kbi ? (vis >> 32) : vis) >> (4 * h);
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const int key = key0 + 32 * kbi + 8 * (v >> 2) + 4 * h + (v & 3);
-                    bool ok = key < kend;
-                    if (tree) ok = ok && ((mrow[(key >> 6) & (kMaskWords - 1)] >> (key & 63)) & 1ull);
-                    sacc[v] = ok ? sacc[v] : -INFINITY;
+                    // all ones if bit 8 (v/4) + v%4 is set, else zero; the score or -inf, chosen bit by bit
+                    const unsigned int keep = (unsigned int)__builtin_amdgcn_sbfe((int)vw32, 8 * (v >> 2) + (v & 3), 1);
+                    sacc[v] = __uint_as_float((__float_as_uint(sacc[v]) & keep) | (0xff800000u & ~keep));
                 }
             }
             float tmax = sacc[0];
@@ -369,13 +427,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
             for (int d = 0; d < DB; ++d)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) mine[d * 16 + v] = oacc[d][v];
-            mine[DB * 16] = m_run;
-            mine[DB * 16 + 1] = l_run;
+                for (int v4 = 0; v4 < 4; ++v4)
+                    *(f32x4*)(mine + d * 16 + 4 * v4) =
+                        f32x4{oacc[d][4 * v4], oacc[d][4 * v4 + 1], oacc[d][4 * v4 + 2], oacc[d][4 * v4 + 3]};
+            *(f32x4*)(mine + DB * 16) = f32x4{m_run, l_run, 0.f, 0.f};
         }
         __syncthreads();
         if (kh == 0) {
-            const float m2 = mine[DB * 16], l2 = mine[DB * 16 + 1];
+            const f32x4 ml2 = *(const f32x4*)(mine + DB * 16);
+            const float m2 = ml2.x, l2 = ml2.y;
             const float mm = fmaxf(m_run, m2);
             float a1 = 0.f, a2 = 0.f;
             if (mm != -INFINITY) {
@@ -387,7 +447,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
             for (int d = 0; d < DB; ++d)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) oacc[d][v] = oacc[d][v] * a1 + mine[d * 16 + v] * a2;
+                for (int v4 = 0; v4 < 4; ++v4) {
+                    const f32x4 o2 = *(const f32x4*)(mine + d * 16 + 4 * v4);
+                    oacc[d][4 * v4] = oacc[d][4 * v4] * a1 + o2.x * a2;
+                    oacc[d][4 * v4 + 1] = oacc[d][4 * v4 + 1] * a1 + o2.y * a2;
+                    oacc[d][4 * v4 + 2] = oacc[d][4 * v4 + 2] * a1 + o2.z * a2;
+                    oacc[d][4 * v4 + 3] = oacc[d][4 * v4 + 3] * a1 + o2.w * a2;
+                }
         }
     }
     const bool holder = WIDE || kh == 0;         // this wavefront holds finished (O, m, l) of its 32 rows
@@ -420,19 +486,35 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     // instead write back and invalidate the whole L2 once per workgroup.  Order: every wavefront waits
     // until its stores have completed (vmcnt), the workgroup meets at a barrier, then one thread takes the
     // ticket; the workgroup that sees the last ticket therefore reads completed partials only.
-    // part_o  [group][split][query block][d block][v4][pair][lane] 2 floats
-    // part_ml [group][split][query block][row] (m c, l)
+    // Only the live rows of a query block travel (a block holds live = min(32, g n - first row) of them):
+    // part_o  [group][split][query block][e][64] x 8 bytes; e = (d block, group of four accumulator values as bf16)
+    //         -- or (d block, pair of floats) when the exchange is fp32 -- and the live lanes of the two half-waves
+    //         packed at the front of each 64-slot line (slot h live + l32): every store and load instruction touches
+    //         one contiguous run, and nothing is moved for rows that do not exist
+    // part_ml [group][split][query block][row] (m c, l) as two floats
     typedef unsigned long long u64;
+    // EPS 64-bit elements per (lane, d block): pairs of floats, or with bf16 partials groups of four values
+    constexpr int EPS = OT_ATTN_PART_BF16 ? 4 : 8;
     auto pack2 = [](float x, float y) -> u64 { return (u64)__float_as_uint(x) | ((u64)__float_as_uint(y) << 32); };
+    auto pack4 = [](float x, float y, float z, float w) -> u64 {
+        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+        const bf16x2 lo = {(__bf16)x, (__bf16)y}, hi = {(__bf16)z, (__bf16)w};
+        return (u64)__builtin_bit_cast(unsigned int, lo) | ((u64)__builtin_bit_cast(unsigned int, hi) << 32);
+    };
     const int group = bz * a_row_blocks + rb;
-    if (holder) {
-        u64* po = (u64*)a.part_o + (((size_t)group * a_splits + split) * NQB + qb) * (DB * 8 * 64) + lane;
+    const int rows_all = a_g * n;
+    if (holder && row_ok) {
+        const int live = min(32, rows_all - (rb * ROWS + qb * 32));
+        u64* po = (u64*)a.part_o + (((size_t)group * a_splits + split) * NQB + qb) * (DB * EPS * 64) + h * live + l32;
 #pragma unroll
         for (int d = 0; d < DB; ++d)
 #pragma unroll
-            for (int v2 = 0; v2 < 8; ++v2)
-                __hip_atomic_store(po + (d * 8 + v2) * 64, pack2(oacc[d][2 * v2], oacc[d][2 * v2 + 1]), __ATOMIC_RELAXED,
-                                   __HIP_MEMORY_SCOPE_AGENT);
+            for (int e = 0; e < EPS; ++e) {
+                const u64 w = OT_ATTN_PART_BF16
+                                  ? pack4(oacc[d][4 * e % 16], oacc[d][(4 * e + 1) % 16], oacc[d][(4 * e + 2) % 16], oacc[d][(4 * e + 3) % 16])
+                                  : pack2(oacc[d][2 * e], oacc[d][2 * e + 1]);
+                __hip_atomic_store(po + (d * EPS + e) * 64, w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
         if (h == 0)                                                  // lanes l and l + 32 hold the same row
             __hip_atomic_store((u64*)a.part_ml + (((size_t)group * a_splits + split) * NQB + qb) * 32 + l32,
                                pack2(m_run == -INFINITY ? -INFINITY : m_run * c /* log2 units */, l_run),
@@ -451,11 +533,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     constexpr int DC = WIDE ? DB : DB / 2;
     const int cq = WIDE ? wave : (wave & 1);
     const int d0 = WIDE ? 0 : (wave >> 1) * DC;
+    const int rho2 = rb * ROWS + cq * 32 + l32;
+    if (rho2 >= rows_all) return;                      // no row behind this lane (no barrier follows)
+    const int live2 = min(32, rows_all - (rb * ROWS + cq * 32));
     // CHUNK splits at a time: all their loads are issued before the first one is used (each is a trip to
-    // memory), and the running maximum M is carried from chunk to chunk like in the main loop.
-    constexpr int CHUNK = 48 / (DC * 8) > 4 ? 4 : (48 / (DC * 8) < 1 ? 1 : 48 / (DC * 8));   // register budget
+    // memory), and the running maximum M is carried from chunk to chunk like in the main loop.  The narrow
+    // variant has the whole register file of its SIMD and takes eight splits -- normally all -- in one trip.
+    constexpr int MREGS = WIDE ? 64 : 96;
+    constexpr int CHUNK = MREGS / (DC * EPS * 2) < 1 ? 1 : MREGS / (DC * EPS * 2);   // register budget
     const u64* mlp = (const u64*)a.part_ml + ((size_t)group * a_splits * NQB + cq) * 32 + l32;
-    const u64* pp = (const u64*)a.part_o + ((size_t)group * a_splits * NQB + cq) * (DB * 8 * 64) + d0 * 8 * 64 + lane;
+    const u64* pp = (const u64*)a.part_o + ((size_t)group * a_splits * NQB + cq) * (DB * EPS * 64) + d0 * EPS * 64 +
+                    h * live2 + l32;
     float M = -INFINITY, Ls = 0.f;
     f32x16 acc[DC];
 #pragma unroll
@@ -463,14 +551,18 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[d][v] = 0.f;
     for (int s0 = 0; s0 < a_splits; s0 += CHUNK) {
-        u64 ml[CHUNK], x[CHUNK][DC * 8];
+        u64 ml[CHUNK], x[CHUNK][DC * EPS];
 #pragma unroll
         for (int i = 0; i < CHUNK; ++i) {
             const int si = s0 + i < a_splits ? s0 + i : a_splits - 1;      // past the end: a copy, weight 0
             ml[i] = __hip_atomic_load(mlp + (size_t)si * NQB * 32, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            const u64* ps = pp + (size_t)si * NQB * (DB * 8 * 64);
+        }
 #pragma unroll
-            for (int e = 0; e < DC * 8; ++e)
+        for (int i = 0; i < CHUNK; ++i) {
+            const int si = s0 + i < a_splits ? s0 + i : a_splits - 1;
+            const u64* ps = pp + (size_t)si * NQB * (DB * EPS * 64);
+#pragma unroll
+            for (int e = 0; e < DC * EPS; ++e)
                 x[i][e] = __hip_atomic_load(ps + e * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         float mi[CHUNK], m_new = M;
@@ -491,16 +583,25 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             const float w = mi[i] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(mi[i] - m_new);
             Ls = fmaf(w, __uint_as_float((unsigned)(ml[i] >> 32)), Ls);
 #pragma unroll
-            for (int e = 0; e < DC * 8; ++e) {
-                acc[e >> 3][2 * (e & 7)] = fmaf(w, __uint_as_float((unsigned)x[i][e]), acc[e >> 3][2 * (e & 7)]);
-                acc[e >> 3][2 * (e & 7) + 1] = fmaf(w, __uint_as_float((unsigned)(x[i][e] >> 32)), acc[e >> 3][2 * (e & 7) + 1]);
+            for (int e = 0; e < DC * EPS; ++e) {
+                const unsigned int lo = (unsigned)x[i][e], hi = (unsigned)(x[i][e] >> 32);
+                if (OT_ATTN_PART_BF16) {
+                    const int dd = e / EPS, v0 = 4 * (e % EPS);
+                    acc[dd][v0] = fmaf(w, __uint_as_float(lo << 16), acc[dd][v0]);
+                    acc[dd][v0 + 1] = fmaf(w, __uint_as_float(lo & 0xffff0000u), acc[dd][v0 + 1]);
+                    acc[dd][v0 + 2] = fmaf(w, __uint_as_float(hi << 16), acc[dd][v0 + 2]);
+                    acc[dd][v0 + 3] = fmaf(w, __uint_as_float(hi & 0xffff0000u), acc[dd][v0 + 3]);
+                } else {
+                    acc[e >> 3][2 * (e & 7)] = fmaf(w, __uint_as_float(lo), acc[e >> 3][2 * (e & 7)]);
+                    acc[e >> 3][2 * (e & 7) + 1] = fmaf(w, __uint_as_float(hi), acc[e >> 3][2 * (e & 7) + 1]);
+                }
             }
         }
         M = m_new;
     }
-    const int rho2 = rb * ROWS + cq * 32 + l32;
-    if (rho2 < a_g * n) {
-        const int hq2 = hk * a_g + rho2 / n, node2 = rho2 % n;
+    {
+        const int head2 = fast_div(rho2, n, a_inv_n);
+        const int hq2 = hk * a_g + head2, node2 = rho2 - head2 * n;
         const float inv = Ls > 0.f ? 1.f / Ls : 0.f;
         unsigned short* orow =
             (unsigned short*)a.O + (long long)b * a.os[0] + (long long)hq2 * a.os[1] + (long long)node2 * a.os[2];
@@ -542,7 +643,7 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const AttnKArgs a) {
     if (tid == 0 && hq == 0 && split == 0 && rb == 0) report_clamp(a.counters, a.prefix_len[b], a.max_prefix);
     const int ptiles = (L + TK - 1) / TK, ttiles = (a.nk + TK - 1) / TK;
     int t0, t1;
-    split_range(ptiles + ttiles, a.splits, split, t0, t1);
+    split_range(ptiles + ttiles, a.splits, a.inv_splits, split, t0, t1);
     const int node = rb * RB + r;
     const bool row_ok = node < n;
 
@@ -553,7 +654,7 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const AttnKArgs a) {
         if (rb * RB + rr < n) w = *(const f32x4*)(qbase + (long long)(rb * RB + rr) * a.qs[2] + cc);
         *(f32x4*)(s_q + rr * D + cc) = w;
     }
-    uint64_t mrow[kMaskWords] = {0ull, 0ull, 0ull, 0ull, 0ull, 0ull, 0ull, 0ull};
+    uint64_t mrow[kMaskWordsF32] = {0ull, 0ull, 0ull, 0ull, 0ull, 0ull, 0ull, 0ull};
     if (row_ok)
         for (int w = 0; w < a.W; ++w) mrow[w] = a.mask[((long long)b * n + node) * a.W + w];
 
@@ -737,13 +838,19 @@ AttnPlan plan_attention(const ot_attn_params& p) {
     if (splits > max_tiles) splits = max_tiles;
     if (splits > kMaxSplits) splits = kMaxSplits;
     if (splits < 1) splits = 1;
-    // even out: every split gets the same number of tiles (the last one possibly fewer)
-    const int per = (max_tiles + splits - 1) / splits;
-    splits = (max_tiles + per - 1) / per;
+#ifndef OT_ATTN_EVEN_OUT
+#define OT_ATTN_EVEN_OUT 1
+#endif
+    if (OT_ATTN_EVEN_OUT) {
+        // even out: every split gets the same number of tiles (the last one possibly fewer)
+        const int per = (max_tiles + splits - 1) / splits;
+        splits = (max_tiles + per - 1) / per;
+    }
     pl.splits = splits;
     // bf16: partials are stored per workgroup (rows padded to the row block); f32: per output row
     const size_t rows = p.dtype == OT_BF16 ? (size_t)base * rows_wg : (size_t)p.batch * p.q_heads * p.n;
-    pl.part_o_bytes = splits > 1 ? align_up(rows * splits * p.head_dim * 4, 256) : 0;
+    const size_t part_elem = (p.dtype == OT_BF16 && OT_ATTN_PART_BF16) ? 2 : 4;
+    pl.part_o_bytes = splits > 1 ? align_up(rows * splits * p.head_dim * part_elem, 256) : 0;
     pl.part_ml_bytes = splits > 1 ? align_up(rows * splits * 2 * 4, 256) : 0;
     pl.bytes = OT_ATTN_SYNC_BYTES + pl.part_o_bytes + pl.part_ml_bytes + 256;
     return pl;
@@ -768,18 +875,20 @@ int launch_tree_attention(const ot_attn_params& p, const AttnPlan& plan, const v
         a.kts[i] = p.kt_strides[i]; a.vts[i] = p.vt_strides[i]; a.os[i] = p.o_strides[i];
     }
     a.row_blocks = plan.row_blocks;
+    auto magic = [](int d) { return d <= 1 ? 0u : (unsigned int)((0x100000000ull + (unsigned)d - 1) / (unsigned)d); };
+    a.inv_splits = magic(a.splits); a.inv_kv_heads = magic(a.kv_heads); a.inv_n = magic(a.n);
     if (p.dtype == OT_BF16) {
         const bool wide = a.g * p.n > 64;
         const long long units = (long long)p.batch * p.kv_heads * plan.splits;
-        const long long wgs = (units + 7) / 8 * 8 * plan.row_blocks;
-        if (wgs > 0x7fffffffLL) return OT_ERR_UNSUPPORTED;
+        const long long unit_groups = (units + 7) / 8;
+        if (unit_groups > 65535 || 8LL * plan.row_blocks > 0x7fffffffLL) return OT_ERR_UNSUPPORTED;   // cannot happen within the limits
         if (plan.splits > 1 && (long long)p.batch * p.kv_heads * plan.row_blocks * 4 > OT_ATTN_STATUS_OFFSET)
             return OT_ERR_UNSUPPORTED;      // cannot happen: splits > 1 only with few workgroups
-        const dim3 grid((unsigned)wgs);
-#define OT_ATTN_ARGS a.prefix_len, a.mask, a.Q, a.row_blocks, a.splits, a.kv_heads, a.g, a.n, a.max_prefix, a.nk, a.W, a
+        const dim3 grid((unsigned)(8 * plan.row_blocks), (unsigned)unit_groups);
+#define OT_ATTN_ARGS a.prefix_len, a.mask, a.Q, a.splits, a.inv_splits, a.kv_heads, a.inv_kv_heads, a.n, a.inv_n, a
 #define OT_ATTN_LAUNCH(DD, WW)                                                                             \
     do {                                                                                                   \
-        const size_t lds = (size_t)((WW) ? 2 : OT_ATTN_NBUF_NARROW) * 64 * DD * sizeof(unsigned int);      \
+        const size_t lds = (size_t)((WW) ? 2 : OT_ATTN_NBUF_NARROW) * (64 * DD + 512) * sizeof(unsigned int); \
         if (lds > 64 * 1024)                                                                               \
             OT_HIP_CHECK(hipFuncSetAttribute((const void*)attn_mfma_kernel<DD, WW>,                        \
                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));       \
@@ -822,7 +931,7 @@ static int validate_attn(const ot_attn_params* p) {
     if (p->head_dim != 64 && p->head_dim != 128) return OT_ERR_UNSUPPORTED;
     if (p->n > OT_MAX_NODES) return OT_ERR_UNSUPPORTED;
     if (p->n_keys < 0) return OT_ERR_INVALID_ARG;
-    if (p->n_keys > OT_MAX_TREE_KEYS) return OT_ERR_UNSUPPORTED;
+    if (p->n_keys > (p->dtype == OT_BF16 ? OT_MAX_TREE_KEYS : OT_MAX_TREE_KEYS_F32)) return OT_ERR_UNSUPPORTED;
     if ((long long)p->batch * p->q_heads > 65535 || (long long)p->batch * p->q_heads * p->n > 0x7fffffffLL)
         return OT_ERR_UNSUPPORTED;
     const int vec = p->dtype == OT_BF16 ? 8 : 4;
