@@ -50,6 +50,7 @@ constexpr int kMaxSplits = 32;
 constexpr int kMaskWordsF32 = 8;                              // the f32 kernel holds a mask row in eight registers
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -119,7 +120,7 @@ __device__ __forceinline__ void split_range(int T, int S, unsigned int inv_S, in
 // WIDE = false: 64 packed rows per workgroup, wavefront = (query block of 32 rows) x (half of each
 //                64-key tile); the two halves are merged through LDS at the end.  For few rows.
 //                Three tile buffers: two tiles are in flight while a third is being computed.
-// WIDE = true : 128 packed rows per workgroup, wavefront = 32 rows x the whole tile; staging one
+// WIDE (VAR 1, 2): 128 or 256 packed rows per workgroup (four or eight wavefronts), wavefront = 32 rows x the whole tile; staging one
 //                tile in LDS is shared by twice as many MFMAs and nothing is merged at the end.
 //                Two tile buffers, so that two workgroups share a compute unit.
 // Workgroups are numbered so that those which stream the same K/V (the row blocks of one
@@ -140,24 +141,27 @@ __device__ __forceinline__ void split_range(int T, int S, unsigned int inv_S, in
 #ifndef OT_ATTN_PART_BF16
 #define OT_ATTN_PART_BF16 1
 #endif
-template <int D, bool WIDE>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_mfma_kernel(
+template <int D, int VAR>
+__global__ __launch_bounds__(VAR == 2 ? 512 : 256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_mfma_kernel(
     // what the first loads need, as leading scalar arguments: the hardware hands these over in registers at
     // wavefront start (kernel-argument preload); they repeat fields of `a`
     const int32_t* a_prefix_len, const uint64_t* a_mask, const void* a_Q, const int a_splits, const unsigned a_inv_splits,
     const int a_kv_heads, const unsigned a_inv_kv_heads, const int a_n, const unsigned a_inv_n, const AttnKArgs a) {
     const int a_g = a.g, a_max_prefix = a.max_prefix, a_nk = a.nk, a_W = a.W, a_row_blocks = a.row_blocks;
+    constexpr bool WIDE = VAR >= 1;
+    constexpr int NWAVES = VAR == 2 ? 8 : 4;
+    constexpr int NT = 64 * NWAVES;        // threads
     constexpr int TK = 64;                 // keys per tile
     constexpr int CPR = D / 8;             // 16-byte chunks per row
     constexpr int SPR = D / 16;            // 32-byte segments per row
     constexpr int SLABS = D / 16;          // 16-wide d slabs of the QK^T contraction
     constexpr int DB = D / 32;             // 32-wide d blocks of O^T
-    constexpr int CH = TK * D / 8 / 256;   // 16-byte chunks per thread per tile (K or V)
+    constexpr int CH = TK * D / 8 / NT;    // 16-byte chunks per thread per tile (K or V)
     constexpr int LPT = 2 * CH;            // asynchronous loads per thread per tile
     constexpr int NKB = WIDE ? 2 : 1;      // 32-key blocks per wavefront per tile
-    constexpr int ROWS = WIDE ? 128 : 64;  // packed query rows per workgroup
+    constexpr int ROWS = VAR == 2 ? 256 : (WIDE ? 128 : 64);   // packed query rows per workgroup
     constexpr int NQB = ROWS / 32;         // query blocks per workgroup
-    constexpr int NBUF = WIDE ? 2 : OT_ATTN_NBUF_NARROW;
+    constexpr int NBUF = VAR == 2 ? 4 : (WIDE ? 2 : OT_ATTN_NBUF_NARROW);
     constexpr int PD = NBUF - 1;           // tiles requested ahead of the one being computed
     static_assert(PD >= 1 && PD <= 3 && PD * LPT < 64, "prefetch depth fits the vmcnt counter");
 
@@ -205,7 +209,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     // this lane's ancestor mask row: one 64-bit word per 64-key tree tile, requested with the tile and, like it,
     // delivered straight into LDS (s_mw: per buffer and wavefront the low words of the 64 lanes, then the high words)
     const uint64_t* const mask_row = a_mask + ((long long)b * n + node) * a_W;
-    unsigned int* const s_mw = s_buf + NBUF * BUF;                      // [NBUF][4 waves][2][64]
+    unsigned int* const s_mw = s_buf + NBUF * BUF;                      // [NBUF][waves][2][64]
 
     const unsigned short* kp = (const unsigned short*)a.Kp + (long long)b * a.kps[0] + (long long)hk * a.kps[1];
     const unsigned short* vp = (const unsigned short*)a.Vp + (long long)b * a.vps[0] + (long long)hk * a.vps[1];
@@ -226,10 +230,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
         for (int v = 0; v < 16; ++v) oacc[d][v] = 0.f;
 
-    // LDS slot sigma = cc * 256 + tid (16 bytes each) holds key row sigma / CPR, chunk position sigma % CPR;
+    // LDS slot sigma = cc * NT + tid (16 bytes each) holds key row sigma / CPR, chunk position sigma % CPR;
     // the chunk stored there is the one the swizzle maps to that position.  KSTEP rows separate cc and cc+1,
     // a multiple of 16, so the swizzle term is the same for every cc.
-    constexpr int KSTEP = 256 / CPR;
+    constexpr int KSTEP = NT / CPR;
     const int kkey0 = tid / CPR, pc = tid % CPR;
     const int kcol = (pc ^ (kkey0 & (CPR - 1))) * 8;                                         // K: chunk c = pc ^ (r % 16)
     const int vcol = (2 * ((pc >> 1) ^ (kkey0 & (SPR - 1))) + (pc & 1)) * 8;                 // V: segment g = (pc/2) ^ (r % 8)
@@ -249,12 +253,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     int t0, t1;
     split_range(ptiles + ttiles, a_splits, a_inv_splits, split, t0, t1);
     auto request_tile = [&](int t, auto buf_c) {
-        constexpr int buf = decltype(buf_c)::value;
+        const int buf = buf_c;                 // a compile-time constant or, in the wide variant's fast loop, a value
         const bool tree = t >= ptiles;
         // the mask word of a tree tile travels ahead of the tile's K/V (older, so it has landed when the tile's
         // wait is over)
         if (tree) {
-            const unsigned lds_w = (unsigned)(size_t)(__attribute__((address_space(3))) void*)(s_mw + (buf * 4 + wave) * 128);
+            const unsigned lds_w = (unsigned)(size_t)(__attribute__((address_space(3))) void*)(s_mw + (buf * NWAVES + wave) * 128);
             const unsigned int* const wp = (const unsigned int*)(mask_row + (t - ptiles));
             asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, off" ::"s"(lds_w), "v"(wp) : "m0", "memory");
             asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, off" ::"s"(lds_w + 256), "v"(wp + 1) : "m0", "memory");
@@ -274,16 +278,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             unsigned lds_k = (unsigned)(size_t)(__attribute__((address_space(3))) void*)(lk + wave_u * 256);
             unsigned lds_v = (unsigned)(size_t)(__attribute__((address_space(3))) void*)(lv + wave_u * 256);
 #pragma unroll
-            for (int cc = 0; cc < CH; ++cc) {                 // 16-byte slots cc * 256 + wave * 64 + lane
+            for (int cc = 0; cc < CH; ++cc) {                 // 16-byte slots cc * NT + wave * 64 + lane
                 asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_k), "v"(kofs), "s"(gk) : "m0", "memory");
                 asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_v), "v"(vofs), "s"(gv) : "m0", "memory");
                 gk += KSTEP * ks; gv += KSTEP * vs;
-                lds_k += 256 * 16; lds_v += 256 * 16;
+                lds_k += NT * 16; lds_v += NT * 16;
             }
         } else {
 #pragma unroll
             for (int cc = 0; cc < CH; ++cc) {
-                const int slot0 = cc * 256 + wave_u * 64;
+                const int slot0 = cc * NT + wave_u * 64;
                 const unsigned lds_k = (unsigned)(size_t)(__attribute__((address_space(3))) void*)(lk + slot0 * 4);
                 const unsigned lds_v = (unsigned)(size_t)(__attribute__((address_space(3))) void*)(lv + slot0 * 4);
                 int row = key0 + kkey0 + cc * KSTEP;
@@ -300,7 +304,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     // same (one word each, into the unused buffer's mask-word slots: a load without a destination register): the
     // wait for Q below can then name a fixed count of younger requests.
     auto pad_requests = [&](int buf) {
-        const unsigned lds_w = (unsigned)(size_t)(__attribute__((address_space(3))) void*)(s_mw + (buf * 4 + wave) * 128);
+        const unsigned lds_w = (unsigned)(size_t)(__attribute__((address_space(3))) void*)(s_mw + (buf * NWAVES + wave) * 128);
 #pragma unroll
         for (int i = 0; i < LPT; ++i)
             asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, off" ::"s"(lds_w), "v"(a_prefix_len) : "m0", "memory");
@@ -341,7 +345,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         // tree tiles the row's ancestor bits
         const bool masked = tree || key0 + TK > kend;
         uint64_t vis = kend - key0 >= TK ? ~0ull : ((1ull << (kend - key0)) - 1ull);
-        if (tree) vis &= (uint64_t)s_mw[(CUR * 4 + wave) * 128 + lane] | ((uint64_t)s_mw[(CUR * 4 + wave) * 128 + 64 + lane] << 32);
+        if (tree) vis &= (uint64_t)s_mw[(CUR * NWAVES + wave) * 128 + lane] | ((uint64_t)s_mw[(CUR * NWAVES + wave) * 128 + 64 + lane] << 32);
 
         // one 32-key block at a time: S^T = K Q^T, online softmax, O^T += V^T P^T
 #pragma unroll
@@ -410,12 +414,187 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             }
         }
     };
-    for (int t = t0; t < t1; t += NBUF) {
-        tile_step(t, std::integral_constant<int, 0>{});
-        if (t + 1 < t1) tile_step(t + 1, std::integral_constant<int, 1>{});
-        if (NBUF > 2 && t + 2 < t1) tile_step(t + 2, std::integral_constant<int, (NBUF > 2 ? 2 : 0)>{});
-        if (NBUF > 3 && t + 3 < t1) tile_step(t + 3, std::integral_constant<int, (NBUF > 3 ? 3 : 0)>{});
+    int t_done = t0;           // tiles [t0, t_done) are consumed
+    if constexpr (WIDE) {
+        // ---- fast loop of the 128-row variant over full prefix tiles: what the MFMA-bound shapes spend their time in.
+        // The softmax reference of a row stays FIXED while scores do not exceed it by more than kSlack (in units
+        // of log2 e / scale): p = 2^(c s - c ref) may then exceed one, which fp32 sums and bf16 operands take in
+        // their stride, and O is never rescaled inside the loop -- the accumulators stay in their registers, the
+        // loop body has no data-dependent path, and the two 32-key blocks of a tile are skewed against each other
+        // so that the matrix pipe and the vector ALU work at the same time inside one wavefront (S of block 1
+        // while the exponentials of block 0 are taken, P V of block 0 while those of block 1 are).  A score beyond
+        // the slack (every row's first tile, then rarely) leaves the loop before anything of the tile is added;
+        // the reference moves up, O and l are rescaled out here, and the loop is entered again at the same tile.
+        constexpr float kSlack = 12.f;
+        static_assert((NBUF & (NBUF - 1)) == 0, "the buffer of a tile is (t - t0) mod NBUF");
+        // tile t has landed for this lane when only the requests of the tiles behind it are outstanding; after the
+        // barrier it has for everybody, and everybody is done with the buffer that tile t + PD goes into
+        auto stage_tile = [&](int t) {
+            const int ahead = t1 - 1 - t < PD - 1 ? t1 - 1 - t : PD - 1;
+            if (ahead <= 0)      asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            else if (ahead == 1) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(LPT) : "memory");
+            else                 asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(2 * LPT) : "memory");
+            if (t + PD < t1) request_tile(t + PD, (t + PD - t0) & (NBUF - 1));
+        };
+        const int t_full = min(t1, L / TK);                      // tiles below t_full are full prefix tiles
+        auto kfrag = [&](const unsigned short* s_k, int kb, int s) {
+            return *(const u32x4*)(s_k + (32 * kb + l32) * D + (((2 * s) ^ kx) << 3));
+        };
+        auto vfrag = [&](const unsigned short* s_v, int kb, int u, int d) {
+            // column 32d+l32 of keys 32kb+16u+4h+{0..3} and of the same +8 (transpose loads, see tile_step)
+            const unsigned short* seg = s_v + (32 * kb + 16 * u + 4 * h + tr_j) * D + (((2 * d) ^ vx) << 4) + tr_q;
+            const s16x4 lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)seg);
+            const s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(seg + 8 * D));
+            return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7));
+        };
+        auto row_max = [&](const f32x16& x) {                   // eight three-input maxima
+            float m = fmaxf(fmaxf(x[0], x[1]), x[2]);
+#pragma unroll
+            for (int v = 3; v < 15; v += 2) m = fmaxf(fmaxf(m, x[v]), x[v + 1]);
+            return xhalf_max(fmaxf(m, x[15]));
+        };
+        int t = t0;
+        bool staged = false;                                      // tile t has been awaited and published
+        float seen = -INFINITY;                                   // largest score of the tile that left the loop
+        while (t < t_full) {
+            if (!staged) {
+                stage_tile(t);
+                staged = true;
+            }
+            {   // move the reference up to what tile t needs; O and l follow
+                const unsigned short* const s_k = (const unsigned short*)(s_buf + ((t - t0) & (NBUF - 1)) * BUF);
+                f32x16 sa, sb;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) { sa[v] = 0.f; sb[v] = 0.f; }
+#pragma unroll
+                for (int s = 0; s < SLABS; ++s) {
+                    sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kfrag(s_k, 0, s)), qf[s], sa, 0, 0, 0);
+                    sb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kfrag(s_k, 1, s)), qf[s], sb, 0, 0, 0);
+                }
+                const float m_new = fmaxf(m_run, fmaxf(row_max(sa), row_max(sb)));
+                const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);      // m_run = -inf gives 0
+                l_run *= alpha;
+#pragma unroll
+                for (int d = 0; d < DB; ++d)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) oacc[d][v] *= alpha;
+                m_run = m_new;
+            }
+            const float mc = m_run * c;
+            const float limit = m_run + kSlack / c;
+            for (;;) {
+                if (!staged) stage_tile(t);
+                staged = true;
+                const unsigned short* const s_k = (const unsigned short*)(s_buf + ((t - t0) & (NBUF - 1)) * BUF);
+                const unsigned short* const s_v = s_k + TK * D;
+                u32x4 kf[SLABS];
+                bf16x8 va[2][DB], vb[2][DB];       // V operands of block 0 and of block 1
+                f32x16 s0, s1;
+#pragma unroll
+                for (int s = 0; s < SLABS; ++s) kf[s] = kfrag(s_k, 0, s);
+#pragma unroll
+                for (int v = 0; v < 16; ++v) { s0[v] = 0.f; s1[v] = 0.f; }
+#pragma unroll
+                for (int s = 0; s < SLABS; ++s)
+                    s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[s]), qf[s], s0, 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int s = 0; s < SLABS; ++s) kf[s] = kfrag(s_k, 1, s);
+                seen = row_max(s0);
+                if (__any(seen > limit)) break;
+                __builtin_amdgcn_sched_barrier(0);
+                // S of block 1 in the matrix pipe, the exponentials of block 0 in the vector ALU, the V operands of
+                // block 0 on their way.  One matrix instruction, then its share of the rest: the wavefront issues in
+                // order, and a run of dependent MFMAs would otherwise hold everything else back until the last one.
+#pragma unroll
+                for (int s = 0; s < SLABS; ++s)
+                    s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[s]), qf[s], s1, 0, 0, 0);
+#pragma unroll
+                for (int u = 0; u < 2; ++u)
+#pragma unroll
+                    for (int d = 0; d < DB; ++d) va[u][d] = vfrag(s_v, 0, u, d);
+                bf16x8 p0[2], p1[2];
+                float psum = 0.f;
+                const bf16x2 ones2 = {(__bf16)1.f, (__bf16)1.f};
+#pragma unroll
+                for (int v = 0; v < 16; v += 2) {
+                    // a pair of probabilities, rounded to the MFMA's operand type, and their sum taken from the
+                    // rounded pair with one dot-product instruction (l then matches what P V multiplies by)
+                    const bf16x2 pr = {(__bf16)__builtin_amdgcn_exp2f(fmaf(s0[v], c, -mc)),
+                                       (__bf16)__builtin_amdgcn_exp2f(fmaf(s0[v + 1], c, -mc))};
+                    psum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones2, psum, false);
+                    p0[v >> 3][v & 7] = pr[0];
+                    p0[v >> 3][(v & 7) + 1] = pr[1];
+                }
+                // (the empty statement is a use of P here: the compiler would otherwise move the exponentials behind
+                // the test below, out of the shadow of the matrix instructions)
+                asm volatile("" ::"v"(p0[0]), "v"(p0[1]), "v"(psum));
+#pragma unroll
+                for (int i = 0; i < SLABS; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x100, 4 * DB / SLABS, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x002, 48 / SLABS, 0);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                seen = row_max(s1);
+                if (__any(seen > limit)) break;
+                __builtin_amdgcn_sched_barrier(0);
+                // P V of block 0 in the matrix pipe, the exponentials of block 1 in the vector ALU, the V operands of
+                // block 1 on their way
+#pragma unroll
+                for (int u = 0; u < 2; ++u)
+#pragma unroll
+                    for (int d = 0; d < DB; ++d) oacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[u][d], p0[u], oacc[d], 0, 0, 0);
+#pragma unroll
+                for (int u = 0; u < 2; ++u)
+#pragma unroll
+                    for (int d = 0; d < DB; ++d) vb[u][d] = vfrag(s_v, 1, u, d);
+#pragma unroll
+                for (int v = 0; v < 16; v += 2) {
+                    // a pair of probabilities, rounded to the MFMA's operand type, and their sum taken from the
+                    // rounded pair with one dot-product instruction (l then matches what P V multiplies by)
+                    const bf16x2 pr = {(__bf16)__builtin_amdgcn_exp2f(fmaf(s1[v], c, -mc)),
+                                       (__bf16)__builtin_amdgcn_exp2f(fmaf(s1[v + 1], c, -mc))};
+                    psum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones2, psum, false);
+                    p1[v >> 3][v & 7] = pr[0];
+                    p1[v >> 3][(v & 7) + 1] = pr[1];
+                }
+#pragma unroll
+                for (int i = 0; i < 2 * DB; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x002, 48 / (2 * DB), 0);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                l_run += psum;
+#pragma unroll
+                for (int u = 0; u < 2; ++u)
+#pragma unroll
+                    for (int d = 0; d < DB; ++d) oacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vb[u][d], p1[u], oacc[d], 0, 0, 0);
+                staged = false;
+                if (++t >= t_full) break;
+            }
+        }
+        (void)seen;
+        t_done = t;
+        // the remaining tiles (the prefix tail and the tree tiles) take the general path, whose buffer index is a
+        // compile-time constant: tile t sits in buffer (t - t0) mod NBUF
+        for (int tt = t_done; tt < t1; ++tt) {
+            const int bi = (tt - t0) & (NBUF - 1);
+            if (bi == 0)                   tile_step(tt, std::integral_constant<int, 0>{});
+            else if (bi == 1)              tile_step(tt, std::integral_constant<int, 1>{});
+            else if (NBUF > 2 && bi == 2)  tile_step(tt, std::integral_constant<int, (NBUF > 2 ? 2 : 0)>{});
+            else if (NBUF > 3)             tile_step(tt, std::integral_constant<int, (NBUF > 3 ? 3 : 0)>{});
+        }
+    } else {
+        for (int t = t0; t < t1; t += NBUF) {
+            tile_step(t, std::integral_constant<int, 0>{});
+            if (t + 1 < t1) tile_step(t + 1, std::integral_constant<int, 1>{});
+            if (NBUF > 2 && t + 2 < t1) tile_step(t + 2, std::integral_constant<int, (NBUF > 2 ? 2 : 0)>{});
+            if (NBUF > 3 && t + 3 < t1) tile_step(t + 3, std::integral_constant<int, (NBUF > 3 ? 3 : 0)>{});
+        }
     }
+    (void)t_done;
 
     l_run = xhalf_sum(l_run);
     if (!WIDE) {
@@ -497,7 +676,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     constexpr int EPS = OT_ATTN_PART_BF16 ? 4 : 8;
     auto pack2 = [](float x, float y) -> u64 { return (u64)__float_as_uint(x) | ((u64)__float_as_uint(y) << 32); };
     auto pack4 = [](float x, float y, float z, float w) -> u64 {
-        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
         const bf16x2 lo = {(__bf16)x, (__bf16)y}, hi = {(__bf16)z, (__bf16)w};
         return (u64)__builtin_bit_cast(unsigned int, lo) | ((u64)__builtin_bit_cast(unsigned int, hi) << 32);
     };
@@ -814,17 +992,27 @@ static size_t align_up(size_t v, size_t al) { return (v + al - 1) / al * al; }
 #define OT_ATTN_WIDE_WGS 512
 #endif
 
+// Packed query rows per workgroup of the bf16 kernel: 64 (narrow: the wavefronts split each tile's keys), 128, or
+// 256 when a KV head has more rows than that -- eight wavefronts then share every staged K/V tile, which halves the
+// traffic into LDS per MFMA and leaves room for a ring of four tiles (three in flight).
+#ifndef OT_ATTN_ROWS256_FROM
+#define OT_ATTN_ROWS256_FROM 129
+#endif
+static int attn_rows_per_workgroup(int rows_per_kv_head) {
+    return rows_per_kv_head <= 64 ? 64 : (rows_per_kv_head >= OT_ATTN_ROWS256_FROM ? 256 : 128);
+}
+
 AttnPlan plan_attention(const ot_attn_params& p) {
     AttnPlan pl;
     const int g = p.q_heads / p.kv_heads;
     int base, tile, rows_wg = 0, splits;
     if (p.dtype == OT_BF16) {
-        const bool wide = g * p.n > 64;                    // wide variant when one KV head has more than 64 rows
-        rows_wg = wide ? 128 : 64;
+        const bool wide = g * p.n > 64;                    // wide variants when one KV head has more than 64 rows
+        rows_wg = attn_rows_per_workgroup(g * p.n);
         pl.row_blocks = (g * p.n + rows_wg - 1) / rows_wg;
         base = p.batch * p.kv_heads * pl.row_blocks;
         tile = 64;
-        int target = wide ? OT_ATTN_WIDE_WGS : OT_ATTN_NARROW_WGS;
+        int target = wide ? (rows_wg == 256 ? OT_ATTN_WIDE_WGS / 2 : OT_ATTN_WIDE_WGS) : OT_ATTN_NARROW_WGS;
         if (!wide && p.head_dim == 64) target *= 2;
         splits = target / base;                            // never more workgroups than fit at once
     } else {
@@ -878,7 +1066,7 @@ int launch_tree_attention(const ot_attn_params& p, const AttnPlan& plan, const v
     auto magic = [](int d) { return d <= 1 ? 0u : (unsigned int)((0x100000000ull + (unsigned)d - 1) / (unsigned)d); };
     a.inv_splits = magic(a.splits); a.inv_kv_heads = magic(a.kv_heads); a.inv_n = magic(a.n);
     if (p.dtype == OT_BF16) {
-        const bool wide = a.g * p.n > 64;
+        const int rows_wg = attn_rows_per_workgroup(a.g * p.n);
         const long long units = (long long)p.batch * p.kv_heads * plan.splits;
         const long long unit_groups = (units + 7) / 8;
         if (unit_groups > 65535 || 8LL * plan.row_blocks > 0x7fffffffLL) return OT_ERR_UNSUPPORTED;   // cannot happen within the limits
@@ -886,17 +1074,19 @@ int launch_tree_attention(const ot_attn_params& p, const AttnPlan& plan, const v
             return OT_ERR_UNSUPPORTED;      // cannot happen: splits > 1 only with few workgroups
         const dim3 grid((unsigned)(8 * plan.row_blocks), (unsigned)unit_groups);
 #define OT_ATTN_ARGS a.prefix_len, a.mask, a.Q, a.splits, a.inv_splits, a.kv_heads, a.inv_kv_heads, a.n, a.inv_n, a
-#define OT_ATTN_LAUNCH(DD, WW)                                                                             \
+#define OT_ATTN_LAUNCH(DD, VV)                                                                             \
     do {                                                                                                   \
-        const size_t lds = (size_t)((WW) ? 2 : OT_ATTN_NBUF_NARROW) * (64 * DD + 512) * sizeof(unsigned int); \
+        const int nbuf = (VV) == 2 ? 4 : ((VV) == 1 ? 2 : OT_ATTN_NBUF_NARROW), nwaves = (VV) == 2 ? 8 : 4; \
+        const size_t lds = (size_t)nbuf * (64 * DD + nwaves * 128) * sizeof(unsigned int);                 \
         if (lds > 64 * 1024)                                                                               \
-            OT_HIP_CHECK(hipFuncSetAttribute((const void*)attn_mfma_kernel<DD, WW>,                        \
+            OT_HIP_CHECK(hipFuncSetAttribute((const void*)attn_mfma_kernel<DD, VV>,                        \
                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));       \
-        if (ev0 || ev1) hipExtLaunchKernelGGL((attn_mfma_kernel<DD, WW>), grid, dim3(256), lds, s, ev0, ev1, 0, OT_ATTN_ARGS); \
-        else hipLaunchKernelGGL((attn_mfma_kernel<DD, WW>), grid, dim3(256), lds, s, OT_ATTN_ARGS);        \
+        if (ev0 || ev1) hipExtLaunchKernelGGL((attn_mfma_kernel<DD, VV>), grid, dim3(64 * nwaves), lds, s, ev0, ev1, 0, OT_ATTN_ARGS); \
+        else hipLaunchKernelGGL((attn_mfma_kernel<DD, VV>), grid, dim3(64 * nwaves), lds, s, OT_ATTN_ARGS);  \
     } while (0)
-        if (p.head_dim == 128) { if (wide) OT_ATTN_LAUNCH(128, true); else OT_ATTN_LAUNCH(128, false); }
-        else                   { if (wide) OT_ATTN_LAUNCH(64, true); else OT_ATTN_LAUNCH(64, false); }
+        const int var = rows_wg == 256 ? 2 : (rows_wg == 128 ? 1 : 0);
+        if (p.head_dim == 128) { if (var == 2) OT_ATTN_LAUNCH(128, 2); else if (var == 1) OT_ATTN_LAUNCH(128, 1); else OT_ATTN_LAUNCH(128, 0); }
+        else                   { if (var == 2) OT_ATTN_LAUNCH(64, 2); else if (var == 1) OT_ATTN_LAUNCH(64, 1); else OT_ATTN_LAUNCH(64, 0); }
 #undef OT_ATTN_LAUNCH
 #undef OT_ATTN_ARGS
     } else {

@@ -301,3 +301,21 @@ def test_repeated_launches_are_bit_identical():
             torch.cuda.synchronize()
             assert torch.equal(pa.out, first)
     assert int(pa.ws[:4096].view(torch.int32).abs().sum().item()) == 0
+
+
+@pytest.mark.parametrize("Hq,Hkv,n", [(8, 2, 25), (16, 2, 40), (4, 4, 70)])      # 100, 320 and 70 packed rows per KV head
+def test_scores_that_jump_between_tiles(Hq, Hkv, n):
+    """The 128- and 256-row variants keep a row's softmax reference fixed while scores stay within a slack of it and
+    move it up otherwise: key bands whose scores differ by factors of up to 400 (beyond what 2^x can hold in fp32
+    relative to the first band) force that path again and again, in the middle of a split."""
+    w = _shape("bf16", 2, Hq, Hkv, 128, 1000, n)
+    x = wl.make_attention_inputs(w, 31)
+    kp = wl.bf16_bits_to_f32(x["K_prefix"]).copy()
+    for lo, f in [(0, 0.1), (200, 1.0), (400, 8.0), (600, 0.5), (800, 40.0), (930, 3.0)]:
+        kp[:, :, lo:] = wl.bf16_bits_to_f32(x["K_prefix"])[:, :, lo:] * f
+    x["K_prefix"] = wl.store(kp, "bf16")
+    mask = _random_masks(2, n, 8)
+    got = _gpu_attention(x, mask, "bf16")
+    want = _oracle_attention(x, mask, "bf16")
+    assert np.isfinite(got).all()
+    assert np.abs(got - want).max() < TOL["bf16"]
