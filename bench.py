@@ -8,9 +8,14 @@ wrote.  Inputs are resident in HBM before the timed region; consecutive steps
 use different copies from a ring larger than the chip's caches, so the logits
 and the K/V cache are streamed from HBM every step.
 
-Prints ONE JSON line: steps/s, the roofline of the dominant kernel (the logits
-row scan, HBM-bound), the K/V-streaming attention kernel as a second roofline,
-and the CPU oracle timed on a bounded sample of the same workload.
+Prints ONE JSON line: steps/s; `roofline` = the roofline-bound kernel that takes
+longest in a step (at the 7B shape the K/V-streaming attention kernel, HBM-bound;
+the tree-selection kernel is longer still but bound by latency, not by a roof),
+`roofline_scan` = the logits row scan; both with the HBM traffic measured by
+rocprofv3 counters (read from the committed summary under profiles/), and against
+a plain streaming read of the same bytes with the same cold-buffer ring; a compact
+leg at the 70B-shaped GQA batch, where the attention is MFMA-bound; and the CPU
+oracle timed on a bounded sample of the same workload.
 """
 from __future__ import annotations
 
@@ -27,10 +32,23 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published
-# HBM bytes one row-scan launch moves (rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, scaled by the same
-# counters' readings for a plain 256 MiB copy); see profiles/bench_7b_hbm_traffic_pmc.txt
-SCAN_TRAFFIC_BYTES = {"7b": 26.56e6}
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, published
+
+
+def measured_traffic(workload: str):
+    """HBM bytes per launch of the scan and the attention kernel as rocprofv3 measured them (--pmc FETCH_SIZE and
+    WRITE_SIZE, scaled by the same counters' readings for a plain 256 MiB copy): the figures of the committed summary
+    profiles/bench_<workload>_hbm_traffic_pmc.txt (lines `traffic <kernel> <bytes>`), or None."""
+    path = os.path.join(ROOT, "profiles", f"bench_{workload}_hbm_traffic_pmc.txt")
+    out = {}
+    try:
+        for line in open(path):
+            f = line.split()
+            if len(f) == 3 and f[0] == "traffic":
+                out[f[1]] = float(f[2])
+    except OSError:
+        return {}, None
+    return out, os.path.relpath(path, ROOT)
 
 
 class Hip:
@@ -93,6 +111,78 @@ def device_attention(w, seed: int, slot: int, plen):
                 V_tree=mk(w.batch, w.kv_heads, w.n, w.head_dim), prefix_len=plen)
 
 
+def gqa_leg(name: str, steps: int, hip, stream):
+    """A compact run of another workload inside the default line: the batched GQA shape whose attention is
+    MFMA-bound.  Inputs are drawn on the device (two ring copies), sequence 0's tree and one (sequence, KV head)
+    group of the attention are checked against the oracle, then `steps` steps are timed with the kernels' own
+    begin/end events."""
+    import torch
+    from oracle import opt_tree as ot_oracle, tree_attention as ta_oracle
+    import workloads as wl
+    from paper_2406_17276_amd import api
+    from tests import _util as U
+    w = wl.WORKLOADS[name]
+    plen_h = wl.prefix_lengths(w, 0)
+    plen_d = torch.from_numpy(plen_h).cuda()
+    bits = lambda t: t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+    builds, attns = [], []
+    for slot in range(2):
+        lg = device_logits(w, 0, slot)
+        at = device_attention(w, 0, slot, plen_d)
+        pb = api.PreparedBuild(lg, w.k, w.n, w.depth)
+        builds.append(pb)
+        attns.append(api.PreparedAttention(at["Q"], at["K_prefix"], at["V_prefix"], at["K_tree"], at["V_tree"], plen_d,
+                                           pb.out.mask))
+    builds[0](stream); attns[0](stream)
+    torch.cuda.synchronize()
+    # parity: the tree of sequence 0 (if its cut gaps allow a bit-exact comparison) and the attention of one group
+    want = ot_oracle.build_tree(U.LazyF64(bits(builds[0].logits[0]), w.dtype), w.k, w.n, w.depth)
+    tree_checked = bool(want["min_gap"] > U.GAP)
+    if tree_checked:
+        sub = api.alloc_tree(1, w.n)
+        for f in ("token", "parent", "depth", "score", "mask", "n_out", "expect"):
+            getattr(sub, f).copy_(getattr(builds[0].out, f)[:1])
+        U.assert_tree_equal(sub, [want], w.n)
+    g = w.q_heads // w.kv_heads
+    Q, Kp, Vp, Kt, Vt = attns[0].keep[:5]
+    f64 = lambda t: wl.to_f64(bits(t), w.dtype)
+    mask_h = builds[0].out.mask[:1].cpu().numpy().view(np.uint64)
+    ref = ta_oracle.tree_verify_attention(f64(Q[:1, :g]), f64(Kp[:1, :1]), f64(Vp[:1, :1]), f64(Kt[:1, :1]), f64(Vt[:1, :1]),
+                                          plen_h[:1], mask_h)
+    err = float(np.abs(U.from_device_f64(attns[0].out[:1, :g]) - ref).max())
+    assert err < 2e-2, f"attention parity {err}"
+    for i in range(4):
+        builds[i % 2](stream); attns[i % 2](stream)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        builds[i % 2](stream); attns[i % 2](stream)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    ev = [[hip.event() for _ in range(4)] for _ in range(steps)]
+    for i in range(steps):
+        builds[i % 2].timed(stream, ev[i][0], ev[i][1])
+        attns[i % 2].timed(stream, ev[i][2], ev[i][3])
+    torch.cuda.synchronize()
+    scan_us = float(np.mean([hip.elapsed_ms(e[0], e[1]) for e in ev])) * 1e3
+    attn_us = float(np.mean([hip.elapsed_ms(e[2], e[3]) for e in ev])) * 1e3
+    S_tot = int(sum(int(l) + w.n for l in plen_h))
+    flops = 4.0 * w.n * S_tot * w.head_dim * w.q_heads
+    logit_bytes = w.batch * w.rows_per_seq() * w.vocab * w.elem_bytes()
+    tf = flops / (attn_us * 1e-6) / 1e12
+    gbs = logit_bytes / (scan_us * 1e-6) / 1e9
+    return {"workload": f"{w.name}: batch {w.batch}, vocab {w.vocab}, depth {w.depth}, top-k {w.k}, n {w.n}; attention "
+                        f"{w.q_heads}q/{w.kv_heads}kv heads, head_dim {w.head_dim}, prefix {w.prefix} +-{int(w.ragged * 100)}%",
+            "steps": steps, "ms_per_step": ms, "steps_per_s": 1e3 / ms, "ring_copies": 2, "inputs": "drawn on the device",
+            "parity_checked": {"tree_sequence_0": tree_checked, "attention_group_0_max_abs_err": err},
+            "roofline": {"kernel": "attn_mfma_kernel", "bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS,
+                         "unit": "TFLOP/s", "frac": tf / MFMA_BF16_PEAK_TFLOPS, "algorithmic_flops": flops,
+                         "avg_kernel_us": attn_us, "traffic": None},
+            "roofline_scan": {"kernel": "row_scan_kernel", "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS,
+                              "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS, "algorithmic_bytes": logit_bytes,
+                              "avg_kernel_us": scan_us, "traffic": None}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -106,6 +196,7 @@ def main():
                     help="draw every input on the device and skip the oracle check and the CPU baseline (for shapes "
                          "whose oracle run takes hours, e.g. --workload large; the line then says parity_checked: false)")
     ap.add_argument("--main-only", action="store_true", help="skip the adaptive-depth and greedy-verification legs")
+    ap.add_argument("--no-gqa-leg", action="store_true", help="skip the compact 70B-shaped GQA leg of the default run")
     ap.add_argument("--cpu-steps", type=int, default=16, help="oracle steps timed for cpu_baseline (0 = skip)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (reference dispatch for scaling rocprofv3 "
@@ -275,8 +366,33 @@ def main():
             api._check(L.ot_yardstick_mfma_loop(iters, sink.data_ptr(), stream), "yardstick")
         torch.cuda.synchronize()
         mfma_tf = 3 * 2048 * 4 * 4 * iters * 32768.0 / (time.perf_counter() - ty) / 1e12
+        # the same plain read at the kernels' own sizes, over the same ring of cold copies: what a launch of this
+        # size can reach at all (ramp-up and tail of a microsecond-scale launch included), timed by HIP events
+        def small_read(tensors, nbytes, workgroups):
+            flat = [t.reshape(-1).view(torch.uint8)[:nbytes // 16 * 16] for t in tensors]
+            sink2 = torch.zeros(workgroups, dtype=torch.int32, device="cuda")
+            evs = [(hip.event(), hip.event()) for _ in range(3 * len(flat))]
+            call = lambda f, e0, e1: api._check(L.ot_yardstick_stream_read_timed(
+                f.data_ptr(), f.numel(), workgroups, sink2.data_ptr(), stream, e0, e1), "yardstick")
+            for f in flat:
+                call(f, None, None)
+            torch.cuda.synchronize()
+            for i, (e0, e1) in enumerate(evs):
+                call(flat[i % len(flat)], e0, e1)
+            torch.cuda.synchronize()
+            us = float(np.median([hip.elapsed_ms(a_, b_) for a_, b_ in evs])) * 1e3
+            return {"bytes": int(flat[0].numel()), "workgroups_of_256": workgroups, "us": us,
+                    "GBs": flat[0].numel() / (us * 1e-6) / 1e9}
+        # the scan's launch holds one 1024-thread workgroup per row part, the attention's one 256-thread workgroup per
+        # (KV head, key split): the reads are launched with as many threads
+        same_scan = (small_read([b_.logits for b_ in builds], logit_bytes, 4 * w.batch * w.rows_per_seq())
+                     if builds[0].logits.is_contiguous() else None)
+        same_attn = small_read([a_.keep[1] for a_ in attns], kv_bytes // 2, 256)
         yard = {"hbm_read_GBs": read_gbs, "mfma_bf16_TFLOPs": mfma_tf,
-                "what": "ot_yardstick_stream_read over 1 GiB; ot_yardstick_mfma_loop (v_mfma_f32_32x32x16_bf16, register operands)"}
+                "hbm_read_scan_sized": same_scan, "hbm_read_half_kv_sized": same_attn,
+                "what": "ot_yardstick_stream_read over 1 GiB (wall clock) and over buffers of the scan's and of half the "
+                        "attention's bytes from the same cold ring (the launch's own begin/end events, median); "
+                        "ot_yardstick_mfma_loop (v_mfma_f32_32x32x16_bf16, register operands)"}
 
     result = {
         "metric": "tree-build+verify-attention steps/sec", "value": K / dt, "unit": "steps/s",
@@ -290,25 +406,44 @@ def main():
                    "ms_per_step_with_events": ms_per_step_events, "ms_per_step_warm_inputs": ms_per_step_warm},
     }
     if scan_ms is not None:
+        traffic, traffic_src = measured_traffic(w.name)
         gbs = logit_bytes / (scan_ms * 1e-3) / 1e9
-        result["roofline"] = {"kernel": "row_scan_kernel", "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS,
-                              "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
-                              "traffic": SCAN_TRAFFIC_BYTES.get(w.name),
-                              "algorithmic_bytes": logit_bytes, "avg_kernel_us": scan_ms * 1e3,
-                              "kernel_us_p10_p50_p90": [float(v) * 1e3 for v in np.percentile(scan_all, [10, 50, 90])]}
-        if yard:
-            result["roofline"]["frac_of_measured_read"] = gbs / yard["hbm_read_GBs"]
+        scan_roof = {"kernel": "row_scan_kernel", "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
+                     "traffic": traffic.get("row_scan_kernel"), "traffic_source": traffic_src,
+                     "algorithmic_bytes": logit_bytes, "avg_kernel_us": scan_ms * 1e3,
+                     "kernel_us_p10_p50_p90": [float(v) * 1e3 for v in np.percentile(scan_all, [10, 50, 90])]}
         agbs = (kv_bytes + qo_bytes) / (attn_ms * 1e-3) / 1e9
-        result["roofline_attention"] = {
-            "kernel": "attn_mfma_kernel" if w.dtype == "bf16" else "attn_f32_kernel", "bound": "hbm",
-            "achieved": agbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": agbs / HBM_PEAK_GBS, "traffic": None,
-            "algorithmic_bytes": kv_bytes + qo_bytes, "avg_kernel_us": attn_ms * 1e3,
-            "mfma_tflops": attn_flops / (attn_ms * 1e-3) / 1e12,
-            "mfma_frac_of_peak": attn_flops / (attn_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
-            "kernel_us_p10_p50_p90": [float(v) * 1e3 for v in np.percentile(attn_all, [10, 50, 90])]}
+        attn_kernel = "attn_mfma_kernel" if w.dtype == "bf16" else "attn_f32_kernel"
+        attn_tf = attn_flops / (attn_ms * 1e-3) / 1e12
+        g_rows = (w.q_heads // w.kv_heads) * w.n
+        mfma_bound = w.dtype == "bf16" and g_rows * 1.0 > 310          # FLOP per K/V byte ~ g n against the ~310 ridge
+        attn_roof = {"kernel": attn_kernel, "avg_kernel_us": attn_ms * 1e3,
+                     "kernel_us_p10_p50_p90": [float(v) * 1e3 for v in np.percentile(attn_all, [10, 50, 90])],
+                     "algorithmic_bytes": kv_bytes + qo_bytes, "algorithmic_flops": attn_flops,
+                     "traffic": traffic.get(attn_kernel), "traffic_source": traffic_src,
+                     "hbm_GBs": agbs, "hbm_frac_of_peak": agbs / HBM_PEAK_GBS,
+                     "mfma_tflops": attn_tf, "mfma_frac_of_peak": attn_tf / MFMA_BF16_PEAK_TFLOPS}
+        if mfma_bound:
+            attn_roof.update({"bound": "mfma", "achieved": attn_tf, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                              "frac": attn_tf / MFMA_BF16_PEAK_TFLOPS})
+        else:
+            attn_roof.update({"bound": "hbm", "achieved": agbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                              "frac": agbs / HBM_PEAK_GBS})
         if yard:
-            result["roofline_attention"]["frac_of_measured_read"] = agbs / yard["hbm_read_GBs"]
-            result["roofline_attention"]["mfma_frac_of_measured"] = attn_flops / (attn_ms * 1e-3) / 1e12 / yard["mfma_bf16_TFLOPs"]
+            scan_roof["frac_of_measured_read"] = gbs / yard["hbm_read_GBs"]
+            if yard.get("hbm_read_scan_sized"):
+                scan_roof["frac_of_same_size_read"] = yard["hbm_read_scan_sized"]["us"] / (scan_ms * 1e3)
+            attn_roof["hbm_frac_of_measured_read"] = agbs / yard["hbm_read_GBs"]
+            attn_roof["mfma_frac_of_measured"] = attn_tf / yard["mfma_bf16_TFLOPs"]
+        # `roofline`: of the kernels a roof bounds, the one that takes longest in a step
+        if attn_ms >= scan_ms:
+            result["roofline"], result["roofline_scan"] = attn_roof, scan_roof
+        else:
+            result["roofline"], result["roofline_attention"] = scan_roof, attn_roof
+        result["config"]["longest_kernel_note"] = (
+            "the tree-selection kernel (one wavefront per sequence, a chain of dependent selections) is not bound by a "
+            "memory or arithmetic roof; its time is ms_per_step minus the two kernels above")
     if yard:
         result["yardsticks"] = yard
 
@@ -456,6 +591,15 @@ def main():
                                  "frac_of_hbm_peak": 2 * logit_bytes / (scan32 * 1e-6) / 1e9 / HBM_PEAK_GBS}
         del pbs
 
+    # ---- the batched GQA shape, where the attention is bound by the matrix pipe, as a compact leg of the default run
+    if args.mode == "stream" and not args.main_only and not args.no_gqa_leg and w.name == "7b":
+        del builds[1:], attns[1:]
+        torch.cuda.empty_cache()
+        result["gqa_70b"] = gqa_leg("70b", 30, hip, stream)
+        if yard:
+            result["gqa_70b"]["roofline"]["frac_of_measured_mfma"] = result["gqa_70b"]["roofline"]["achieved"] / yard["mfma_bf16_TFLOPs"]
+            result["gqa_70b"]["roofline_scan"]["frac_of_measured_read"] = result["gqa_70b"]["roofline_scan"]["achieved"] / yard["hbm_read_GBs"]
+
     # ---- CPU oracle on a bounded sample of the same workload ----------------------------------
     if args.cpu_steps > 0 and not args.skip_parity:
         from threadpoolctl import threadpool_limits
@@ -469,7 +613,8 @@ def main():
                 ta_oracle.tree_verify_attention(f64["Q"], f64["K_prefix"], f64["V_prefix"], f64["K_tree"],
                                                 f64["V_tree"], plen_h, m)
                 cpu_dt += time.perf_counter() - tc
-        result["cpu_baseline"] = {"value": args.cpu_steps / cpu_dt, "unit": "steps/s", "cores": 1, "kind": "oracle",
+        result["cpu_baseline"] = {"value": args.cpu_steps / cpu_dt, "unit": "steps/s", "cores": 1,
+                                  "host_cores": os.cpu_count(), "kind": "oracle",
                                   "sample": f"{args.cpu_steps} full steps of the same workload (fp64 NumPy oracle: "
                                             "tree build + tree attention; inputs pre-generated; 1 thread)"}
     print(json.dumps(result))

@@ -333,6 +333,11 @@ OT_API int ot_kv_append(const ot_attn_params* p, void* K_prefix, void* V_prefix,
 #define OT_YARDSTICK_WORKGROUPS 2048
 OT_API int ot_yardstick_stream_read(const void* src, size_t bytes, void* sink, void* hip_stream);
 OT_API int ot_yardstick_mfma_loop(int32_t iters, void* sink, void* hip_stream);
+/* The streaming read with a caller-chosen number of workgroups (1..2^20, of 256 threads; `sink` holds that many words)
+ * and, as in the *_timed calls above, two optional hipEvent_t that receive the kernel's own begin and end time stamps:
+ * what a launch of a given size and shape reaches, ramp-up and tail included, measured the way the hot kernels are. */
+OT_API int ot_yardstick_stream_read_timed(const void* src, size_t bytes, int32_t workgroups, void* sink, void* hip_stream,
+                                   void* kernel_begin_event, void* kernel_end_event);
 
 #ifdef __cplusplus
 }

@@ -102,6 +102,9 @@ def lib():
         L.ot_kv_append.argtypes = [C.POINTER(AttnParams)] + [C.c_void_p] * 9
         L.ot_yardstick_stream_read.restype = C.c_int
         L.ot_yardstick_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
+        L.ot_yardstick_stream_read_timed.restype = C.c_int
+        L.ot_yardstick_stream_read_timed.argtypes = [C.c_void_p, C.c_size_t, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                                     C.c_void_p]
         L.ot_yardstick_mfma_loop.restype = C.c_int
         L.ot_yardstick_mfma_loop.argtypes = [C.c_int32, C.c_void_p, C.c_void_p]
         L.ot_attn_workspace_bytes.restype = C.c_size_t

@@ -233,6 +233,8 @@ def test_yardsticks_reject_bad_arguments_without_launching():
     assert L.ot_yardstick_stream_read(None, 1 << 20, f, None) == -1
     assert L.ot_yardstick_stream_read(C.c_void_p(0x1008), 1 << 20, f, None) == -1
     assert L.ot_yardstick_stream_read(f, 8, f, None) == -1
+    assert L.ot_yardstick_stream_read_timed(None, 1 << 20, 64, f, None, None, None) == -1
+    assert L.ot_yardstick_stream_read_timed(f, 1 << 20, 0, f, None, None, None) == -1
     assert L.ot_yardstick_mfma_loop(0, f, None) == -1
     assert L.ot_yardstick_mfma_loop(10, None, None) == -1
 
