@@ -551,7 +551,7 @@ def main():
 
     # ---- drafting-phase attention of the same shape, outside the timed region: the n frontier tokens against the
     # prefix and the K/V of all depth*n pool nodes (the draft model's attention of the last drafting step)
-    if args.mode == "stream" and not args.main_only and w.depth * w.n <= 512 and w.dtype == "bf16":
+    if args.mode == "stream" and not args.main_only and w.dtype == "bf16":
         gd = torch.Generator(device="cuda"); gd.manual_seed(seed + 555)
         nk = w.depth * w.n
         ktp = torch.randn((w.batch, w.kv_heads, nk, w.head_dim), generator=gd, device="cuda").to(torch.bfloat16)

@@ -156,8 +156,8 @@ OT_API int ot_tree_finalize(const ot_build_params* p, int32_t steps_done,
  * tree cache.  ot_tree_frontier_mask, called after the expand of step steps_done-1, writes
  *   mask[b][s][0..W)  W = OT_MASK_WORDS(depth*n): bit j set iff pool node j is frontier node s or one of its
  *                     ancestors; rows s >= F are zero,
- * ready for ot_tree_verify_attention with n_keys = depth*n.  Only for depth*n <= OT_MAX_TREE_KEYS
- * (OT_ERR_UNSUPPORTED otherwise). */
+ * ready for ot_tree_verify_attention with n_keys = depth*n (at most OT_MAX_DEPTH * OT_MAX_NODES = OT_MAX_TREE_KEYS
+ * pool nodes; f32 tensors: n_keys up to OT_MAX_TREE_KEYS_F32). */
 OT_API int ot_tree_frontier_mask(const ot_build_params* p, int32_t steps_done,
                           void* workspace, size_t workspace_bytes, uint64_t* mask, void* hip_stream);
 

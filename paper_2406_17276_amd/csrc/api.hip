@@ -70,7 +70,7 @@ BuildWorkspace carve_build_workspace(const ot_build_params& p, void* base) {
     w.seq_E = (double*)take((size_t)p.batch * 8);
     w.seq_steps = (int32_t*)take((size_t)p.batch * 4);
     w.seq_active = (int32_t*)take((size_t)p.batch * 4);
-    if ((long long)p.depth * p.n <= kFrontMaskKeys) w.front_mask = (uint64_t*)take((size_t)2 * p.batch * p.n * 8 * 8);
+    w.front_anc = (unsigned short*)take((size_t)2 * p.batch * p.n * OT_MAX_DEPTH * sizeof(unsigned short));
     w.bytes = off;
     return w;
 }
@@ -240,7 +240,6 @@ int ot_tree_frontier_mask(const ot_build_params* p, int32_t steps_done, void* wo
     int st = validate_build(p, false);
     if (st != OT_OK) return st;
     if (steps_done < 1 || steps_done > p->depth) return OT_ERR_INVALID_ARG;
-    if ((long long)p->depth * p->n > kFrontMaskKeys) return OT_ERR_UNSUPPORTED;
     if (!workspace || (uintptr_t)workspace % 16 || !mask || (uintptr_t)mask % 8) return OT_ERR_INVALID_ARG;
     const BuildWorkspace ws = carve_build_workspace(*p, workspace);
     if (workspace_bytes < ws.bytes) return OT_ERR_WORKSPACE_TOO_SMALL;

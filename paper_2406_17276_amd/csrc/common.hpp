@@ -33,9 +33,6 @@ struct Frontier {
 };
 Frontier make_frontier(int k, int n, int depth);
 
-// Pool nodes (depth * n) up to which the streaming builder keeps the frontier's ancestor masks.
-constexpr int kFrontMaskKeys = 512;
-
 // Elements of one vocabulary row handled by one workgroup of the row scan.
 constexpr int kScanPartElems = 32768;
 inline int scan_parts(int vocab) { return (vocab + kScanPartElems - 1) / kScanPartElems; }
@@ -57,8 +54,7 @@ struct BuildWorkspace {
     double* seq_E;                  // [batch]             streaming state: E of Algorithm 1's loop
     int32_t* seq_steps;             // [batch]             layers drafted (frozen when the loop has stopped)
     int32_t* seq_active;            // [batch]             0 once E_sub - E <= delta was seen
-    uint64_t* front_mask;           // [2][batch][n][8]    ancestor masks of the last two frontiers over pool
-                                    //                     indices; null when depth * n > kFrontMaskKeys
+    unsigned short* front_anc;      // [2][batch][n][OT_MAX_DEPTH]  root paths (pool indices) of the last two frontiers
     size_t bytes;
 };
 BuildWorkspace carve_build_workspace(const ot_build_params& p, void* base);

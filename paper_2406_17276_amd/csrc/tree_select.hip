@@ -31,8 +31,9 @@ struct SelKArgs {
     double* pool_p;                                           // [batch][depth][n]  (streaming state) p^ of every pool node
     double* seq_E; int32_t* seq_steps; int32_t* seq_active;   // [batch]            (streaming state) adaptive depth
     double* e_sub; int32_t* go_on; double delta;              // outputs / threshold of the E_sub query
-    u64* front_mask;                                          // [2][batch][n][8] (streaming state) or null: ancestor
-                                                              // masks of the last two frontiers over pool indices
+    unsigned short* front_anc;                                // [2][batch][n][OT_MAX_DEPTH] (streaming state): the pool
+                                                              // indices of every node of the last two frontiers' root
+                                                              // paths, the node itself last
     u64* mask_out; int mask_words;                            // output of the frontier-mask query
     int gridDim_batch;                                        // batch size (the grid of these kernels)
     int32_t* steps_used;                                      // [batch] output of the one-shot adaptive build
@@ -680,22 +681,17 @@ __global__ __launch_bounds__(256) void tree_step_kernel(const SelKArgs a) {
             a.frontier_parent[(size_t)b * n + off + r] = tid;
         }
     }
-    // ancestor masks of the new frontier over pool indices (layer t+1, slot s) -> t n + s: the parent's mask
-    // plus the node's own bit (Algorithm 2's mask, built incrementally for the drafting phase)
-    if (a.front_mask) {
-        const size_t fm = (size_t)a.gridDim_batch * n * 8;
-        const u64* prev = a.front_mask + (size_t)((t & 1) ^ 1) * fm + ((size_t)b * n + tid) * 8;
-        u64* cur = a.front_mask + (size_t)(t & 1) * fm + (size_t)b * n * 8;
-        u64 pm[8];
-#pragma unroll
-        for (int w = 0; w < 8; ++w) pm[w] = (t > 0 && active) ? prev[w] : 0ull;
-#pragma unroll
-        for (int r = 0; r < KMAX; ++r) {
-            if (r < cnt) {
-                const int idx = t * n + off + r;
-#pragma unroll
-                for (int w = 0; w < 8; ++w) cur[(size_t)(off + r) * 8 + w] = pm[w] | (w == (idx >> 6) ? 1ull << (idx & 63) : 0ull);
-            }
+    // Root paths of the new frontier over pool indices ((layer t+1, slot s) -> t n + s): the parent's path plus the
+    // node itself -- the incremental form of Algorithm 2's mask for the drafting phase.  A path has at most `depth`
+    // entries however many nodes the pool holds, so the state stays small; ot_tree_frontier_mask turns it into bits.
+    {
+        const size_t fa = (size_t)a.gridDim_batch * n * OT_MAX_DEPTH;
+        const unsigned short* prev = a.front_anc + (size_t)((t & 1) ^ 1) * fa + ((size_t)b * n + tid) * OT_MAX_DEPTH;
+        unsigned short* cur = a.front_anc + (size_t)(t & 1) * fa + (size_t)b * n * OT_MAX_DEPTH;
+        for (int r = 0; r < cnt; ++r) {
+            unsigned short* row = cur + (size_t)(off + r) * OT_MAX_DEPTH;
+            for (int e = 0; e < t; ++e) row[e] = prev[e];
+            row[t] = (unsigned short)(t * n + off + r);
         }
     }
 }
@@ -766,16 +762,22 @@ __global__ __launch_bounds__(256) void tree_esub_kernel(const SelKArgs a) {
     }
 }
 
-// The frontier's ancestor masks, from the state the step kernel keeps: mask_out [batch][n][mask_words]
+// The frontier's ancestor masks, from the root paths the step kernel keeps: mask_out [batch][n][mask_words]
 __global__ __launch_bounds__(256) void tree_front_mask_kernel(const SelKArgs a) {
     const int b = blockIdx.x, n = a.n;
     const int steps = a.step < a.seq_steps[b] ? a.step : a.seq_steps[b];
     const int F = steps > 0 ? a.F[steps] : 0;
-    const size_t fm = (size_t)a.gridDim_batch * n * 8;
-    const u64* src = a.front_mask + (size_t)((steps - 1) & 1) * fm + (size_t)b * n * 8;
+    const size_t fa = (size_t)a.gridDim_batch * n * OT_MAX_DEPTH;
+    const unsigned short* src = a.front_anc + (size_t)((steps - 1) & 1) * fa + (size_t)b * n * OT_MAX_DEPTH;
     for (int i = threadIdx.x; i < n * a.mask_words; i += blockDim.x) {
         const int s = i / a.mask_words, w = i - s * a.mask_words;
-        a.mask_out[(size_t)b * n * a.mask_words + i] = (s < F && w < 8) ? src[(size_t)s * 8 + w] : 0ull;
+        u64 bits = 0ull;
+        if (s < F)
+            for (int e = 0; e < steps; ++e) {
+                const int idx = src[(size_t)s * OT_MAX_DEPTH + e];
+                if ((idx >> 6) == w) bits |= 1ull << (idx & 63);
+            }
+        a.mask_out[(size_t)b * n * a.mask_words + i] = bits;
     }
 }
 
@@ -1334,7 +1336,7 @@ SelKArgs make_args(const SelectGeometry& g, const BuildWorkspace& ws) {
     a.pool_p = ws.pool_p; a.seq_E = ws.seq_E; a.seq_steps = ws.seq_steps; a.seq_active = ws.seq_active;
     a.e_sub = nullptr; a.go_on = nullptr; a.delta = 0.0;
     a.steps_used = nullptr;
-    a.front_mask = (u64*)ws.front_mask; a.mask_out = nullptr; a.mask_words = 0; a.gridDim_batch = g.batch;
+    a.front_anc = ws.front_anc; a.mask_out = nullptr; a.mask_words = 0; a.gridDim_batch = g.batch;
     a.out = ot_tree_out{nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
     a.frontier_token = nullptr; a.frontier_parent = nullptr; a.frontier_count = nullptr;
     a.step = 0;
@@ -1505,7 +1507,6 @@ int launch_tree_esub(const SelectGeometry& g, int steps_done, double delta, cons
 int launch_tree_front_mask(const SelectGeometry& g, int steps_done, const BuildWorkspace& ws, uint64_t* mask_out,
                            int mask_words, hipStream_t s) {
     SelKArgs a = make_args(g, ws);
-    if (!a.front_mask) return OT_ERR_UNSUPPORTED;
     a.step = steps_done; a.mask_out = (u64*)mask_out; a.mask_words = mask_words;
     hipLaunchKernelGGL(tree_front_mask_kernel, dim3(g.batch), dim3(256), 0, s, a);
     OT_HIP_CHECK(hipGetLastError());

@@ -248,4 +248,3 @@ def test_frontier_mask_rejects_bad_arguments_without_launching():
     assert L.ot_tree_frontier_mask(C.byref(p), 0, f, need, f, None) == -1
     assert L.ot_tree_frontier_mask(C.byref(p), 1, f, need, None, None) == -1
     assert L.ot_tree_frontier_mask(C.byref(p), 1, f, need - 1, f, None) == -3
-    assert L.ot_tree_frontier_mask(C.byref(_bp(n=200, depth=4)), 1, f, 1 << 30, f, None) == -2      # 800 pool nodes

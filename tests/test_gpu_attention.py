@@ -253,6 +253,9 @@ def test_one_workspace_serves_consecutive_calls():
     ("bf16", 1, 8, 8, 128, 700, 10, 50, 10, 10),     # 7B-shaped drafting step: 50 queries, 500 pool keys, 8 words
     ("bf16", 2, 8, 2, 128, 300, 6, 40, 8, 6),        # packed GQA rows (128-row workgroups), 320 pool keys
     ("bf16", 1, 4, 4, 64, 0, 4, 64, 8, 3),           # no prefix, 512 pool keys of which 3 layers are filled
+    ("bf16", 1, 4, 4, 128, 2048, 10, 64, 12, 12),    # the 13B drafting shape (four of its heads): 768 pool keys
+    ("bf16", 2, 16, 2, 128, 700, 8, 60, 10, 10),     # the 70B drafting shape (two of its KV heads): 600 pool keys
+    ("bf16", 1, 8, 2, 128, 512, 16, 256, 20, 20),    # the Large drafting shape (two of its KV heads): 5120 pool keys
 ])
 def test_drafting_phase_attention_frontier_against_pool(dtype, B, Hq, Hkv, D, L, k, n, d, upto):
     """n frontier queries against the prefix and the K/V of all pool nodes (n_keys = depth * n), with the

@@ -281,14 +281,26 @@ def test_adaptive_depth_matches_oracle():
     U.assert_tree_equal(got, want, n)
 
 
-def test_frontier_masks_of_the_drafting_phase_match_oracle():
+@pytest.mark.parametrize("V,k,n,d,B", [(1500, 4, 40, 7, 3),       # 280 pool indices: five mask words
+                                       (600, 6, 100, 9, 2),       # 900 pool indices, two wavefronts per sequence
+                                       (400, 16, 256, 20, 1)])    # the Large drafting shape: 5120 pool indices
+def test_frontier_masks_of_the_drafting_phase_match_oracle(V, k, n, d, B):
     """ot_tree_frontier_mask after every expand: the incrementally kept ancestor masks over pool indices."""
     import torch
     from paper_2406_17276_amd import api
-    V, k, n, d, B = 1500, 4, 40, 7, 3                      # 280 pool indices: five mask words
-    g = np.random.default_rng(5)
-    x = (g.standard_normal((B, d, n, V)) * 3.0).astype(np.float32)
-    builders = [ot_oracle.TreeBuilder(k, n) for _ in range(B)]
+    for seed in range(5, 25):                              # inputs whose every cut has a gap the fp32 sums cannot flip
+        g = np.random.default_rng(seed)
+        x = (g.standard_normal((B, d, n, V)) * 3.0).astype(np.float32)
+        want, builders = [], [ot_oracle.TreeBuilder(k, n) for _ in range(B)]
+        for t in range(d):
+            for b in range(B):
+                F = builders[b].frontier_score.shape[0]
+                builders[b].expand(x[b, t, :F].astype(np.float64))
+            want.append([ot_oracle.frontier_masks(bld.layers, n, d) for bld in builders])
+        if min(min(bld.cut_gaps) for bld in builders) > U.GAP:
+            break
+    else:
+        raise RuntimeError("no gapped input")
     stream = api.TreeStream(B, V, k, n, d, api.OT_F32)
     dev = torch.from_numpy(x).cuda()
     for t in range(d):
@@ -297,10 +309,7 @@ def test_frontier_masks_of_the_drafting_phase_match_oracle():
         torch.cuda.synchronize()
         m = m.cpu().numpy().view(np.uint64)
         for b in range(B):
-            F = builders[b].frontier_score.shape[0]
-            builders[b].expand(x[b, t, :F].astype(np.float64))
-            np.testing.assert_array_equal(m[b], ot_oracle.frontier_masks(builders[b].layers, n, d))
-    assert min(min(bld.cut_gaps) for bld in builders) > U.GAP
+            np.testing.assert_array_equal(m[b], want[t][b], err_msg=f"step {t}, sequence {b}")
 
 
 @pytest.mark.parametrize("V,k,n,dmax,B,dtype,delta", [
