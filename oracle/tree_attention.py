@@ -60,3 +60,18 @@ def tree_verify_attention(Q, K_prefix, V_prefix, K_tree, V_tree, prefix_len, mas
                 w = np.where(visible, w, 0.0)
                 O[b, h, i] = (w / w.sum()) @ V
     return O
+
+
+def tree_verify_attention_fp8kv(Q, K8_prefix, V8_prefix, K8_tree, V8_tree, k_scale, v_scale, prefix_len, mask,
+                                decode, scale=None):
+    """The same attention over a K/V cache kept in 8 bits.  The paper states no precision for the cache; the reading
+    built here: K and V (prefix and tree rows alike) are stored as FP8 E4M3 bytes with one real scale factor per
+    (sequence, KV head) for K and one for V, the value a byte stands for being  scale * decode(byte);  Q and O keep
+    their 16-bit type.  What is computed is the attention of the function above on exactly those values -- the
+    rounding happened when the cache was written and is not part of this step.
+    K8_* / V8_* uint8 [B,Hkv,rows,D]; k_scale, v_scale [B,Hkv]; decode: bytes -> real values (exact widening)."""
+    ks = np.asarray(k_scale, dtype=np.float64)[:, :, None, None]
+    vs = np.asarray(v_scale, dtype=np.float64)[:, :, None, None]
+    wide = lambda a: np.asarray(decode(a), dtype=np.float64)
+    return tree_verify_attention(Q, ks * wide(K8_prefix), vs * wide(V8_prefix), ks * wide(K8_tree), vs * wide(V8_tree),
+                                 prefix_len, mask, scale)

@@ -126,3 +126,70 @@ def test_empty_prefix_and_wide_mask_words():
     roots = [i for i in range(n) if parents[0][i] < 0]
     for i in roots:                    # a root child with no prefix sees only itself
         np.testing.assert_allclose(O[0, 0, i], x["V_tree"][0, 0, i], rtol=1e-13)
+
+
+# ---------------------------------------------------------------------------
+# 8-bit K/V cache: the format's plumbing (workloads.py) and the oracle's reading
+# ---------------------------------------------------------------------------
+def test_e4m3_decode_against_the_format_definition():
+    """Values written out from the format's definition: bias 7, three mantissa bits, subnormals m * 2^-9, no
+    infinities, one NaN code per sign, largest finite value 448."""
+    dec = wl.e4m3_bits_to_f32
+    hand = {0x00: 0.0, 0x01: 2.0 ** -9, 0x07: 7 * 2.0 ** -9, 0x08: 2.0 ** -6, 0x38: 1.0, 0x39: 1.125, 0x3C: 1.5,
+            0x40: 2.0, 0x7E: 448.0, 0x77: 240.0, 0xB8: -1.0, 0xFE: -448.0, 0x81: -2.0 ** -9}
+    for code, val in hand.items():
+        assert float(dec(np.array([code], dtype=np.uint8))[0]) == val, hex(code)
+    allv = dec(np.arange(256, dtype=np.uint8))
+    assert np.isnan(allv[0x7F]) and np.isnan(allv[0xFF]) and np.isfinite(np.delete(allv, [0x7F, 0xFF])).all()
+    assert np.all(np.diff(allv[:0x7F]) > 0)                              # codes 0..0x7e increase strictly
+    assert np.array_equal(allv[0x80:0xFF], -allv[:0x7F])                # the sign bit mirrors
+    assert np.signbit(allv[0x80]) and allv[0x80] == 0.0                 # minus zero
+    assert np.array_equal(allv[:0x7F].astype(np.float32).view(np.uint32) & 0xFFFF, np.zeros(0x7F, dtype=np.uint32))   # every value is a bf16 value
+
+
+def test_e4m3_rounding_is_to_nearest_even_and_saturates():
+    enc, dec = wl.f32_to_e4m3_bits, wl.e4m3_bits_to_f32
+    codes = np.arange(256, dtype=np.uint8)
+    finite = np.delete(codes, [0x7F, 0xFF])
+    assert np.array_equal(enc(dec(finite)), finite)                     # every code is a fixed point
+    # halfway between neighbours goes to the even code; just off halfway goes to the nearer one
+    t = dec(np.arange(0x7F, dtype=np.uint8)).astype(np.float64)
+    for i in range(0x7E):
+        mid = np.float32((t[i] + t[i + 1]) / 2)
+        if float(mid) == (t[i] + t[i + 1]) / 2:
+            assert int(enc(np.array([mid]))[0]) == (i if i % 2 == 0 else i + 1)
+        assert int(enc(np.array([np.float32(t[i] + 0.26 * (t[i + 1] - t[i]))]))[0]) == i
+        assert int(enc(np.array([np.float32(t[i] + 0.74 * (t[i + 1] - t[i]))]))[0]) == i + 1
+    assert int(enc(np.array([1e6], dtype=np.float32))[0]) == 0x7E and int(enc(np.array([-1e6], dtype=np.float32))[0]) == 0xFE
+    assert int(enc(np.array([0.0], dtype=np.float32))[0]) == 0 and int(enc(np.array([-0.0], dtype=np.float32))[0]) == 0x80
+    g = np.random.default_rng(3)
+    x = (g.standard_normal(20000) * 3).astype(np.float32)
+    err = np.abs(dec(enc(x)).astype(np.float64) - x)
+    table = np.abs(dec(finite).astype(np.float64))
+    nearest = np.abs(np.abs(x.astype(np.float64))[:, None] - table[None, :]).min(axis=1)
+    np.testing.assert_allclose(err, nearest, rtol=0, atol=0)            # brute force: no code is nearer
+
+
+def test_fp8_cache_attention_is_the_plain_attention_of_the_dequantised_cache():
+    """Scales of one make it the plain oracle on the decoded bytes; scaling K by s is scaling the softmax scale by s;
+    scaling V by s scales O by s (the two places a scale factor can act)."""
+    B, Hq, Hkv, n, D, L = 2, 4, 2, 6, 16, 9
+    g = np.random.default_rng(5)
+    x = _inputs(B, Hq, Hkv, n, D, L, 7, lens=[9, 4])
+    _, mask = _masks(B, n, 3)
+    q8 = lambda a: wl.f32_to_e4m3_bits(a.astype(np.float32))
+    K8p, V8p, K8t, V8t = q8(x["K_prefix"]), q8(x["V_prefix"]), q8(x["K_tree"]), q8(x["V_tree"])
+    one = np.ones((B, Hkv))
+    base = ta.tree_verify_attention_fp8kv(x["Q"], K8p, V8p, K8t, V8t, one, one, x["prefix_len"], mask, wl.e4m3_bits_to_f32)
+    d = lambda a: wl.e4m3_bits_to_f32(a).astype(np.float64)
+    plain = ta.tree_verify_attention(x["Q"], d(K8p), d(V8p), d(K8t), d(V8t), x["prefix_len"], mask)
+    np.testing.assert_array_equal(base, plain)
+    ks, vs = g.uniform(0.5, 2.0, (B, Hkv)), g.uniform(0.5, 2.0, (B, Hkv))
+    got = ta.tree_verify_attention_fp8kv(x["Q"], K8p, V8p, K8t, V8t, ks, vs, x["prefix_len"], mask, wl.e4m3_bits_to_f32)
+    for b in range(B):
+        for hk in range(Hkv):
+            hs = slice(hk * (Hq // Hkv), (hk + 1) * (Hq // Hkv))
+            sub = ta.tree_verify_attention(x["Q"][b:b + 1, hs], d(K8p)[b:b + 1, hk:hk + 1], d(V8p)[b:b + 1, hk:hk + 1],
+                                           d(K8t)[b:b + 1, hk:hk + 1], d(V8t)[b:b + 1, hk:hk + 1], x["prefix_len"][b:b + 1],
+                                           mask[b:b + 1], scale=ks[b, hk] / np.sqrt(D))
+            np.testing.assert_allclose(got[b:b + 1, hs], vs[b, hk] * sub, rtol=1e-12, atol=1e-14)

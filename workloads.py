@@ -35,17 +35,46 @@ def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
     return (np.asarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
 
 
+def e4m3_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    """Exact widening of FP8 E4M3 bytes (the OCP 8-bit format: 1 sign, 4 exponent bits with bias 7, 3 mantissa bits,
+    no infinities, S.1111.111 = NaN, largest finite value 448) to float32."""
+    b = np.asarray(b, dtype=np.uint8).astype(np.int32)
+    sign = np.where(b & 0x80, -1.0, 1.0)
+    e, m = (b >> 3) & 15, b & 7
+    mag = np.where(e == 0, m * 2.0 ** -9, (1.0 + m / 8.0) * np.exp2((e - 7).astype(np.float64)))
+    mag = np.where((e == 15) & (m == 7), np.nan, mag)
+    return (sign * mag).astype(np.float32)
+
+
+def f32_to_e4m3_bits(x: np.ndarray) -> np.ndarray:
+    """Round float32 to FP8 E4M3 (nearest, ties to even; magnitudes beyond 448 saturate to 448): the byte whose
+    decoded value is nearest, found by search in the sorted table of the 127 non-negative finite codes."""
+    x = np.asarray(x, dtype=np.float32).astype(np.float64)
+    table = e4m3_bits_to_f32(np.arange(0x7F, dtype=np.uint8)).astype(np.float64)      # codes 0..0x7e, increasing
+    a = np.minimum(np.abs(x), 448.0)
+    hi = np.clip(np.searchsorted(table, a, side="left"), 1, 0x7E)
+    lo = hi - 1
+    dlo, dhi = a - table[lo], table[hi] - a
+    pick_hi = (dhi < dlo) | ((dhi == dlo) & (hi % 2 == 0))                             # tie: the even code
+    code = np.where(pick_hi, hi, lo).astype(np.uint8)
+    return np.where(np.signbit(x), code | 0x80, code).astype(np.uint8)
+
+
 def to_f64(a: np.ndarray, dtype: str) -> np.ndarray:
-    """Exact float64 view of a stored tensor ('f32' array or 'bf16' bit patterns)."""
+    """Exact float64 view of a stored tensor ('f32' array, 'bf16' bit patterns or 'e4m3' bytes)."""
     if dtype == "bf16":
         return bf16_bits_to_f32(a).astype(np.float64)
+    if dtype == "e4m3":
+        return e4m3_bits_to_f32(a).astype(np.float64)
     return np.asarray(a, dtype=np.float32).astype(np.float64)
 
 
 def store(x32: np.ndarray, dtype: str) -> np.ndarray:
-    """Round a float32 array to the stored dtype (bf16 -> uint16 bits)."""
+    """Round a float32 array to the stored dtype (bf16 -> uint16 bits, e4m3 -> bytes)."""
     if dtype == "bf16":
         return f32_to_bf16_bits(x32)
+    if dtype == "e4m3":
+        return f32_to_e4m3_bits(x32)
     return np.ascontiguousarray(x32, dtype=np.float32)
 
 
