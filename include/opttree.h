@@ -232,6 +232,21 @@ OT_API int ot_tree_verify_attention(const ot_attn_params* p,
                              void* O,                                /* [batch][q_heads][n][head_dim] */
                              void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* The same attention over a K/V cache kept in 8 bits.  The paper states no precision for the cache; the reading built
+ * here: K_prefix, V_prefix, K_tree and V_tree hold FP8 E4M3 bytes (the OCP 8-bit format: 4 exponent bits with bias 7,
+ * 3 mantissa bits, no infinities, largest value 448), and a byte of sequence b, KV head h stands for
+ * k_scale[b][h] * decode(byte) (K) or v_scale[b][h] * decode(byte) (V); k_scale, v_scale: device float
+ * [batch][kv_heads], positive and finite.  Q and O are bf16 (p->dtype must be OT_BF16).  The K/V strides of `p` count
+ * elements = bytes and must be multiples of 16.  What is computed is the attention defined above on exactly those
+ * values (each byte is widened without error; the factors join the softmax scale and the final normalisation);
+ * quantising the cache is the caller's step.  Workspace and all other arguments as for ot_tree_verify_attention. */
+OT_API int ot_tree_verify_attention_fp8kv(const ot_attn_params* p,
+                             const void* Q, const void* K_prefix, const void* V_prefix,
+                             const void* K_tree, const void* V_tree,
+                             const float* k_scale, const float* v_scale,
+                             const int32_t* prefix_len, const uint64_t* mask,
+                             void* O, void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* ot_tree_verify_attention for callers that cannot allocate device memory or keep a workspace (code under HIP
  * graph capture, tight serving loops, harnesses that forbid hipMalloc): the same kernels, with the workspace in
  * a library-owned device array of OT_ATTN_SCRATCH_BYTES that every GPU the library runs on holds until the

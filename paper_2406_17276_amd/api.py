@@ -115,6 +115,8 @@ def lib():
         L.ot_tree_verify_attention.argtypes = [C.POINTER(AttnParams)] + [C.c_void_p] * 9 + [C.c_size_t, C.c_void_p]
         L.ot_tree_verify_attention_noalloc.restype = C.c_int
         L.ot_tree_verify_attention_noalloc.argtypes = [C.POINTER(AttnParams)] + [C.c_void_p] * 9
+        L.ot_tree_verify_attention_fp8kv.restype = C.c_int
+        L.ot_tree_verify_attention_fp8kv.argtypes = [C.POINTER(AttnParams)] + [C.c_void_p] * 11 + [C.c_size_t, C.c_void_p]
         L.ot_tree_verify_attention_timed.restype = C.c_int
         L.ot_tree_verify_attention_timed.argtypes = ([C.POINTER(AttnParams)] + [C.c_void_p] * 9 +
                                                      [C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p])
@@ -366,6 +368,31 @@ def tree_verify_attention_noalloc(Q, K_prefix, V_prefix, K_tree, V_tree, prefix_
     _check(lib().ot_tree_verify_attention_noalloc(
         C.byref(p), ptr(Q), ptr(K_prefix), ptr(V_prefix), ptr(K_tree), ptr(V_tree), ptr(prefix_len), ptr(mask),
         ptr(out), _stream()), "ot_tree_verify_attention_noalloc")
+    return out
+
+
+def tree_verify_attention_fp8kv(Q, K_prefix, V_prefix, K_tree, V_tree, k_scale, v_scale, prefix_len, mask, out=None,
+                                workspace=None, softmax_scale: float = 0.0):
+    """ot_tree_verify_attention_fp8kv on the current stream.  Q bf16 [B,Hq,n,D]; K/V uint8 tensors of FP8 E4M3 bytes
+    [B,Hkv,rows,D]; k_scale, v_scale float32 [B,Hkv]."""
+    import torch
+    for t in (K_prefix, V_prefix, K_tree, V_tree):
+        if t is not None and t.dtype != torch.uint8:
+            raise TypeError("the 8-bit cache is passed as uint8 tensors")
+    for t in (k_scale, v_scale):
+        if t.dtype != torch.float32 or not t.is_contiguous() or tuple(t.shape) != (Q.shape[0], K_tree.shape[1]):
+            raise ValueError("scales must be contiguous float32 [B, Hkv]")
+    p = attn_params(Q, K_prefix, V_prefix, K_tree, V_tree, softmax_scale=softmax_scale)
+    if out is None:
+        out = torch.empty_like(Q)
+    p.o_strides = (C.c_int64 * 3)(out.stride(0), out.stride(1), out.stride(2))
+    if workspace is None:
+        workspace = attn_workspace(p, Q.device)
+    ptr = lambda t: None if t is None else t.data_ptr()
+    _check(lib().ot_tree_verify_attention_fp8kv(
+        C.byref(p), ptr(Q), ptr(K_prefix), ptr(V_prefix), ptr(K_tree), ptr(V_tree), ptr(k_scale), ptr(v_scale),
+        ptr(prefix_len), ptr(mask), ptr(out), ptr(workspace), workspace.numel(), _stream()),
+        "ot_tree_verify_attention_fp8kv")
     return out
 
 

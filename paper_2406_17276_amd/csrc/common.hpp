@@ -99,10 +99,11 @@ struct AttnPlan {
     int splits;          // KV splits per (b, kv head, row block)
     size_t part_o_bytes, part_ml_bytes, bytes;
 };
-AttnPlan plan_attention(const ot_attn_params& p);
+AttnPlan plan_attention(const ot_attn_params& p, bool kv8 = false);
 int launch_tree_attention(const ot_attn_params& p, const AttnPlan& plan, const void* Q, const void* Kp, const void* Vp,
                           const void* Kt, const void* Vt, const int32_t* prefix_len, const uint64_t* mask, void* O,
-                          void* workspace, hipStream_t s, hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr);
+                          void* workspace, hipStream_t s, hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr,
+                          const float* k_scale = nullptr, const float* v_scale = nullptr);
 
 }  // namespace ot
 

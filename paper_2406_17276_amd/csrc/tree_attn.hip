@@ -66,6 +66,7 @@ struct AttnKArgs {
     int batch, q_heads, kv_heads, g, n, nk, D, max_prefix, splits, W, dtype, row_blocks;   // n query rows, nk tree keys
     unsigned int inv_splits, inv_kv_heads, inv_n;   // division by multiplication (fast_div): ceil(2^32 / d), unused for d = 1
     float scale_log2;   // softmax scale * log2(e)
+    const float *k_scale, *v_scale;   // 8-bit K/V cache: one factor per (sequence, KV head) each; null otherwise
     long long qs[3], kps[3], vps[3], kts[3], vts[3], os[3];
 };
 
@@ -141,7 +142,11 @@ __device__ __forceinline__ void split_range(int T, int S, unsigned int inv_S, in
 #ifndef OT_ATTN_PART_BF16
 #define OT_ATTN_PART_BF16 1
 #endif
-template <int D, int VAR>
+// KV8: K and V arrive as FP8 E4M3 bytes with a scale factor per (sequence, KV head) each.  A tile is copied into LDS
+// as it is (half the bytes), then every thread widens its sixteen-byte pieces to bf16 in place -- every E4M3 value
+// is a bf16 value -- into the layout the operand reads expect (two more barriers per tile); the K factor joins the
+// softmax scale, the V factor the final normalisation.  Everything else is the bf16 kernel.
+template <int D, int VAR, bool KV8>
 __global__ __launch_bounds__(VAR == 2 ? 512 : 256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_mfma_kernel(
     // what the first loads need, as leading scalar arguments: the hardware hands these over in registers at
     // wavefront start (kernel-argument preload); they repeat fields of `a`
@@ -156,7 +161,10 @@ __global__ __launch_bounds__(VAR == 2 ? 512 : 256) __attribute__((amdgpu_waves_p
     constexpr int SPR = D / 16;            // 32-byte segments per row
     constexpr int SLABS = D / 16;          // 16-wide d slabs of the QK^T contraction
     constexpr int DB = D / 32;             // 32-wide d blocks of O^T
-    constexpr int CH = TK * D / 8 / NT;    // 16-byte chunks per thread per tile (K or V)
+    constexpr int ESZ = KV8 ? 1 : 2;       // bytes per stored K/V element
+    constexpr int CPRG = D * ESZ / 16;     // 16-byte chunks per row in global memory
+    constexpr int CH = TK * CPRG / NT;     // 16-byte chunks per thread per tile (K or V)
+    static_assert(CH >= 1, "a tile has at least one chunk per thread");
     constexpr int LPT = 2 * CH;            // asynchronous loads per thread per tile
     constexpr int NKB = WIDE ? 2 : 1;      // 32-key blocks per wavefront per tile
     constexpr int ROWS = VAR == 2 ? 256 : (WIDE ? 128 : 64);   // packed query rows per workgroup
@@ -211,10 +219,10 @@ __global__ __launch_bounds__(VAR == 2 ? 512 : 256) __attribute__((amdgpu_waves_p
     const uint64_t* const mask_row = a_mask + ((long long)b * n + node) * a_W;
     unsigned int* const s_mw = s_buf + NBUF * BUF;                      // [NBUF][waves][2][64]
 
-    const unsigned short* kp = (const unsigned short*)a.Kp + (long long)b * a.kps[0] + (long long)hk * a.kps[1];
-    const unsigned short* vp = (const unsigned short*)a.Vp + (long long)b * a.vps[0] + (long long)hk * a.vps[1];
-    const unsigned short* kt = (const unsigned short*)a.Kt + (long long)b * a.kts[0] + (long long)hk * a.kts[1];
-    const unsigned short* vt = (const unsigned short*)a.Vt + (long long)b * a.vts[0] + (long long)hk * a.vts[1];
+    const unsigned char* kp = (const unsigned char*)a.Kp + ((long long)b * a.kps[0] + (long long)hk * a.kps[1]) * ESZ;
+    const unsigned char* vp = (const unsigned char*)a.Vp + ((long long)b * a.vps[0] + (long long)hk * a.vps[1]) * ESZ;
+    const unsigned char* kt = (const unsigned char*)a.Kt + ((long long)b * a.kts[0] + (long long)hk * a.kts[1]) * ESZ;
+    const unsigned char* vt = (const unsigned char*)a.Vt + ((long long)b * a.vts[0] + (long long)hk * a.vts[1]) * ESZ;
 
     // transpose-load addressing: key row and first column this lane points at inside a 4-key x 32-column block
     const int tr_j = (lane & 15) >> 2, tr_q = 4 * (lane & 3);
@@ -222,7 +230,9 @@ __global__ __launch_bounds__(VAR == 2 ? 512 : 256) __attribute__((amdgpu_waves_p
     // V segment (2d + g1) of row 4h + tr_j (mod 8) -> position (2d) ^ vx
     const int kx = h ^ (l32 & (CPR - 1));
     const int vx = ((lane >> 4) & 1) ^ ((4 * h + tr_j) & (SPR - 1));
-    const float c = a.scale_log2;          // scores are kept raw; p = 2^(c s - c m)
+    // scores are kept raw; p = 2^(c s - c m).  An 8-bit cache's K factor scales every score: it joins c.
+    const float c = KV8 ? a.scale_log2 * a.k_scale[bz] : a.scale_log2;
+    const float v_factor = KV8 ? a.v_scale[bz] : 1.f;
     float m_run = -INFINITY, l_run = 0.f;
     f32x16 oacc[DB];
 #pragma unroll
@@ -233,10 +243,11 @@ __global__ __launch_bounds__(VAR == 2 ? 512 : 256) __attribute__((amdgpu_waves_p
     // LDS slot sigma = cc * NT + tid (16 bytes each) holds key row sigma / CPR, chunk position sigma % CPR;
     // the chunk stored there is the one the swizzle maps to that position.  KSTEP rows separate cc and cc+1,
     // a multiple of 16, so the swizzle term is the same for every cc.
-    constexpr int KSTEP = NT / CPR;
-    const int kkey0 = tid / CPR, pc = tid % CPR;
-    const int kcol = (pc ^ (kkey0 & (CPR - 1))) * 8;                                         // K: chunk c = pc ^ (r % 16)
-    const int vcol = (2 * ((pc >> 1) ^ (kkey0 & (SPR - 1))) + (pc & 1)) * 8;                 // V: segment g = (pc/2) ^ (r % 8)
+    // (KV8: the copy is not swizzled -- slot sigma holds chunk sigma % CPRG of row sigma / CPRG -- the widening is.)
+    constexpr int KSTEP = NT / CPRG;
+    const int kkey0 = tid / CPRG, pc = tid % CPRG;
+    const int kcol = KV8 ? pc * 16 : (pc ^ (kkey0 & (CPR - 1))) * 16;                        // byte column; K: chunk c = pc ^ (r % 16)
+    const int vcol = KV8 ? pc * 16 : (2 * ((pc >> 1) ^ (kkey0 & (SPR - 1))) + (pc & 1)) * 16;  // V: segment g = (pc/2) ^ (r % 8)
     const int wave_u = wave;
     // Request tile t: global memory -> LDS buffer `buf`, 16 bytes per lane and instruction, no registers in
     // between.  Full tiles address memory as (uniform base of the tile's rows) + (this lane's fixed 32-bit
@@ -246,8 +257,8 @@ __global__ __launch_bounds__(VAR == 2 ? 512 : 256) __attribute__((amdgpu_waves_p
     // finite.  Written as assembly on purpose: the compiler does not track these loads, so it puts no wait
     // between them and the LDS reads of the tile being computed; completion is awaited explicitly, per tile,
     // with s_waitcnt vmcnt (loads complete in order) ahead of the barrier that publishes the buffer.
-    const unsigned kofs_p = (unsigned)(kkey0 * (int)a.kps[2] + kcol) * 2u, vofs_p = (unsigned)(kkey0 * (int)a.vps[2] + vcol) * 2u;
-    const unsigned kofs_t = (unsigned)(kkey0 * (int)a.kts[2] + kcol) * 2u, vofs_t = (unsigned)(kkey0 * (int)a.vts[2] + vcol) * 2u;
+    const unsigned kofs_p = (unsigned)(kkey0 * (int)a.kps[2] * ESZ + kcol), vofs_p = (unsigned)(kkey0 * (int)a.vps[2] * ESZ + vcol);
+    const unsigned kofs_t = (unsigned)(kkey0 * (int)a.kts[2] * ESZ + kcol), vofs_t = (unsigned)(kkey0 * (int)a.vts[2] * ESZ + vcol);
     const int L = clamp_len(L_raw, a_max_prefix);
     const int ptiles = (L + TK - 1) / TK, ttiles = (a_nk + TK - 1) / TK;
     int t0, t1;
@@ -265,16 +276,16 @@ __global__ __launch_bounds__(VAR == 2 ? 512 : 256) __attribute__((amdgpu_waves_p
         }
         const int key0 = tree ? (t - ptiles) * TK : t * TK;
         const int last = (tree ? a_nk : L) - 1;
-        const long long ks = tree ? a.kts[2] : a.kps[2];
-        const long long vs = tree ? a.vts[2] : a.vps[2];
-        const unsigned short* kbase = tree ? kt : kp;
-        const unsigned short* vbase = tree ? vt : vp;
+        const long long ks = (tree ? a.kts[2] : a.kps[2]) * ESZ;      // row strides in bytes
+        const long long vs = (tree ? a.vts[2] : a.vps[2]) * ESZ;
+        const unsigned char* kbase = tree ? kt : kp;
+        const unsigned char* vbase = tree ? vt : vp;
         unsigned int* const lk = s_buf + buf * BUF;
         unsigned int* const lv = lk + TK * D / 2;
         if (key0 + TK - 1 <= last) {
             const unsigned kofs = tree ? kofs_t : kofs_p, vofs = tree ? vofs_t : vofs_p;
-            const unsigned short* gk = kbase + (long long)key0 * ks;      // uniform: rows key0 + cc KSTEP of the tile
-            const unsigned short* gv = vbase + (long long)key0 * vs;
+            const unsigned char* gk = kbase + (long long)key0 * ks;       // uniform: rows key0 + cc KSTEP of the tile
+            const unsigned char* gv = vbase + (long long)key0 * vs;
             unsigned lds_k = (unsigned)(size_t)(__attribute__((address_space(3))) void*)(lk + wave_u * 256);
             unsigned lds_v = (unsigned)(size_t)(__attribute__((address_space(3))) void*)(lv + wave_u * 256);
 #pragma unroll
@@ -292,14 +303,55 @@ __global__ __launch_bounds__(VAR == 2 ? 512 : 256) __attribute__((amdgpu_waves_p
                 const unsigned lds_v = (unsigned)(size_t)(__attribute__((address_space(3))) void*)(lv + slot0 * 4);
                 int row = key0 + kkey0 + cc * KSTEP;
                 row = row < last ? row : last;
-                const unsigned short* gk = kbase + row * ks + kcol;
-                const unsigned short* gv = vbase + row * vs + vcol;
+                const unsigned char* gk = kbase + row * ks + kcol;
+                const unsigned char* gv = vbase + row * vs + vcol;
                 asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_k), "v"(gk) : "m0", "memory");
                 asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_v), "v"(gv) : "m0", "memory");
             }
         }
     };
 
+    // KV8: widen the tile that has just landed in buffer `buf`, in place.  Every thread reads the sixteen-byte pieces
+    // it owns (sixteen values each), the workgroup meets (the bf16 tile overwrites the bytes), the pieces are written
+    // as bf16 where the operand reads expect them (K: 16-byte chunk c of row r at position c ^ (r mod 16); V: 32-byte
+    // segment g at g ^ (r mod 8)), and the workgroup meets again.
+    auto widen_tile = [&](int buf) {
+        unsigned char* const rk = (unsigned char*)(s_buf + buf * BUF);
+        unsigned char* const rv = rk + TK * D * 2;
+        u32x4 wk[CH], wv[CH];
+#pragma unroll
+        for (int cc = 0; cc < CH; ++cc) {
+            wk[cc] = *(const u32x4*)(rk + (cc * NT + tid) * 16);
+            wv[cc] = *(const u32x4*)(rv + (cc * NT + tid) * 16);
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        auto widen = [](const u32x4& w, u32x4& lo, u32x4& hi) {
+            unsigned int o[8];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const auto p01 = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[i], false);     // bytes 0, 1 of the word
+                const auto p23 = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[i], true);      // bytes 2, 3
+                o[2 * i] = (__float_as_uint(p01[0]) >> 16) | (__float_as_uint(p01[1]) & 0xffff0000u);
+                o[2 * i + 1] = (__float_as_uint(p23[0]) >> 16) | (__float_as_uint(p23[1]) & 0xffff0000u);
+            }
+            lo = u32x4{o[0], o[1], o[2], o[3]};
+            hi = u32x4{o[4], o[5], o[6], o[7]};
+        };
+#pragma unroll
+        for (int cc = 0; cc < CH; ++cc) {
+            const int sigma = cc * NT + tid, row = sigma / CPRG, c16 = sigma % CPRG;
+            u32x4 lo, hi;
+            widen(wk[cc], lo, hi);
+            unsigned short* const krow = (unsigned short*)rk + row * D;
+            *(u32x4*)(krow + (((2 * c16) ^ (row & (CPR - 1))) << 3)) = lo;
+            *(u32x4*)(krow + (((2 * c16 + 1) ^ (row & (CPR - 1))) << 3)) = hi;
+            widen(wv[cc], lo, hi);
+            unsigned short* const vseg = (unsigned short*)rv + row * D + ((c16 ^ (row & (SPR - 1))) << 4);
+            *(u32x4*)vseg = lo;
+            *(u32x4*)(vseg + 8) = hi;
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    };
     // The first PD tiles are requested at once.  A split with fewer tiles issues the same number of loads all the
     // same (one word each, into the unused buffer's mask-word slots: a load without a destination register): the
     // wait for Q below can then name a fixed count of younger requests.
@@ -334,6 +386,7 @@ __global__ __launch_bounds__(VAR == 2 ? 512 : 256) __attribute__((amdgpu_waves_p
         else if (ahead == 1) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(LPT) : "memory");
         else                 asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(2 * LPT) : "memory");
         if (t + PD < t1) request_tile(t + PD, std::integral_constant<int, PREV>{});
+        if constexpr (KV8) widen_tile(CUR);
 
         const unsigned short* const s_k = (const unsigned short*)(s_buf + CUR * BUF);
         const unsigned short* const s_v = s_k + TK * D;
@@ -435,6 +488,7 @@ __global__ __launch_bounds__(VAR == 2 ? 512 : 256) __attribute__((amdgpu_waves_p
             else if (ahead == 1) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(LPT) : "memory");
             else                 asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(2 * LPT) : "memory");
             if (t + PD < t1) request_tile(t + PD, (t + PD - t0) & (NBUF - 1));
+            if constexpr (KV8) widen_tile((t - t0) & (NBUF - 1));
         };
         const int t_full = min(t1, L / TK);                      // tiles below t_full are full prefix tiles
         auto kfrag = [&](const unsigned short* s_k, int kb, int s) {
@@ -639,7 +693,7 @@ __global__ __launch_bounds__(VAR == 2 ? 512 : 256) __attribute__((amdgpu_waves_p
 
     if (a_splits == 1) {
         if (holder && row_ok) {
-            const float inv = l_run > 0.f ? 1.f / l_run : 0.f;
+            const float inv = l_run > 0.f ? v_factor / l_run : 0.f;
             unsigned short* orow =
                 (unsigned short*)a.O + (long long)b * a.os[0] + (long long)hq * a.os[1] + (long long)node * a.os[2];
 #pragma unroll
@@ -780,7 +834,7 @@ __global__ __launch_bounds__(VAR == 2 ? 512 : 256) __attribute__((amdgpu_waves_p
     {
         const int head2 = fast_div(rho2, n, a_inv_n);
         const int hq2 = hk * a_g + head2, node2 = rho2 - head2 * n;
-        const float inv = Ls > 0.f ? 1.f / Ls : 0.f;
+        const float inv = Ls > 0.f ? v_factor / Ls : 0.f;
         unsigned short* orow =
             (unsigned short*)a.O + (long long)b * a.os[0] + (long long)hq2 * a.os[1] + (long long)node2 * a.os[2];
 #pragma unroll
@@ -1002,13 +1056,14 @@ static int attn_rows_per_workgroup(int rows_per_kv_head) {
     return rows_per_kv_head <= 64 ? 64 : (rows_per_kv_head >= OT_ATTN_ROWS256_FROM ? 256 : 128);
 }
 
-AttnPlan plan_attention(const ot_attn_params& p) {
+AttnPlan plan_attention(const ot_attn_params& p, bool kv8) {
     AttnPlan pl;
     const int g = p.q_heads / p.kv_heads;
     int base, tile, rows_wg = 0, splits;
     if (p.dtype == OT_BF16) {
         const bool wide = g * p.n > 64;                    // wide variants when one KV head has more than 64 rows
         rows_wg = attn_rows_per_workgroup(g * p.n);
+        if (kv8 && rows_wg == 256) rows_wg = 128;
         pl.row_blocks = (g * p.n + rows_wg - 1) / rows_wg;
         base = p.batch * p.kv_heads * pl.row_blocks;
         tile = 64;
@@ -1046,10 +1101,13 @@ AttnPlan plan_attention(const ot_attn_params& p) {
 
 int launch_tree_attention(const ot_attn_params& p, const AttnPlan& plan, const void* Q, const void* Kp, const void* Vp,
                           const void* Kt, const void* Vt, const int32_t* prefix_len, const uint64_t* mask, void* O,
-                          void* workspace, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1) {
+                          void* workspace, hipStream_t s, hipEvent_t ev0, hipEvent_t ev1, const float* k_scale,
+                          const float* v_scale) {
+    const bool kv8 = k_scale != nullptr;
     AttnKArgs a;
     a.Q = Q; a.Kp = Kp; a.Vp = Vp; a.Kt = Kt; a.Vt = Vt;
     a.prefix_len = prefix_len; a.mask = mask; a.O = O;
+    a.k_scale = k_scale; a.v_scale = v_scale;
     a.counters = (unsigned int*)workspace;
     a.part_o = (float*)((char*)workspace + OT_ATTN_SYNC_BYTES);
     a.part_ml = (float*)((char*)workspace + OT_ATTN_SYNC_BYTES + plan.part_o_bytes);
@@ -1066,7 +1124,8 @@ int launch_tree_attention(const ot_attn_params& p, const AttnPlan& plan, const v
     auto magic = [](int d) { return d <= 1 ? 0u : (unsigned int)((0x100000000ull + (unsigned)d - 1) / (unsigned)d); };
     a.inv_splits = magic(a.splits); a.inv_kv_heads = magic(a.kv_heads); a.inv_n = magic(a.n);
     if (p.dtype == OT_BF16) {
-        const int rows_wg = attn_rows_per_workgroup(a.g * p.n);
+        int rows_wg = attn_rows_per_workgroup(a.g * p.n);
+        if (kv8 && rows_wg == 256) rows_wg = 128;
         const long long units = (long long)p.batch * p.kv_heads * plan.splits;
         const long long unit_groups = (units + 7) / 8;
         if (unit_groups > 65535 || 8LL * plan.row_blocks > 0x7fffffffLL) return OT_ERR_UNSUPPORTED;   // cannot happen within the limits
@@ -1074,19 +1133,22 @@ int launch_tree_attention(const ot_attn_params& p, const AttnPlan& plan, const v
             return OT_ERR_UNSUPPORTED;      // cannot happen: splits > 1 only with few workgroups
         const dim3 grid((unsigned)(8 * plan.row_blocks), (unsigned)unit_groups);
 #define OT_ATTN_ARGS a.prefix_len, a.mask, a.Q, a.splits, a.inv_splits, a.kv_heads, a.inv_kv_heads, a.n, a.inv_n, a
-#define OT_ATTN_LAUNCH(DD, VV)                                                                             \
+#define OT_ATTN_LAUNCH(DD, VV, K8)                                                                         \
     do {                                                                                                   \
         const int nbuf = (VV) == 2 ? 4 : ((VV) == 1 ? 2 : OT_ATTN_NBUF_NARROW), nwaves = (VV) == 2 ? 8 : 4; \
         const size_t lds = (size_t)nbuf * (64 * DD + nwaves * 128) * sizeof(unsigned int);                 \
         if (lds > 64 * 1024)                                                                               \
-            OT_HIP_CHECK(hipFuncSetAttribute((const void*)attn_mfma_kernel<DD, VV>,                        \
+            OT_HIP_CHECK(hipFuncSetAttribute((const void*)attn_mfma_kernel<DD, VV, K8>,                    \
                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));       \
-        if (ev0 || ev1) hipExtLaunchKernelGGL((attn_mfma_kernel<DD, VV>), grid, dim3(64 * nwaves), lds, s, ev0, ev1, 0, OT_ATTN_ARGS); \
-        else hipLaunchKernelGGL((attn_mfma_kernel<DD, VV>), grid, dim3(64 * nwaves), lds, s, OT_ATTN_ARGS);  \
+        if (ev0 || ev1) hipExtLaunchKernelGGL((attn_mfma_kernel<DD, VV, K8>), grid, dim3(64 * nwaves), lds, s, ev0, ev1, 0, OT_ATTN_ARGS); \
+        else hipLaunchKernelGGL((attn_mfma_kernel<DD, VV, K8>), grid, dim3(64 * nwaves), lds, s, OT_ATTN_ARGS); \
     } while (0)
         const int var = rows_wg == 256 ? 2 : (rows_wg == 128 ? 1 : 0);
-        if (p.head_dim == 128) { if (var == 2) OT_ATTN_LAUNCH(128, 2); else if (var == 1) OT_ATTN_LAUNCH(128, 1); else OT_ATTN_LAUNCH(128, 0); }
-        else                   { if (var == 2) OT_ATTN_LAUNCH(64, 2); else if (var == 1) OT_ATTN_LAUNCH(64, 1); else OT_ATTN_LAUNCH(64, 0); }
+        if (kv8) {              // the 8-bit cache runs the 64- and 128-row variants
+            if (p.head_dim == 128) { if (var >= 1) OT_ATTN_LAUNCH(128, 1, true); else OT_ATTN_LAUNCH(128, 0, true); }
+            else                   { if (var >= 1) OT_ATTN_LAUNCH(64, 1, true); else OT_ATTN_LAUNCH(64, 0, true); }
+        } else if (p.head_dim == 128) { if (var == 2) OT_ATTN_LAUNCH(128, 2, false); else if (var == 1) OT_ATTN_LAUNCH(128, 1, false); else OT_ATTN_LAUNCH(128, 0, false); }
+        else                   { if (var == 2) OT_ATTN_LAUNCH(64, 2, false); else if (var == 1) OT_ATTN_LAUNCH(64, 1, false); else OT_ATTN_LAUNCH(64, 0, false); }
 #undef OT_ATTN_LAUNCH
 #undef OT_ATTN_ARGS
     } else {
@@ -1112,7 +1174,7 @@ int launch_tree_attention(const ot_attn_params& p, const AttnPlan& plan, const v
 
 using namespace ot;
 
-static int validate_attn(const ot_attn_params* p) {
+static int validate_attn(const ot_attn_params* p, bool kv8 = false) {
     if (!p) return OT_ERR_INVALID_ARG;
     if (p->batch < 1 || p->q_heads < 1 || p->kv_heads < 1 || p->n < 1 || p->max_prefix < 0) return OT_ERR_INVALID_ARG;
     if (p->q_heads % p->kv_heads) return OT_ERR_INVALID_ARG;
@@ -1124,9 +1186,10 @@ static int validate_attn(const ot_attn_params* p) {
     if (p->n_keys > (p->dtype == OT_BF16 ? OT_MAX_TREE_KEYS : OT_MAX_TREE_KEYS_F32)) return OT_ERR_UNSUPPORTED;
     if ((long long)p->batch * p->q_heads > 65535 || (long long)p->batch * p->q_heads * p->n > 0x7fffffffLL)
         return OT_ERR_UNSUPPORTED;
-    const int vec = p->dtype == OT_BF16 ? 8 : 4;
+    if (kv8 && p->dtype != OT_BF16) return OT_ERR_INVALID_ARG;      // Q and O of the 8-bit cache variant are bf16
     const int64_t* st[6] = {p->q_strides, p->kp_strides, p->vp_strides, p->kt_strides, p->vt_strides, p->o_strides};
     for (int t = 0; t < 6; ++t) {
+        const int vec = (kv8 && t >= 1 && t <= 4) ? 16 : (p->dtype == OT_BF16 ? 8 : 4);      // elements per 16 bytes
         for (int i = 0; i < 3; ++i)
             if (st[t][i] < 0 || st[t][i] % vec) return OT_ERR_INVALID_ARG;
         if (st[t][2] < p->head_dim) return OT_ERR_INVALID_ARG;
@@ -1139,24 +1202,30 @@ extern "C" {
 
 size_t ot_attn_workspace_bytes(const ot_attn_params* p) {
     if (validate_attn(p) != OT_OK) return 0;
-    return plan_attention(*p).bytes;
+    const size_t plain = plan_attention(*p).bytes;
+    // one workspace serves the 8-bit cache variant too, whose row blocks and key splits may differ
+    const size_t kv8 = p->dtype == OT_BF16 ? plan_attention(*p, true).bytes : 0;
+    return plain > kv8 ? plain : kv8;
 }
 
 static int attention_entry(const ot_attn_params* p, const void* Q, const void* K_prefix, const void* V_prefix,
                            const void* K_tree, const void* V_tree, const int32_t* prefix_len, const uint64_t* mask,
-                           void* O, void* workspace, size_t workspace_bytes, void* hip_stream, void* ev0, void* ev1) {
-    int st = validate_attn(p);
+                           void* O, void* workspace, size_t workspace_bytes, void* hip_stream, void* ev0, void* ev1,
+                           const float* k_scale = nullptr, const float* v_scale = nullptr, bool kv8 = false) {
+    int st = validate_attn(p, kv8);
     if (st != OT_OK) return st;
+    if (kv8 && (!k_scale || !v_scale || ((uintptr_t)k_scale % 4) || ((uintptr_t)v_scale % 4))) return OT_ERR_INVALID_ARG;
     if (!Q || !K_tree || !V_tree || !prefix_len || !mask || !O || !workspace) return OT_ERR_INVALID_ARG;
     if (p->max_prefix > 0 && (!K_prefix || !V_prefix)) return OT_ERR_INVALID_ARG;
     const void* ptrs[7] = {Q, K_prefix, V_prefix, K_tree, V_tree, O, workspace};
     for (int i = 0; i < 7; ++i)
         if (ptrs[i] && ((uintptr_t)ptrs[i] % 16)) return OT_ERR_INVALID_ARG;
     if (((uintptr_t)prefix_len % 4) || ((uintptr_t)mask % 8)) return OT_ERR_INVALID_ARG;
-    const AttnPlan plan = plan_attention(*p);
+    const AttnPlan plan = plan_attention(*p, kv8);
     if (workspace_bytes < plan.bytes) return OT_ERR_WORKSPACE_TOO_SMALL;
     return launch_tree_attention(*p, plan, Q, K_prefix, V_prefix, K_tree, V_tree, prefix_len, mask, O, workspace,
-                                 (hipStream_t)hip_stream, (hipEvent_t)ev0, (hipEvent_t)ev1);
+                                 (hipStream_t)hip_stream, (hipEvent_t)ev0, (hipEvent_t)ev1, kv8 ? k_scale : nullptr,
+                                 kv8 ? v_scale : nullptr);
 }
 
 int ot_attn_workspace_prepare(void* workspace, size_t workspace_bytes, void* hip_stream) {
@@ -1215,6 +1284,14 @@ int ot_tree_verify_attention_noalloc(const ot_attn_params* p, const void* Q, con
     }
     return attention_entry(p, Q, K_prefix, V_prefix, K_tree, V_tree, prefix_len, mask, O, ptr, OT_ATTN_SCRATCH_BYTES,
                            hip_stream, nullptr, nullptr);
+}
+
+int ot_tree_verify_attention_fp8kv(const ot_attn_params* p, const void* Q, const void* K_prefix, const void* V_prefix,
+                                   const void* K_tree, const void* V_tree, const float* k_scale, const float* v_scale,
+                                   const int32_t* prefix_len, const uint64_t* mask, void* O, void* workspace,
+                                   size_t workspace_bytes, void* hip_stream) {
+    return attention_entry(p, Q, K_prefix, V_prefix, K_tree, V_tree, prefix_len, mask, O, workspace, workspace_bytes,
+                           hip_stream, nullptr, nullptr, k_scale, v_scale, true);
 }
 
 int ot_tree_verify_attention_timed(const ot_attn_params* p, const void* Q, const void* K_prefix, const void* V_prefix,

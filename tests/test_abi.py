@@ -107,6 +107,24 @@ def test_attention_rejects_bad_arguments_without_launching():
     assert L.ot_attn_workspace_prepare(f, 100, None) == -3
 
 
+def test_fp8_cache_attention_rejects_bad_arguments_without_launching():
+    L = api.lib()
+    s = (C.c_int64 * 3)
+    f = C.c_void_p(0x1000)
+    ok = _ap(dtype=1)                                      # bf16 Q and O; all K/V strides are multiples of 16 bytes
+    need = api.attn_workspace_bytes(ok)
+    call = lambda p, a, ws=need: L.ot_tree_verify_attention_fp8kv(C.byref(p), *a, ws, None)
+    args = [f] * 11                                        # Q, Kp, Vp, Kt, Vt, k_scale, v_scale, prefix_len, mask, O, workspace
+    assert call(_ap(dtype=0), args) == -1                  # f32 Q/O
+    assert call(_ap(dtype=1, kp_strides=s(32768, 8192, 72)), args) == -1     # 72 bytes: fine for bf16 rows, not for byte rows
+    bad = list(args); bad[5] = None
+    assert call(ok, bad) == -1                             # k_scale NULL
+    bad = list(args); bad[6] = C.c_void_p(0x1002)
+    assert call(ok, bad) == -1                             # v_scale misaligned
+    assert call(ok, args, need - 1) == -3
+    assert call(_ap(dtype=1, head_dim=96), args) == -2
+
+
 def test_no_allocation_entry_point_validates_before_touching_the_gpu():
     L = api.lib()
     f = C.c_void_p(0x1000)

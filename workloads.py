@@ -188,6 +188,18 @@ def make_attention_inputs(w: Workload, seed: int, seqs=None, n=None):
     return dict(Q=Q, K_prefix=Kp, V_prefix=Vp, K_tree=Kt, V_tree=Vt, prefix_len=plen.astype(np.int32))
 
 
+def quantise_cache_e4m3(prefix_stored: np.ndarray, tree_stored: np.ndarray, dtype: str):
+    """The caller-side step that writes an 8-bit cache: one scale per (sequence, KV head) = largest magnitude over
+    prefix and tree rows / 448 (the format's largest value), values divided by it and rounded to E4M3 bytes.
+    Inputs [B,Hkv,rows,D] in the stored dtype; returns (prefix bytes, tree bytes, float32 scales [B,Hkv])."""
+    pre = to_f64(prefix_stored, dtype).astype(np.float32)
+    tre = to_f64(tree_stored, dtype).astype(np.float32)
+    amax = np.maximum(np.abs(pre).max(axis=(2, 3)), np.abs(tre).max(axis=(2, 3)))
+    scale = (np.maximum(amax, 1e-12) / np.float32(448.0)).astype(np.float32)
+    s = scale[:, :, None, None]
+    return f32_to_e4m3_bits(pre / s), f32_to_e4m3_bits(tre / s), scale
+
+
 def random_tree_parents(n: int, seed: int, shape: str = "random") -> np.ndarray:
     """A random forest over n nodes in parents-first order: parent[i] in [-1, i) (-1 = child of the root)."""
     g = _rng(seed, 4, n)
