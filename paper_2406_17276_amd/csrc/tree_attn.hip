@@ -64,6 +64,7 @@ struct AttnKArgs {
     float* part_o;      // per-split partial O   (layout: see the kernel that writes it)
     float* part_ml;     // per-split (m, l)
     int batch, q_heads, kv_heads, g, n, nk, D, max_prefix, splits, W, dtype, row_blocks;   // n query rows, nk tree keys
+    int splits_share_xcd;   // workgroup numbering of the bf16 kernel, see there
     unsigned int inv_splits, inv_kv_heads, inv_n;   // division by multiplication (fast_div): ceil(2^32 / d), unused for d = 1
     float scale_log2;   // softmax scale * log2(e)
     const float *k_scale, *v_scale;   // 8-bit K/V cache: one factor per (sequence, KV head) each; null otherwise
@@ -126,7 +127,9 @@ __device__ __forceinline__ void split_range(int T, int S, unsigned int inv_S, in
 //                Two tile buffers, so that two workgroups share a compute unit.
 // Workgroups are numbered so that those which stream the same K/V (the row blocks of one
 // (sequence, KV head, split)) sit on the same XCD, next to each other in its dispatch order, and
-// share that XCD's L2: hardware hands workgroup L to XCD L % 8.
+// share that XCD's L2: hardware hands workgroup L to XCD L % 8.  When the (sequence, KV head) pairs divide evenly
+// over the eight XCDs, the key splits of a pair share an XCD as well: they read the same Q rows, which then come
+// from memory once per pair instead of once per split.
 //
 // With more than one split, every workgroup leaves its partial (O, m, l) in the workspace in the
 // accumulator's own register order (coalesced 16-byte stores), then takes a ticket from the counter
@@ -185,9 +188,19 @@ __global__ __launch_bounds__(VAR == 2 ? 512 : 256) __attribute__((amdgpu_waves_p
     // workgroup numbering: see above
     // grid (8 x row blocks, units / 8): hardware hands workgroups out with x running fastest
     const int xcd = blockIdx.x & 7, rb = blockIdx.x >> 3;
-    const int unit = blockIdx.y * 8 + xcd;
-    if (unit >= a.batch * a_kv_heads * a_splits) return;
-    const int bz = fast_div(unit, a_splits, a_inv_splits), split = unit - bz * a_splits;
+    int bz, split;
+    if (a.splits_share_xcd) {
+        // (sequence, KV head) pairs dealt round over the XCDs, all splits of a pair on the same one
+        const int round = fast_div(blockIdx.y, a_splits, a_inv_splits);
+        split = blockIdx.y - round * a_splits;
+        bz = round * 8 + xcd;
+        if (bz >= a.batch * a_kv_heads) return;
+    } else {
+        const int unit = blockIdx.y * 8 + xcd;
+        if (unit >= a.batch * a_kv_heads * a_splits) return;
+        bz = fast_div(unit, a_splits, a_inv_splits);
+        split = unit - bz * a_splits;
+    }
     const int b = fast_div(bz, a_kv_heads, a_inv_kv_heads), hk = bz - b * a_kv_heads;
     const int n = a_n;
     // the prefix length decides which tiles this workgroup streams: fetched first (a scalar load, ahead of the
@@ -1105,6 +1118,7 @@ int launch_tree_attention(const ot_attn_params& p, const AttnPlan& plan, const v
                           const float* v_scale) {
     const bool kv8 = k_scale != nullptr;
     AttnKArgs a;
+    a.splits_share_xcd = 0;
     a.Q = Q; a.Kp = Kp; a.Vp = Vp; a.Kt = Kt; a.Vt = Vt;
     a.prefix_len = prefix_len; a.mask = mask; a.O = O;
     a.k_scale = k_scale; a.v_scale = v_scale;
@@ -1127,7 +1141,8 @@ int launch_tree_attention(const ot_attn_params& p, const AttnPlan& plan, const v
         int rows_wg = attn_rows_per_workgroup(a.g * p.n);
         if (kv8 && rows_wg == 256) rows_wg = 128;
         const long long units = (long long)p.batch * p.kv_heads * plan.splits;
-        const long long unit_groups = (units + 7) / 8;
+        const long long unit_groups = (units + 7) / 8;      // the same count either way when pairs % 8 == 0
+        a.splits_share_xcd = (plan.splits > 1 && ((long long)p.batch * p.kv_heads) % 8 == 0) ? 1 : 0;
         if (unit_groups > 65535 || 8LL * plan.row_blocks > 0x7fffffffLL) return OT_ERR_UNSUPPORTED;   // cannot happen within the limits
         if (plan.splits > 1 && (long long)p.batch * p.kv_heads * plan.row_blocks * 4 > OT_ATTN_STATUS_OFFSET)
             return OT_ERR_UNSUPPORTED;      // cannot happen: splits > 1 only with few workgroups
