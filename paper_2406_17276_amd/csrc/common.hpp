@@ -130,9 +130,12 @@ __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w 
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
 // DPP moves inside a 64-lane wavefront (GCN/CDNA encodings).
-template <int CTRL, int ROW_MASK = 0xf>
+// BOUND (bound_ctrl): a lane whose source does not exist reads 0 instead of keeping `old`.  The quad and mirror
+// permutations have a source for every lane, so the flag changes nothing there -- except that the compiler may
+// then fold the move into the instruction that uses it.
+template <int CTRL, int ROW_MASK = 0xf, bool BOUND = (ROW_MASK == 0xf && (CTRL < 0x100 || CTRL == 0x140 || CTRL == 0x141))>
 __device__ __forceinline__ int dpp_i(int old, int v) {
-    return __builtin_amdgcn_update_dpp(old, v, CTRL, ROW_MASK, 0xf, false);
+    return __builtin_amdgcn_update_dpp(old, v, CTRL, ROW_MASK, 0xf, BOUND);
 }
 constexpr int DPP_QUAD_XOR1 = 0xB1;      // quad_perm [1,0,3,2]
 constexpr int DPP_QUAD_XOR2 = 0x4E;      // quad_perm [2,3,0,1]
@@ -189,6 +192,14 @@ __device__ __forceinline__ double wave_sum_d(double v) {
     v += dpp_d<DPP_ROW_HALF_MIRROR>(v);
     v += dpp_d<DPP_ROW_MIRROR>(v);
     return (rl_d(v, 0) + rl_d(v, 16)) + (rl_d(v, 32) + rl_d(v, 48));
+}
+// sum over the wavefront as a scalar: fp32 inside each row of 16 lanes, the four row sums added in fp64
+__device__ __forceinline__ double wave_sum_rows_d(float v) {
+    v += __int_as_float(dpp_i<DPP_QUAD_XOR1>(__float_as_int(v), __float_as_int(v)));
+    v += __int_as_float(dpp_i<DPP_QUAD_XOR2>(__float_as_int(v), __float_as_int(v)));
+    v += __int_as_float(dpp_i<DPP_ROW_HALF_MIRROR>(__float_as_int(v), __float_as_int(v)));
+    v += __int_as_float(dpp_i<DPP_ROW_MIRROR>(__float_as_int(v), __float_as_int(v)));
+    return ((double)rl_f(v, 0) + (double)rl_f(v, 16)) + ((double)rl_f(v, 32) + (double)rl_f(v, 48));
 }
 // max over the wavefront as a scalar
 __device__ __forceinline__ float wave_max_f(float v) {

@@ -9,8 +9,8 @@
 //   2. every wavefront, on its own: lane maxima -> wave maximum m_w, then s_w = sum exp(x - m_w)
 //      over its registers (no workgroup barrier before this, so wavefronts whose data arrived
 //      early do their arithmetic while the others still wait for memory),
-//   3. barrier; tau = the k-th largest of 16 group maxima (one per 1/16th of the workgroup): each
-//      group holds an element >= its maximum, so at least k elements are >= tau,
+//   3. barrier; tau = the k-th largest of the group maxima (a group = a row of 16 lanes, 64 groups in a
+//      1024-thread workgroup): each group holds an element >= its maximum, so at least k elements are >= tau,
 //   4. sweep over the registers: elements >= tau go to an LDS candidate list (a 16-byte vector is
 //      skipped when its own maximum is below tau),
 //   5. the k best candidates are ranked by counting (value desc, token asc); the wave partials are
@@ -19,6 +19,7 @@
 // If the candidate list overflows (massive ties), a slow exact path extracts the k best
 // by k rounds of a workgroup-wide arg-max over the part, re-read from memory.
 #include "common.hpp"
+#include <type_traits>
 
 namespace ot {
 namespace {
@@ -59,7 +60,8 @@ __device__ __forceinline__ void scan_item(const ScanHead& h, const ScanKArgs& a,
     constexpr int VPL = EPL / VEC;      // 16-byte vectors per lane
     constexpr int NW = NT / 64;
 
-    __shared__ float s_gmax[16];
+    constexpr int G = NT / 16;          // groups for the threshold: the rows of 16 lanes (16, 32 or 64 of them)
+    __shared__ float s_gmax[G];
     __shared__ float s_wm[16];
     __shared__ double s_ws[16];
     __shared__ float s_tau;
@@ -92,39 +94,59 @@ __device__ __forceinline__ void scan_item(const ScanHead& h, const ScanKArgs& a,
 
     // ---- 1. load ----------------------------------------------------------
     // VECLOAD: the host guarantees 16-byte aligned rows and vocab % VEC == 0, so a vector is
-    // either wholly inside the part or wholly outside.  Otherwise: guarded scalar loads.
+    // either wholly inside the part or wholly outside.  A lane's address is (uniform start of the part) + (a 32-bit
+    // byte offset); lanes past the end of the part re-read the part's first vector and are set to -inf afterwards,
+    // which only the part's last vectors need (a uniform test).  Otherwise: guarded scalar loads.
     float x[EPL];
-    if (DT == OT_BF16) {
+    const int len = e_end - e_begin;
+    if (VECLOAD) {
+        typedef typename std::conditional<DT == OT_BF16, u32x4, f32x4>::type vec_t;
+        constexpr int ESIZE = DT == OT_BF16 ? 2 : 4;
+        const char* part = (const char*)h.logits + (row_off + e_begin) * ESIZE;
+        vec_t w[VPL];
+#pragma unroll
+        for (int i = 0; i < VPL; ++i) {                   // all loads go out before the first use
+            const int e = (i * NT + tid) * VEC;
+            w[i] = __builtin_nontemporal_load((const vec_t*)(part + (e < len ? (unsigned int)e * ESIZE : 0u)));
+        }
+#pragma unroll
+        for (int i = 0; i < VPL; ++i) {
+            if ((i + 1) * NT * VEC > len) {
+                asm volatile("");      // keeps this a branch: full vectors skip the selects
+                const bool have = (i * NT + tid) * VEC < len;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    if (DT == OT_BF16) w[i][c] = have ? w[i][c] : 0xff80ff80u;     // a pair of -inf
+                    else               w[i][c] = have ? w[i][c] : -INFINITY;
+                }
+            }
+            if (DT == OT_BF16) {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    x[i * 8 + 2 * c] = bf16_lo((uint32_t)w[i][c]);
+                    x[i * 8 + 2 * c + 1] = bf16_hi((uint32_t)w[i][c]);
+                }
+            } else {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) x[i * 4 + c] = (float)w[i][c];
+            }
+        }
+    } else if (DT == OT_BF16) {
         const unsigned short* row = (const unsigned short*)h.logits + row_off;
 #pragma unroll
         for (int i = 0; i < VPL; ++i) {
             const int e0 = e_begin + (i * NT + tid) * VEC;
-            if (VECLOAD) {
-                u32x4 w = {0xff80ff80u, 0xff80ff80u, 0xff80ff80u, 0xff80ff80u};   // -inf pairs
-                if (e0 < e_end) w = __builtin_nontemporal_load((const u32x4*)(row + e0));
-                x[i * 8 + 0] = bf16_lo(w.x); x[i * 8 + 1] = bf16_hi(w.x);
-                x[i * 8 + 2] = bf16_lo(w.y); x[i * 8 + 3] = bf16_hi(w.y);
-                x[i * 8 + 4] = bf16_lo(w.z); x[i * 8 + 5] = bf16_hi(w.z);
-                x[i * 8 + 6] = bf16_lo(w.w); x[i * 8 + 7] = bf16_hi(w.w);
-            } else {
 #pragma unroll
-                for (int c = 0; c < VEC; ++c)
-                    x[i * 8 + c] = (e0 + c < e_end) ? __uint_as_float((unsigned)row[e0 + c] << 16) : -INFINITY;
-            }
+            for (int c = 0; c < VEC; ++c)
+                x[i * 8 + c] = (e0 + c < e_end) ? __uint_as_float((unsigned)row[e0 + c] << 16) : -INFINITY;
         }
     } else {
         const float* row = (const float*)h.logits + row_off;
 #pragma unroll
         for (int i = 0; i < VPL; ++i) {
             const int e0 = e_begin + (i * NT + tid) * VEC;
-            if (VECLOAD) {
-                f32x4 w = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
-                if (e0 < e_end) w = __builtin_nontemporal_load((const f32x4*)(row + e0));
-                x[i * 4 + 0] = w.x; x[i * 4 + 1] = w.y; x[i * 4 + 2] = w.z; x[i * 4 + 3] = w.w;
-            } else {
 #pragma unroll
-                for (int c = 0; c < VEC; ++c) x[i * 4 + c] = (e0 + c < e_end) ? row[e0 + c] : -INFINITY;
-            }
+            for (int c = 0; c < VEC; ++c) x[i * 4 + c] = (e0 + c < e_end) ? row[e0 + c] : -INFINITY;
         }
     }
 
@@ -150,27 +172,26 @@ __device__ __forceinline__ void scan_item(const ScanHead& h, const ScanKArgs& a,
 #pragma unroll
         for (int i = 0; i < EPL; ++i) acc[i & 3] += __builtin_amdgcn_exp2f(fmaf(x[i], kLog2e, -mc_w));
     }
-    const double s_w = wave_sum_d((double)(acc[0] + acc[1]) + (double)(acc[2] + acc[3]));
+    const double s_w = wave_sum_rows_d((acc[0] + acc[1]) + (acc[2] + acc[3]));
     const int lane = tid & 63, wave = tid >> 6;
     if (lane == 0) { s_wm[wave] = mc_w; s_ws[wave] = s_w; }     // (reference exponent in log2 units, sum)
-    // 16 group maxima: a group is 1/16th of the workgroup (a wavefront, half of one, or a row of 16 lanes)
-    if (NT == 1024)     { if (lane == 0) s_gmax[wave] = m_w; }
-    else if (NT == 512) { if (lane == 0) { s_gmax[2 * wave] = fmaxf(rl_f(rmax, 0), rl_f(rmax, 16));
-                                           s_gmax[2 * wave + 1] = fmaxf(rl_f(rmax, 32), rl_f(rmax, 48)); } }
-    else                { if ((lane & 15) == 0) s_gmax[tid >> 4] = rmax; }
+    // group maxima: a group is a row of 16 lanes
+    if ((lane & 15) == 0) s_gmax[tid >> 4] = rmax;
     __syncthreads();
 
-    // ---- 3. tau: the kk-th largest of the 16 group maxima ------------------
-    if (tid < 16) {
-        const float v = s_gmax[tid];
-        int rank = 0;
+    // ---- 3. tau: the kk-th largest of the G group maxima -------------------
+    // Every group holds an element >= its maximum, so at least kk elements are >= tau; the more groups, the
+    // tighter the threshold (k = 16 over 16 groups would take the smallest maximum and let several times k
+    // elements through).  Wavefront w ranks maxima w, w + NW, ...: one ballot per maximum, all wavefronts at once.
+    {
+        const int kk = a.k < G ? a.k : G;
+        const float mine = lane < G ? s_gmax[lane] : -INFINITY;
 #pragma unroll
-        for (int jj = 0; jj < 16; ++jj) {
-            const float u = s_gmax[jj];
-            rank += (u > v || (u == v && jj < tid)) ? 1 : 0;
+        for (int q = wave; q < G; q += NW) {
+            const float v = s_gmax[q];
+            const unsigned long long before = __ballot(lane < G && (mine > v || (mine == v && lane < q)));
+            if (__popcll(before) == kk - 1 && lane == 0) s_tau = v;
         }
-        const int kk = a.k < 16 ? a.k : 16;
-        if (rank == kk - 1) s_tau = v;
     }
     __syncthreads();
     const float tau = s_tau;
