@@ -52,7 +52,8 @@ BuildWorkspace carve_build_workspace(const ot_build_params& p, void* base) {
     memset(&w, 0, sizeof(w));
     size_t off = 0;
     char* b = (char*)base;
-    auto take = [&](size_t bytes) { char* q = b + off; off = align_up(off + bytes, 256); return (void*)q; };
+    // (a null base is the sizing pass: offsets only)
+    auto take = [&](size_t bytes) { char* q = b ? b + off : nullptr; off = align_up(off + bytes, 256); return (void*)q; };
     w.row_lse = (double*)take(rows * 8);
     w.row_topv = (float*)take(rows * k * 4);
     w.row_topi = (int32_t*)take(rows * k * 4);

@@ -1277,7 +1277,7 @@ int ot_tree_verify_attention_noalloc(const ot_attn_params* p, const void* Q, con
                                      const uint64_t* mask, void* O, void* hip_stream) {
     int st = validate_attn(p);
     if (st != OT_OK) return st;
-    if (plan_attention(*p).bytes > (size_t)OT_ATTN_SCRATCH_BYTES) return OT_ERR_SCRATCH_LIMIT;
+    if (ot_attn_workspace_bytes(p) > (size_t)OT_ATTN_SCRATCH_BYTES) return OT_ERR_SCRATCH_LIMIT;
     int dev = -1;
     OT_HIP_CHECK(hipGetDevice(&dev));
     if (dev < 0 || dev >= kMaxDevices) return OT_ERR_UNSUPPORTED;

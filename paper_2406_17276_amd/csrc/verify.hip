@@ -300,7 +300,8 @@ BuildWorkspace carve_verify_workspace(const ot_verify_params& p, void* base) {
     memset(&w, 0, sizeof(w));
     size_t off = 0;
     char* b = (char*)base;
-    auto take = [&](size_t bytes) { char* q = b + off; off = align256(off + bytes); return (void*)q; };
+    // (a null base is the sizing pass: offsets only)
+    auto take = [&](size_t bytes) { char* q = b ? b + off : nullptr; off = align256(off + bytes); return (void*)q; };
     w.row_lse = (double*)take(rows * 8);
     w.row_topv = (float*)take(rows * 4);
     w.row_topi = (int32_t*)take(rows * 4);
@@ -321,7 +322,8 @@ SampleWorkspace carve_sample_workspace(const ot_verify_params& p, void* base) {
     w.nseg = (p.vocab + elems - 1) / elems;
     size_t off = 0;
     char* b = (char*)base;
-    auto take = [&](size_t bytes) { char* q = b + off; off = align256(off + bytes); return (void*)q; };
+    // (a null base is the sizing pass: offsets only)
+    auto take = [&](size_t bytes) { char* q = b ? b + off : nullptr; off = align256(off + bytes); return (void*)q; };
     w.seg_s = (double*)take(rows * w.nseg * 8);
     w.seg_m = (float*)take(rows * w.nseg * 4);
     w.truth = (int32_t*)take(rows * 4);

@@ -56,7 +56,7 @@ using namespace ot;
 extern "C" {
 
 int ot_yardstick_stream_read(const void* src, size_t bytes, void* sink, void* hip_stream) {
-    if (!src || !sink || bytes < 16 || ((uintptr_t)src % 16) || ((uintptr_t)sink % 4)) return OT_ERR_INVALID_ARG;
+    if (!src || !sink || bytes < 16 || bytes % 16 || ((uintptr_t)src % 16) || ((uintptr_t)sink % 4)) return OT_ERR_INVALID_ARG;
     hipLaunchKernelGGL(stream_read_kernel, dim3(OT_YARDSTICK_WORKGROUPS), dim3(256), 0, (hipStream_t)hip_stream,
                        (const u32x4*)src, bytes / 16, (unsigned int*)sink);
     OT_HIP_CHECK(hipGetLastError());
@@ -65,7 +65,7 @@ int ot_yardstick_stream_read(const void* src, size_t bytes, void* sink, void* hi
 
 int ot_yardstick_stream_read_timed(const void* src, size_t bytes, int32_t workgroups, void* sink, void* hip_stream,
                                    void* kernel_begin_event, void* kernel_end_event) {
-    if (!src || !sink || bytes < 16 || ((uintptr_t)src % 16) || ((uintptr_t)sink % 4)) return OT_ERR_INVALID_ARG;
+    if (!src || !sink || bytes < 16 || bytes % 16 || ((uintptr_t)src % 16) || ((uintptr_t)sink % 4)) return OT_ERR_INVALID_ARG;
     if (workgroups < 1 || workgroups > (1 << 20)) return OT_ERR_INVALID_ARG;
     hipExtLaunchKernelGGL(stream_read_kernel, dim3((unsigned)workgroups), dim3(256), 0, (hipStream_t)hip_stream,
                           (hipEvent_t)kernel_begin_event, (hipEvent_t)kernel_end_event, 0, (const u32x4*)src, bytes / 16,
