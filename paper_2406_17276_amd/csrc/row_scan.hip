@@ -396,35 +396,50 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu((NT == 1024 
     }
 }
 
-// Rows that span several parts: combine the per-part (max, sum) pairs and merge the
-// per-part sorted top-k lists.  One thread per row.
-__global__ void merge_parts_kernel(int rows, int parts, int k, const float* part_m, const double* part_s,
-                                   const float* part_topv, const int32_t* part_topi, double* row_lse,
-                                   float* row_topv, int32_t* row_topi) {
-    const int rid = blockIdx.x * blockDim.x + threadIdx.x;
-    if (rid >= rows) return;
-    const size_t base = (size_t)rid * parts;
+// Rows that span several parts: combine the per-part (max, sum) pairs and merge the per-part top-k lists.
+// One wavefront per row: the parts' statistics sit in the first lanes, the parts * k <= 128 candidates go through
+// LDS and every lane ranks its (at most two) candidates by counting those that precede them (value desc, token
+// asc: tokens of different parts differ, so the order is total); ranks below k are the row's list.
+__global__ __launch_bounds__(256) void merge_parts_kernel(int rows, int parts, int k, const float* part_m,
+                                                          const double* part_s, const float* part_topv,
+                                                          const int32_t* part_topi, double* row_lse, float* row_topv,
+                                                          int32_t* row_topi) {
+    __shared__ float s_v[4][128];
+    __shared__ int s_i[4][128];
+    const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int rid = blockIdx.x * 4 + w;
+    const bool live = rid < rows;
+    const size_t base = (size_t)(live ? rid : 0) * parts;
+    const int total = parts * k;
     // part_m is the part's reference exponent in log2 units (fp32 max times the fp32 log2e of the scan kernel)
-    float M = part_m[base];
-    for (int p = 1; p < parts; ++p) M = fmaxf(M, part_m[base + p]);
-    double s = 0.0;
-    for (int p = 0; p < parts; ++p) s += part_s[base + p] * exp2((double)part_m[base + p] - (double)M);
-    row_lse[rid] = (double)M / (double)kLog2e + log(s);
-    // k-way merge of sorted lists; heads[] are positions inside each part's list
-    int head[8];
-    for (int p = 0; p < 8; ++p) head[p] = 0;
-    for (int r = 0; r < k; ++r) {
-        int bp = -1; float bv = 0.f; int bi = 0;
-        for (int p = 0; p < parts; ++p) {
-            if (head[p] >= k) continue;
-            const float v = part_topv[(base + p) * k + head[p]];
-            const int id = part_topi[(base + p) * k + head[p]];
-            if (bp < 0 || v > bv || (v == bv && id < bi)) { bp = p; bv = v; bi = id; }
-        }
-        row_topv[(size_t)rid * k + r] = bv;
-        row_topi[(size_t)rid * k + r] = bi;
-        head[bp]++;
+    const float pm = lane < parts ? part_m[base + lane] : -INFINITY;
+    const float M = wave_max(pm);
+    const double s = wave_sum(lane < parts ? part_s[base + lane] * exp2((double)pm - (double)M) : 0.0);
+    if (live && lane == 0) row_lse[rid] = (double)M / (double)kLog2e + log(s);
+    for (int c = lane; c < total; c += 64) {               // the row's lists are contiguous: part p, rank r at p k + r
+        s_v[w][c] = part_topv[base * k + c];
+        s_i[w][c] = part_topi[base * k + c];
     }
+    __syncthreads();
+    float v[2]; int id[2], rank[2] = {0, 0};
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        const int c = lane + 64 * q;
+        v[q] = c < total ? s_v[w][c] : -INFINITY;
+        id[q] = c < total ? s_i[w][c] : 0x7fffffff;
+    }
+    for (int j = 0; j < total; ++j) {
+        const float u = s_v[w][j];
+        const int ui = s_i[w][j];
+#pragma unroll
+        for (int q = 0; q < 2; ++q) rank[q] += (u > v[q] || (u == v[q] && ui < id[q])) ? 1 : 0;
+    }
+#pragma unroll
+    for (int q = 0; q < 2; ++q)
+        if (live && lane + 64 * q < total && rank[q] < k) {
+            row_topv[(size_t)rid * k + rank[q]] = v[q];
+            row_topi[(size_t)rid * k + rank[q]] = id[q];
+        }
 }
 
 }  // namespace
@@ -475,8 +490,7 @@ int launch_row_scan(const ScanGeometry& g, const void* logits, const BuildWorksp
 #undef OT_SCAN_ARGS
     OT_HIP_CHECK(hipGetLastError());
     if (parts > 1) {
-        const int threads = 128;
-        hipLaunchKernelGGL(merge_parts_kernel, dim3((unsigned)((rows + threads - 1) / threads)), dim3(threads), 0, s,
+        hipLaunchKernelGGL(merge_parts_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s,
                            (int)rows, parts, g.k, ws.part_m, ws.part_s, ws.part_topv, ws.part_topi, ws.row_lse,
                            ws.row_topv, ws.row_topi);
         OT_HIP_CHECK(hipGetLastError());
