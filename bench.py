@@ -171,16 +171,19 @@ def gqa_leg(name: str, steps: int, hip, stream):
     logit_bytes = w.batch * w.rows_per_seq() * w.vocab * w.elem_bytes()
     tf = flops / (attn_us * 1e-6) / 1e12
     gbs = logit_bytes / (scan_us * 1e-6) / 1e9
+    traffic, traffic_src = measured_traffic(name)
     return {"workload": f"{w.name}: batch {w.batch}, vocab {w.vocab}, depth {w.depth}, top-k {w.k}, n {w.n}; attention "
                         f"{w.q_heads}q/{w.kv_heads}kv heads, head_dim {w.head_dim}, prefix {w.prefix} +-{int(w.ragged * 100)}%",
             "steps": steps, "ms_per_step": ms, "steps_per_s": 1e3 / ms, "ring_copies": 2, "inputs": "drawn on the device",
             "parity_checked": {"tree_sequence_0": tree_checked, "attention_group_0_max_abs_err": err},
             "roofline": {"kernel": "attn_mfma_kernel", "bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS,
                          "unit": "TFLOP/s", "frac": tf / MFMA_BF16_PEAK_TFLOPS, "algorithmic_flops": flops,
-                         "avg_kernel_us": attn_us, "traffic": None},
+                         "avg_kernel_us": attn_us, "traffic": traffic.get("attn_mfma_kernel"),
+                         "traffic_source": traffic_src},
             "roofline_scan": {"kernel": "row_scan_kernel", "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS,
                               "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS, "algorithmic_bytes": logit_bytes,
-                              "avg_kernel_us": scan_us, "traffic": None}}
+                              "avg_kernel_us": scan_us, "traffic": traffic.get("row_scan_kernel"),
+                              "traffic_source": traffic_src}}
 
 
 def main():
