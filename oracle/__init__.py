@@ -9,7 +9,7 @@ the HIP package.
   opt_tree.py        draft-tree construction (Sec. 3: Eq. 1-3, Thm. 3.1/3.2,
                      Algorithm 1 with a fixed number of drafting steps)
   tree_attention.py  tree-masked attention used by the verification forward
-                     (Sec. 3, Algorithm 2: "tree attention mask")
+                     (Sec. 3, Algorithm 2: the mask that goes with the tree)
 
 Parity pins (tests/test_oracle_*.py, marker "not gpu"):
   row statistics      -> scipy.special.logsumexp, closed form for constant rows,

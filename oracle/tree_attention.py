@@ -1,7 +1,7 @@
 """fp64 oracle for tree-masked verification attention.  TEST INFRASTRUCTURE ONLY.
 
 Algorithm 2 of the paper (arxiv 2406.17276) feeds the n draft nodes to the
-target model together with "the corresponding tree attention mask": every
+target model together with the attention mask that belongs to the tree: every
 node attends to the whole cached prefix and, inside the tree, to itself and
 its ancestors only (Sec. 1, tree-structured drafts; Sec. 3, Algorithm 2).
 The paper gives no formula for attention itself; this is ordinary scaled
