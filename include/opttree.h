@@ -14,7 +14,8 @@
  *     stream has been synchronised;
  *   - the library keeps no global device state: scratch lives in a caller-owned
  *     workspace sized by the *_workspace_bytes query.  Concurrent calls must use
- *     distinct workspaces;
+ *     distinct workspaces.  (One documented exception: ot_tree_verify_attention_noalloc
+ *     works in a fixed array that the library's code object holds on every GPU.);
  *   - alignment of device pointers: workspaces and the attention tensors (Q, K, V, O) 16 bytes; logits
  *     rows the size of one element (rows that are 16-byte aligned, with strides and a vocabulary that are
  *     multiples of 16 bytes, take the vector-load path, anything else a slower element-load path); int32 /
