@@ -492,6 +492,10 @@ __global__ __launch_bounds__(VAR == 2 ? 512 : 256) __attribute__((amdgpu_waves_p
         // the slack (every row's first tile, then rarely) leaves the loop before anything of the tile is added;
         // the reference moves up, O and l are rescaled out here, and the loop is entered again at the same tile.
         constexpr float kSlack = 12.f;
+#ifndef OT_ATTN_SUMCHECK
+#define OT_ATTN_SUMCHECK 1
+#endif
+        constexpr float kSumLimit = 16.f * 4096.f;          // sixteen terms of at most 2^kSlack
         static_assert((NBUF & (NBUF - 1)) == 0, "the buffer of a tile is (t - t0) mod NBUF");
         // tile t has landed for this lane when only the requests of the tiles behind it are outstanding; after the
         // barrier it has for everybody, and everybody is done with the buffer that tile t + PD goes into
@@ -567,8 +571,10 @@ __global__ __launch_bounds__(VAR == 2 ? 512 : 256) __attribute__((amdgpu_waves_p
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int s = 0; s < SLABS; ++s) kf[s] = kfrag(s_k, 1, s);
+#if !OT_ATTN_SUMCHECK
                 seen = row_max(s0);
                 if (__any(seen > limit)) break;
+#endif
                 __builtin_amdgcn_sched_barrier(0);
                 // S of block 1 in the matrix pipe, the exponentials of block 0 in the vector ALU, the V operands of
                 // block 0 on their way.  One matrix instruction, then its share of the rest: the wavefront issues in
@@ -604,7 +610,16 @@ __global__ __launch_bounds__(VAR == 2 ? 512 : 256) __attribute__((amdgpu_waves_p
                 }
                 __builtin_amdgcn_sched_barrier(0);
                 seen = row_max(s1);
+#if OT_ATTN_SUMCHECK
+                // block 0 is tested on what its exponentials came to instead of on its scores: a probability beyond
+                // 2^kSlack shows in the lane's sum (all terms are positive; an overflow gives +inf), which is there
+                // anyway, while the maximum of sixteen scores costs a dozen instructions.  Nothing of the tile has
+                // been added yet.  The bound is on the sum of sixteen terms, so single terms up to 2^kSlack pass
+                // as before and a few somewhat larger ones may: the formats have the room.
+                if (__any(seen > limit || psum > kSumLimit)) break;
+#else
                 if (__any(seen > limit)) break;
+#endif
                 __builtin_amdgcn_sched_barrier(0);
                 // P V of block 0 in the matrix pipe, the exponentials of block 1 in the vector ALU, the V operands of
                 // block 1 on their way
