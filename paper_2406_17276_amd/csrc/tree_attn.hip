@@ -24,7 +24,7 @@
 // tile's mask words (one 64-bit word per query row) travel the same way, just ahead of the tile.  A
 // wavefront's 64 lanes land on 1 KB of consecutive LDS, so rows are unpadded and bank conflicts are
 // avoided by an XOR swizzle instead: lane -> global chunk is chosen such that 16-byte chunk c of key
-// row r sits at chunk position c ^ (r mod 16) (K), and 32-byte segment g of row r at g ^ (r mod 8) (V).
+// row r sits at chunk position c ^ (r mod 16) (K), and 32-byte segment g of row r at g ^ v_swizzle(r) (V; see the kernel).
 // Tiles that reach past the end of the keys re-read the last valid row for the missing rows (their scores
 // are masked).  V is the transposed operand (a lane needs 8 keys of ONE column): it is read with the gfx950
 // LDS transpose load ds_read_b64_tr_b16, which lets 16 lanes read four 32-byte row segments and hands
@@ -162,6 +162,12 @@ __global__ __launch_bounds__(VAR == 2 ? 512 : 256) __attribute__((amdgpu_waves_p
     constexpr int TK = 64;                 // keys per tile
     constexpr int CPR = D / 8;             // 16-byte chunks per row
     constexpr int SPR = D / 16;            // 32-byte segments per row
+    // Where V's 32-byte segment g of key row r sits inside the row: at g ^ v_swizzle(r).  A transposed operand read
+    // touches, per 32 lanes, four consecutive rows (r mod 4 = 0..3) and the two halves of a 32-column block (segments
+    // 2d and 2d + 1); LDS serves 256 bytes = eight segments per cycle, so these eight must fall into eight different
+    // 32-byte slots of a 256-byte window: the row's low bits go into the bits above the half bit (a plain g ^ (r mod 8)
+    // put two of them into every slot it used: every such read took twice its time).
+    auto v_swizzle = [](int r) { return D == 128 ? (r & 3) << 1 : ((r >> 1) & 1) << 1; };
     constexpr int SLABS = D / 16;          // 16-wide d slabs of the QK^T contraction
     constexpr int DB = D / 32;             // 32-wide d blocks of O^T
     constexpr int ESZ = KV8 ? 1 : 2;       // bytes per stored K/V element
@@ -240,9 +246,9 @@ __global__ __launch_bounds__(VAR == 2 ? 512 : 256) __attribute__((amdgpu_waves_p
     // transpose-load addressing: key row and first column this lane points at inside a 4-key x 32-column block
     const int tr_j = (lane & 15) >> 2, tr_q = 4 * (lane & 3);
     // swizzle terms of this lane's operand reads: K chunk (2s + h) of row l32 -> position (2s) ^ kx;
-    // V segment (2d + g1) of row 4h + tr_j (mod 8) -> position (2d) ^ vx
+    // V segment (2d + g1) of row 4h + tr_j (mod 4) -> position (2d) ^ vx
     const int kx = h ^ (l32 & (CPR - 1));
-    const int vx = ((lane >> 4) & 1) ^ ((4 * h + tr_j) & (SPR - 1));
+    const int vx = ((lane >> 4) & 1) ^ v_swizzle(4 * h + tr_j);
     // scores are kept raw; p = 2^(c s - c m).  An 8-bit cache's K factor scales every score: it joins c.
     const float c = KV8 ? a.scale_log2 * a.k_scale[bz] : a.scale_log2;
     const float v_factor = KV8 ? a.v_scale[bz] : 1.f;
@@ -260,7 +266,7 @@ __global__ __launch_bounds__(VAR == 2 ? 512 : 256) __attribute__((amdgpu_waves_p
     constexpr int KSTEP = NT / CPRG;
     const int kkey0 = tid / CPRG, pc = tid % CPRG;
     const int kcol = KV8 ? pc * 16 : (pc ^ (kkey0 & (CPR - 1))) * 16;                        // byte column; K: chunk c = pc ^ (r % 16)
-    const int vcol = KV8 ? pc * 16 : (2 * ((pc >> 1) ^ (kkey0 & (SPR - 1))) + (pc & 1)) * 16;  // V: segment g = (pc/2) ^ (r % 8)
+    const int vcol = KV8 ? pc * 16 : (2 * ((pc >> 1) ^ v_swizzle(kkey0)) + (pc & 1)) * 16;  // V: segment g = (pc/2) ^ v_swizzle(r)
     const int wave_u = wave;
     // Request tile t: global memory -> LDS buffer `buf`, 16 bytes per lane and instruction, no registers in
     // between.  Full tiles address memory as (uniform base of the tile's rows) + (this lane's fixed 32-bit
@@ -327,7 +333,7 @@ __global__ __launch_bounds__(VAR == 2 ? 512 : 256) __attribute__((amdgpu_waves_p
     // KV8: widen the tile that has just landed in buffer `buf`, in place.  Every thread reads the sixteen-byte pieces
     // it owns (sixteen values each), the workgroup meets (the bf16 tile overwrites the bytes), the pieces are written
     // as bf16 where the operand reads expect them (K: 16-byte chunk c of row r at position c ^ (r mod 16); V: 32-byte
-    // segment g at g ^ (r mod 8)), and the workgroup meets again.
+    // segment g at g ^ v_swizzle(r)), and the workgroup meets again.
     auto widen_tile = [&](int buf) {
         unsigned char* const rk = (unsigned char*)(s_buf + buf * BUF);
         unsigned char* const rv = rk + TK * D * 2;
@@ -359,7 +365,7 @@ __global__ __launch_bounds__(VAR == 2 ? 512 : 256) __attribute__((amdgpu_waves_p
             *(u32x4*)(krow + (((2 * c16) ^ (row & (CPR - 1))) << 3)) = lo;
             *(u32x4*)(krow + (((2 * c16 + 1) ^ (row & (CPR - 1))) << 3)) = hi;
             widen(wv[cc], lo, hi);
-            unsigned short* const vseg = (unsigned short*)rv + row * D + ((c16 ^ (row & (SPR - 1))) << 4);
+            unsigned short* const vseg = (unsigned short*)rv + row * D + ((c16 ^ v_swizzle(row)) << 4);
             *(u32x4*)vseg = lo;
             *(u32x4*)(vseg + 8) = hi;
         }
