@@ -97,6 +97,7 @@ int launch_tree_esub(const SelectGeometry& g, int steps_done, double delta, cons
 struct AttnPlan {
     int row_blocks;      // blocks of query rows per KV head
     int splits;          // KV splits per (b, kv head, row block)
+    int balance;         // bf16 batches: workgroups take their jobs longest first, decided on the device
     size_t part_o_bytes, part_ml_bytes, bytes;
 };
 AttnPlan plan_attention(const ot_attn_params& p, bool kv8 = false);

@@ -130,6 +130,52 @@ def test_full_batch_as_the_bench_launches_it_sampled_groups(name, groups):
         assert np.abs(got - want).max() < TOL["bf16"]
 
 
+@pytest.mark.parametrize("B,Hq,Hkv,D,n,lengths", [
+    (33, 16, 8, 128, 40, "ragged"),        # 128-row blocks, 264 workgroups: one more round than the chip holds at once
+    (64, 8, 4, 128, 70, "ragged"),         # 256-row blocks, 256 workgroups, the largest batch that is ranked
+    (40, 16, 8, 64, 33, "ties"),           # head_dim 64; many equal lengths, some zero, some beyond the buffer
+    (65, 8, 4, 128, 70, "ragged"),         # one sequence too many for the ranking: the order of the sequences
+])
+def test_batches_that_take_their_jobs_longest_first(B, Hq, Hkv, D, n, lengths):
+    """Batches that fill the chip with one key range per (sequence, KV head): every workgroup ranks the sequences by
+    prefix length on the device and takes its job in that order.  Whatever the order, every (sequence, KV head) must
+    come out exactly once: all outputs are finite and non-zero, and sampled sequences (the longest, the shortest, ties,
+    clamped ones) agree with the oracle."""
+    import torch
+    from paper_2406_17276_amd import api
+    Lmax, g = 320, Hq // Hkv
+    rng = np.random.default_rng(B * 1000 + n)
+    if lengths == "ragged":
+        plen = rng.integers(1, Lmax + 1, size=B).astype(np.int32)
+        plen[0], plen[B // 2], plen[B - 1] = Lmax, 1, Lmax // 2
+    else:
+        plen = rng.choice(np.array([0, 64, 64, 128, 200, 200, 200, Lmax], dtype=np.int32), size=B)
+        plen[1], plen[2] = Lmax + 500, -7                     # clamped to Lmax and to 0 on the device
+    eff = np.clip(plen, 0, Lmax)
+    gen = torch.Generator(device="cuda"); gen.manual_seed(B + n)
+    draw = lambda *shape: torch.randn(shape, generator=gen, device="cuda").to(torch.bfloat16)
+    Q = draw(B, Hq, n, D)
+    Kp, Vp = draw(B, Hkv, Lmax, D), draw(B, Hkv, Lmax, D)
+    Kt, Vt = draw(B, Hkv, n, D), draw(B, Hkv, n, D)
+    mask = _random_masks(B, n, 31)
+    out = api.tree_verify_attention(Q, Kp, Vp, Kt, Vt, torch.from_numpy(plen).cuda(), U.mask_to_device(mask))
+    torch.cuda.synchronize()
+    of = out.float()
+    assert bool(torch.isfinite(of).all())
+    assert bool((of.abs().amax(dim=(2, 3)) > 0).all())          # no (sequence, head) was left out
+    order = np.argsort(-eff, kind="stable")
+    picks = sorted({int(order[0]), int(order[1]), int(order[B // 2]), int(order[-1]), 1, 2, B - 1})
+    for b in picks:
+        for kvh in (0, Hkv - 1):
+            qh = slice(kvh * g, kvh * g + g)
+            sub = dict(Q=_stored(Q[b:b + 1, qh]), K_prefix=_stored(Kp[b:b + 1, kvh:kvh + 1]),
+                       V_prefix=_stored(Vp[b:b + 1, kvh:kvh + 1]), K_tree=_stored(Kt[b:b + 1, kvh:kvh + 1]),
+                       V_tree=_stored(Vt[b:b + 1, kvh:kvh + 1]), prefix_len=eff[b:b + 1])
+            want = _oracle_attention(sub, mask[b:b + 1], "bf16")
+            got = U.from_device_f64(out[b:b + 1, qh])
+            assert np.abs(got - want).max() < TOL["bf16"], (b, kvh, int(plen[b]))
+
+
 @pytest.mark.parametrize("dtype,B,Hq,Hkv,D,L,n,ragged,shape", [
     ("f32", 2, 4, 4, 64, 128, 16, 0.0, "random"),
     ("f32", 2, 6, 2, 128, 77, 37, 0.3, "random"),      # GQA, ragged, n not a multiple of 16

@@ -56,6 +56,7 @@ def _oracle(x, mask, scale=None, heads=None):
     (1, 8, 8, 64, 0, 33, 0.0, "star"),           # no prefix at all: tree keys only
     (3, 4, 2, 128, 65, 256, 0.5, "random"),      # the largest tree, short ragged prefixes (tree tiles dominate)
     (1, 2, 2, 128, 63, 1, 0.0, "random"),        # a single node
+    (33, 16, 8, 128, 150, 40, 0.5, "random"),    # a batch that fills the chip: jobs taken longest first
 ])
 def test_shapes_and_edges(B, Hq, Hkv, D, L, n, ragged, shape):
     x = _inputs(B, Hq, Hkv, D, L, n, ragged, 5)
