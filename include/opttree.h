@@ -50,8 +50,7 @@ extern "C" {
 #define OT_MAX_TOPK       16   /* k  */
 #define OT_MAX_DEPTH      32   /* d  */
 #define OT_MAX_HEAD_DIM  128
-#define OT_MAX_TREE_KEYS 8192     /* tree keys of the attention when they are more than the query rows (bf16) */
-#define OT_MAX_TREE_KEYS_F32 512  /* the same for f32 tensors */
+#define OT_MAX_TREE_KEYS 8192     /* tree keys of the attention when they are more than the query rows */
 #define OT_MASK_WORDS(n) (((n) + 63) / 64)
 
 OT_API int ot_version(void);                       /* 100*major + minor */
@@ -158,7 +157,7 @@ OT_API int ot_tree_finalize(const ot_build_params* p, int32_t steps_done,
  *   mask[b][s][0..W)  W = OT_MASK_WORDS(depth*n): bit j set iff pool node j is frontier node s or one of its
  *                     ancestors; rows s >= F are zero,
  * ready for ot_tree_verify_attention with n_keys = depth*n (at most OT_MAX_DEPTH * OT_MAX_NODES = OT_MAX_TREE_KEYS
- * pool nodes; f32 tensors: n_keys up to OT_MAX_TREE_KEYS_F32). */
+ * pool nodes). */
 OT_API int ot_tree_frontier_mask(const ot_build_params* p, int32_t steps_done,
                           void* workspace, size_t workspace_bytes, uint64_t* mask, void* hip_stream);
 

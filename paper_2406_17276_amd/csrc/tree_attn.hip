@@ -47,7 +47,6 @@ namespace {
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr int kMaxSplits = 32;
-constexpr int kMaskWordsF32 = 8;                              // the f32 kernel holds a mask row in eight registers
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
@@ -944,9 +943,8 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const AttnKArgs a) {
         if (rb * RB + rr < n) w = *(const f32x4*)(qbase + (long long)(rb * RB + rr) * a.qs[2] + cc);
         *(f32x4*)(s_q + rr * D + cc) = w;
     }
-    uint64_t mrow[kMaskWordsF32] = {0ull, 0ull, 0ull, 0ull, 0ull, 0ull, 0ull, 0ull};
-    if (row_ok)
-        for (int w = 0; w < a.W; ++w) mrow[w] = a.mask[((long long)b * n + node) * a.W + w];
+    // this row's ancestor mask: the 64-bit word that covers a 32-key tree tile is read with the tile
+    const uint64_t* const mask_row = a.mask + ((long long)b * n + (row_ok ? node : 0)) * a.W;
 
     const float* kp = (const float*)a.Kp + (long long)b * a.kps[0] + (long long)hk * a.kps[1];
     const float* vp = (const float*)a.Vp + (long long)b * a.vps[0] + (long long)hk * a.vps[1];
@@ -967,6 +965,7 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const AttnKArgs a) {
         const long long ks = tree ? a.kts[2] : a.kps[2];
         const long long vs = tree ? a.vts[2] : a.vps[2];
         __syncthreads();
+        const uint64_t mword = (tree && row_ok) ? mask_row[key0 >> 6] : 0ull;
         for (int i = tid; i < TK * D / 4; i += 256) {
             const int key = i / (D / 4), cc = (i % (D / 4)) * 4;
             f32x4 kw = {0.f, 0.f, 0.f, 0.f}, vw = {0.f, 0.f, 0.f, 0.f};
@@ -992,7 +991,7 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const AttnKArgs a) {
             }
             const int key = key0 + kl;
             bool ok = row_ok && key < kend;
-            if (tree) ok = ok && ((mrow[key >> 6] >> (key & 63)) & 1ull);
+            if (tree) ok = ok && ((mword >> (key & 63)) & 1ull);
             s2[u] = ok ? acc * a.scale_log2 : -INFINITY;
         }
         const float tmax = row16_max(fmaxf(s2[0], s2[1]));
@@ -1258,7 +1257,7 @@ static int validate_attn(const ot_attn_params* p, bool kv8 = false) {
     if (p->head_dim != 64 && p->head_dim != 128) return OT_ERR_UNSUPPORTED;
     if (p->n > OT_MAX_NODES) return OT_ERR_UNSUPPORTED;
     if (p->n_keys < 0) return OT_ERR_INVALID_ARG;
-    if (p->n_keys > (p->dtype == OT_BF16 ? OT_MAX_TREE_KEYS : OT_MAX_TREE_KEYS_F32)) return OT_ERR_UNSUPPORTED;
+    if (p->n_keys > OT_MAX_TREE_KEYS) return OT_ERR_UNSUPPORTED;
     if ((long long)p->batch * p->q_heads > 65535 || (long long)p->batch * p->q_heads * p->n > 0x7fffffffLL)
         return OT_ERR_UNSUPPORTED;
     if (kv8 && p->dtype != OT_BF16) return OT_ERR_INVALID_ARG;      // Q and O of the 8-bit cache variant are bf16

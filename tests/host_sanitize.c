@@ -112,7 +112,6 @@ int main(void) {
                         for (int dt = 0; dt < 2; ++dt)
                             for (int hd = 64; hd <= 128; hd += 64) {
                                 if (nks[e] && nks[e] < ns[d]) continue;
-                                if (dt == 0 && nks[e] > OT_MAX_TREE_KEYS_F32) continue;
                                 ot_attn_params p = attn(batches[c], heads[a][0], heads[a][1], hd, ns[d], prefixes[b], dt, nks[e]);
                                 const size_t need = ot_attn_workspace_bytes(&p);
                                 ++calls;
@@ -135,7 +134,7 @@ int main(void) {
         q = p; q.head_dim = 96; EXPECT(ot_attn_workspace_bytes(&q), 0);
         q = p; q.n = 0; EXPECT(ot_attn_workspace_bytes(&q), 0);
         q = p; q.n = 257; EXPECT(ot_attn_workspace_bytes(&q), 0);
-        q = p; q.n_keys = 513; EXPECT(ot_attn_workspace_bytes(&q), 0);          /* f32: at most 512 tree keys */
+        q = p; q.n_keys = OT_MAX_TREE_KEYS + 1; EXPECT(ot_attn_workspace_bytes(&q), 0);
         q = p; q.n_keys = -1; EXPECT(ot_attn_workspace_bytes(&q), 0);
         q = p; q.max_prefix = -1; EXPECT(ot_attn_workspace_bytes(&q), 0);
         q = p; q.q_strides[2] = 62; EXPECT(ot_attn_workspace_bytes(&q), 0);

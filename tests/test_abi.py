@@ -85,7 +85,7 @@ def test_attention_rejects_bad_arguments_without_launching():
     assert api.attn_workspace_bytes(_ap(head_dim=96)) == 0
     assert api.attn_workspace_bytes(_ap(n=0)) == 0
     assert api.attn_workspace_bytes(_ap(n=257)) == 0
-    assert api.attn_workspace_bytes(_ap(n_keys=513)) == 0
+    assert api.attn_workspace_bytes(_ap(n_keys=8193)) == 0
     assert api.attn_workspace_bytes(_ap(n_keys=-1)) == 0
     assert api.attn_workspace_bytes(_ap(n_keys=300)) > 0
     assert api.attn_workspace_bytes(_ap(q_strides=s(4096, 1024, 62))) == 0

@@ -296,6 +296,8 @@ def test_one_workspace_serves_consecutive_calls():
 
 @pytest.mark.parametrize("dtype,B,Hq,Hkv,D,L,k,n,d,upto", [
     ("f32", 2, 4, 2, 64, 90, 3, 12, 5, 4),          # 60 pool rows, one mask word
+    ("f32", 1, 4, 2, 64, 50, 10, 50, 12, 12),        # f32 beyond eight mask words: 600 pool keys
+    ("f32", 1, 2, 2, 128, 33, 16, 256, 7, 7),        # f32, the largest frontier: 1792 pool keys, 28 words
     ("bf16", 1, 8, 8, 128, 700, 10, 50, 10, 10),     # 7B-shaped drafting step: 50 queries, 500 pool keys, 8 words
     ("bf16", 2, 8, 2, 128, 300, 6, 40, 8, 6),        # packed GQA rows (128-row workgroups), 320 pool keys
     ("bf16", 1, 4, 4, 64, 0, 4, 64, 8, 3),           # no prefix, 512 pool keys of which 3 layers are filled
