@@ -116,9 +116,11 @@ OT_API int ot_build_tree_timed(const ot_build_params* p, const void* logits,
  * (E = 0 at the start), and drafting ends when E_sub - E <= delta or after p->depth steps.  The logits of
  * all p->depth steps are passed as for ot_build_tree; rows of steps that are not drafted are scanned but not
  * used.  steps_used[b] (int32, device) receives the number of steps drafted, e_sub[b] (double, device) the
- * last E_sub.  Only for the shapes that run on the single-wavefront path (n <= 64 and
- * (rows per sequence + 1) * k within the LDS budget -- the 7B, 13B and 70B shapes): OT_ERR_UNSUPPORTED
- * otherwise; the streaming calls below with ot_tree_esub cover every shape. */
+ * last E_sub.  Shapes on the single-wavefront path (n <= 64 and (rows per sequence + 1) * k within the LDS
+ * budget -- the 7B, 13B and 70B shapes) run the loop inside one kernel; all other shapes run it step by step on
+ * the stream with the kernels of the streaming calls below (the scan of a step's rows, the step, E_sub and the
+ * loop condition; a sequence that stops is frozen on the device, nothing is read back, and rows of steps that
+ * no sequence drafts are still scanned).  Either way the call returns without waiting for the device. */
 OT_API int ot_build_tree_adaptive(const ot_build_params* p, double delta, const void* logits,
                   void* workspace, size_t workspace_bytes,
                   const ot_tree_out* out, int32_t* steps_used, double* e_sub, void* hip_stream);

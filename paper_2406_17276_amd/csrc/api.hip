@@ -83,6 +83,11 @@ static int check_tree_out(const ot_tree_out* o) {
     return OT_OK;
 }
 
+__global__ void copy_i32_kernel(const int32_t* src, int32_t* dst, int count) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) dst[i] = src[i];
+}
+
 static SelectGeometry select_geometry(const ot_build_params& p, const Frontier& f) {
     SelectGeometry g;
     g.batch = p.batch; g.k = p.k; g.n = p.n; g.depth = p.depth;
@@ -167,10 +172,38 @@ int ot_build_tree_adaptive(const ot_build_params* p, double delta, const void* l
     if (st != OT_OK) return st;
     const Frontier f = make_frontier(p->k, p->n, p->depth);
     const SelectGeometry g = select_geometry(*p, f);
-    if (!tree_adaptive_supported(g)) return OT_ERR_UNSUPPORTED;
     const BuildWorkspace ws = carve_build_workspace(*p, workspace);
     if (workspace_bytes < ws.bytes) return OT_ERR_WORKSPACE_TOO_SMALL;
     hipStream_t s = (hipStream_t)hip_stream;
+    if (!tree_adaptive_supported(g)) {
+        // Shapes beyond the single-wavefront kernel (n > 64, large pools): the loop of Algorithm 1 as the streaming
+        // entry points run it, step by step on the stream -- scan of the step's F_t rows, selection, E_sub and the
+        // loop condition, all decided on the device (a sequence that stops is frozen there: later steps skip it,
+        // the final selection uses the layers it had), so the host neither waits nor reads anything back.  The
+        // frontier lists and the per-step decisions land in the output arrays, which the final selection overwrites.
+        st = launch_tree_begin(g, ws, s);
+        if (st != OT_OK) return st;
+        for (int t = 0; t < p->depth; ++t) {
+            ScanGeometry sg;
+            sg.batch = p->batch; sg.vocab = p->vocab; sg.k = p->k; sg.dtype = p->logits_dtype;
+            sg.nsteps = 1; sg.rows_per_seq = f.F[t];
+            sg.grow_k = 1; sg.grow_n = 1;
+            sg.stride_seq = p->stride_seq; sg.stride_depth = 0; sg.stride_row = p->stride_row;
+            st = launch_row_scan(sg, (const char*)logits + (size_t)t * p->stride_depth * esize, ws, s);
+            if (st != OT_OK) return st;
+            SelectGeometry gs = g;
+            gs.rows_per_seq = f.F[t];
+            st = launch_tree_step(gs, t, ws, out->token, out->parent, nullptr, s);
+            if (st != OT_OK) return st;
+            st = launch_tree_esub(g, t + 1, delta, ws, e_sub, out->depth, s);
+            if (st != OT_OK) return st;
+        }
+        st = launch_tree_finalize(g, p->depth, ws, *out, s);
+        if (st != OT_OK) return st;
+        hipLaunchKernelGGL(copy_i32_kernel, dim3((p->batch + 255) / 256), dim3(256), 0, s, ws.seq_steps, steps_used, p->batch);
+        OT_HIP_CHECK(hipGetLastError());
+        return OT_OK;
+    }
     ScanGeometry sg;
     sg.batch = p->batch; sg.vocab = p->vocab; sg.k = p->k; sg.dtype = p->logits_dtype;
     sg.nsteps = p->depth; sg.rows_per_seq = f.rows;

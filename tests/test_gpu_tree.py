@@ -316,6 +316,9 @@ def test_frontier_masks_of_the_drafting_phase_match_oracle(V, k, n, d, B):
     (2000, 6, 30, 8, 5, "f32", 0.01),
     (32000, 10, 50, 10, 2, "bf16", 0.02),      # 7B shape
     (500, 4, 64, 12, 3, "f32", 0.003),
+    (900, 4, 100, 7, 4, "f32", 0.004),         # n > 64: the step-by-step form inside the call
+    (3000, 16, 256, 5, 3, "bf16", 0.02),       # the widest frontier and k
+    (70000, 3, 70, 6, 2, "f32", 0.01),         # rows of three scan parts
 ])
 def test_one_shot_adaptive_build_matches_oracle(V, k, n, dmax, B, dtype, delta):
     """ot_build_tree_adaptive: the stopping rule of Algorithm 1 applied inside the kernel."""
@@ -341,9 +344,13 @@ def test_one_shot_adaptive_build_matches_oracle(V, k, n, dmax, B, dtype, delta):
     U.assert_tree_equal(got, want, n)
 
 
-def test_one_shot_adaptive_build_is_refused_off_the_single_wavefront_path():
+def test_one_shot_adaptive_build_with_a_threshold_nothing_passes_stops_after_one_step_at_any_width():
     import torch
     from paper_2406_17276_amd import api
-    x = torch.zeros((1, 3, 100, 64), dtype=torch.float32, device="cuda")
-    with pytest.raises(api.OptTreeError):
-        api.build_tree_adaptive(x, 2, 100, 3, 0.1)
+    g = np.random.default_rng(5)
+    x = g.standard_normal((2, 3, 100, 64)).astype(np.float32)
+    got, steps, e_sub = api.build_tree_adaptive(torch.from_numpy(x).cuda(), 2, 100, 3, 10.0)
+    torch.cuda.synchronize()
+    assert list(steps.cpu().numpy()) == [1, 1]
+    want = [ot_oracle.build_tree_adaptive(x[b].astype(np.float64), 2, 100, 3, 10.0) for b in range(2)]
+    U.assert_tree_equal(got, want, 100)
