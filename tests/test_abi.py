@@ -199,7 +199,8 @@ def test_one_shot_adaptive_build_rejects_bad_arguments_without_launching():
     assert call(p, 0.1, f, f, need, None, f) == -1
     assert call(p, 0.1, f, f, need, f, C.c_void_p(0x1004)) == -1        # e_sub is double[batch]
     assert call(p, 0.1, f, f, need - 1, f, f) == -3
-    assert call(_bp(n=100), 0.1, f, f, api.build_workspace_bytes(_bp(n=100)), f, f) == -2   # n beyond one wavefront
+    # (n beyond one wavefront is served step by step: the same argument checks apply before anything is launched)
+    assert call(_bp(n=100), 0.1, f, f, api.build_workspace_bytes(_bp(n=100)) - 1, f, f) == -3
 
 
 def test_verify_rejects_bad_arguments_without_launching():
