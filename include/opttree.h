@@ -119,8 +119,8 @@ OT_API int ot_build_tree_timed(const ot_build_params* p, const void* logits,
  * last E_sub.  Shapes on the single-wavefront path (n <= 64 and (rows per sequence + 1) * k within the LDS
  * budget -- the 7B, 13B and 70B shapes) run the loop inside one kernel; all other shapes run it step by step on
  * the stream with the kernels of the streaming calls below (the scan of a step's rows, the step, E_sub and the
- * loop condition; a sequence that stops is frozen on the device, nothing is read back, and rows of steps that
- * no sequence drafts are still scanned).  Either way the call returns without waiting for the device. */
+ * loop condition; a sequence that stops is frozen on the device, nothing is read back, and the rows of the steps
+ * it does not draft are not read).  Either way the call returns without waiting for the device. */
 OT_API int ot_build_tree_adaptive(const ot_build_params* p, double delta, const void* logits,
                   void* workspace, size_t workspace_bytes,
                   const ot_tree_out* out, int32_t* steps_used, double* e_sub, void* hip_stream);
@@ -170,7 +170,8 @@ OT_API int ot_tree_frontier_mask(const ot_build_params* p, int32_t steps_done,
  *              E over the root-containing n-node subtrees of T; non-decreasing in the steps, Thm. 3.2),
  *   go_on[b] = 1 if e_sub[b] - E[b] > delta, and then E[b] <- e_sub[b]; else 0.   (E[b] = 0 after begin.)
  * e_sub (double[batch]) and go_on (int32[batch]) are device pointers.  A sequence whose go_on was 0 is
- * frozen: later ot_tree_expand calls leave its tree and its frontier outputs untouched, later ot_tree_esub
+ * frozen: later ot_tree_expand calls do not read its rows and leave its tree and its frontier outputs untouched,
+ * later ot_tree_esub
  * calls return go_on = 0 for it, and ot_tree_finalize selects among the layers it had when it stopped.
  * The caller ends the loop when no go_on is set or the maximum depth p->depth is reached.
  * Returns OT_ERR_INVALID_ARG for steps_done outside 1..depth, a NaN delta, or null / misaligned pointers. */

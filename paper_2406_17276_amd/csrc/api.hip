@@ -189,7 +189,7 @@ int ot_build_tree_adaptive(const ot_build_params* p, double delta, const void* l
             sg.nsteps = 1; sg.rows_per_seq = f.F[t];
             sg.grow_k = 1; sg.grow_n = 1;
             sg.stride_seq = p->stride_seq; sg.stride_depth = 0; sg.stride_row = p->stride_row;
-            st = launch_row_scan(sg, (const char*)logits + (size_t)t * p->stride_depth * esize, ws, s);
+            st = launch_row_scan(sg, (const char*)logits + (size_t)t * p->stride_depth * esize, ws, s, nullptr, nullptr, true);
             if (st != OT_OK) return st;
             SelectGeometry gs = g;
             gs.rows_per_seq = f.F[t];
@@ -248,7 +248,7 @@ int ot_tree_expand(const ot_build_params* p, int32_t step, const void* rows, int
     sg.nsteps = 1; sg.rows_per_seq = f.F[step];
     sg.grow_k = 1; sg.grow_n = 1;
     sg.stride_seq = stride_seq; sg.stride_depth = 0; sg.stride_row = stride_row;
-    st = launch_row_scan(sg, rows, ws, s);
+    st = launch_row_scan(sg, rows, ws, s, nullptr, nullptr, true);      // rows of frozen sequences are not read
     if (st != OT_OK) return st;
     SelectGeometry g = select_geometry(*p, f);
     g.rows_per_seq = f.F[step];

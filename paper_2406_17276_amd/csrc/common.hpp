@@ -71,8 +71,9 @@ struct ScanGeometry {
 };
 
 // ev0/ev1 (optional): events that receive the begin and end time stamps of the scan kernel itself
+// skip_frozen: rows of sequences whose ws.seq_active flag is 0 (stopped by the rule of Algorithm 1) are not read
 int launch_row_scan(const ScanGeometry& g, const void* logits, const BuildWorkspace& ws, hipStream_t s,
-                    hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr);
+                    hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr, bool skip_frozen = false);
 
 struct SelectGeometry {
     int batch, k, n, depth;

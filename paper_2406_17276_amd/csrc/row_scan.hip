@@ -34,6 +34,7 @@ struct ScanKArgs {
     // P == 1: final row results; P > 1: per-part results
     double* row_lse; float* row_topv; int32_t* row_topi;
     float* part_m; double* part_s; float* part_topv; int32_t* part_topi;
+    const int32_t* seq_active;        // SKIP kernels: rows of sequence b are left unread when seq_active[b] == 0
 };
 
 __device__ __forceinline__ unsigned int f32_key(float v) {
@@ -378,19 +379,27 @@ __device__ __forceinline__ void scan_item(const ScanHead& h, const ScanKArgs& a,
 // Launches of up to kScanMaxGrid items have one workgroup per item; larger ones (long-vocabulary, large-batch
 // shapes with 10^5..10^6 items) are walked with a grid stride, because starting a workgroup costs about as
 // much as a small item's share of the memory traffic.
-template <int DT, int NT, int EPL, bool VECLOAD>
+// SKIP: the scan of one drafting step in the loop of Algorithm 1 -- a sequence that the stopping rule has frozen
+// drafts no further, and its rows are not read (the flag is the step kernel's own, on the device).
+__device__ __forceinline__ bool scan_item_frozen(const ScanKArgs& a, int part_geom, int rows_per_seq, int wg) {
+    const int rid = wg / (part_geom & 15);
+    return a.seq_active[rid / rows_per_seq] == 0;
+}
+template <int DT, int NT, int EPL, bool VECLOAD, bool SKIP>
 __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu((NT == 1024 && VECLOAD) ? 8 : 4, 8))) void row_scan_kernel(
     const void* logits, const long long stride_seq, const long long stride_depth, const long long stride_row,
     const int vocab, const int part_geom, const int rows_per_seq, const int grow, const ScanKArgs a) {
+    if (SKIP && scan_item_frozen(a, part_geom, rows_per_seq, blockIdx.x)) return;
     const ScanHead h{logits, stride_seq, stride_depth, stride_row, vocab, part_geom, rows_per_seq, grow};
     scan_item<DT, NT, EPL, VECLOAD>(h, a, blockIdx.x);
 }
-template <int DT, int NT, int EPL, bool VECLOAD>
+template <int DT, int NT, int EPL, bool VECLOAD, bool SKIP>
 __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu((NT == 1024 && VECLOAD) ? 8 : 4, 8))) void row_scan_strided_kernel(
     const void* logits, const long long stride_seq, const long long stride_depth, const long long stride_row,
     const int vocab, const int part_geom, const int rows_per_seq, const int grow, const ScanKArgs a) {
     const ScanHead h{logits, stride_seq, stride_depth, stride_row, vocab, part_geom, rows_per_seq, grow};
     for (int wg = blockIdx.x; wg < a.items; wg += gridDim.x) {
+        if (SKIP && scan_item_frozen(a, part_geom, rows_per_seq, wg)) continue;      // (the whole workgroup skips)
         scan_item<DT, NT, EPL, VECLOAD>(h, a, wg);
         if (wg + (int)gridDim.x < a.items) __syncthreads();      // the next item reuses the shared arrays
     }
@@ -445,7 +454,7 @@ __global__ __launch_bounds__(256) void merge_parts_kernel(int rows, int parts, i
 }  // namespace
 
 int launch_row_scan(const ScanGeometry& g, const void* logits, const BuildWorkspace& ws, hipStream_t s, hipEvent_t ev0,
-                    hipEvent_t ev1) {
+                    hipEvent_t ev1, bool skip_frozen) {
     const int parts = scan_parts(g.vocab);
     if (parts > 8) return OT_ERR_UNSUPPORTED;
     const int esize = g.dtype == OT_BF16 ? 2 : 4;
@@ -460,6 +469,7 @@ int launch_row_scan(const ScanGeometry& g, const void* logits, const BuildWorksp
     const int grow = g.nsteps | (g.grow_k << 8) | (g.grow_n << 16);
     a.row_lse = ws.row_lse; a.row_topv = ws.row_topv; a.row_topi = ws.row_topi;
     a.part_m = ws.part_m; a.part_s = ws.part_s; a.part_topv = ws.part_topv; a.part_topi = ws.part_topi;
+    a.seq_active = skip_frozen ? ws.seq_active : nullptr;
 
     const bool aligned = ((uintptr_t)logits % 16 == 0) && (g.stride_seq % vec == 0) && (g.stride_depth % vec == 0) &&
                          (g.stride_row % vec == 0) && (g.vocab % vec == 0);
@@ -471,14 +481,15 @@ int launch_row_scan(const ScanGeometry& g, const void* logits, const BuildWorksp
     const dim3 gd((unsigned)(grid <= kScanMaxGrid ? grid : kScanMaxGrid));
 
 #define OT_SCAN_ARGS logits, g.stride_seq, g.stride_depth, g.stride_row, g.vocab, part_geom, g.rows_per_seq, grow, a
-#define OT_SCAN_LAUNCH(DT, NT, VL)                                                                       \
+#define OT_SCAN_LAUNCH2(DT, NT, VL, SK)                                                                  \
     do {                                                                                                 \
         if (grid > kScanMaxGrid) {                                                                       \
-            if (ev0 || ev1) hipExtLaunchKernelGGL((row_scan_strided_kernel<DT, NT, 32, VL>), gd, dim3(NT), 0, s, ev0, ev1, 0, OT_SCAN_ARGS); \
-            else hipLaunchKernelGGL((row_scan_strided_kernel<DT, NT, 32, VL>), gd, dim3(NT), 0, s, OT_SCAN_ARGS);   \
-        } else if (ev0 || ev1) hipExtLaunchKernelGGL((row_scan_kernel<DT, NT, 32, VL>), gd, dim3(NT), 0, s, ev0, ev1, 0, OT_SCAN_ARGS); \
-        else hipLaunchKernelGGL((row_scan_kernel<DT, NT, 32, VL>), gd, dim3(NT), 0, s, OT_SCAN_ARGS);               \
+            if (ev0 || ev1) hipExtLaunchKernelGGL((row_scan_strided_kernel<DT, NT, 32, VL, SK>), gd, dim3(NT), 0, s, ev0, ev1, 0, OT_SCAN_ARGS); \
+            else hipLaunchKernelGGL((row_scan_strided_kernel<DT, NT, 32, VL, SK>), gd, dim3(NT), 0, s, OT_SCAN_ARGS);   \
+        } else if (ev0 || ev1) hipExtLaunchKernelGGL((row_scan_kernel<DT, NT, 32, VL, SK>), gd, dim3(NT), 0, s, ev0, ev1, 0, OT_SCAN_ARGS); \
+        else hipLaunchKernelGGL((row_scan_kernel<DT, NT, 32, VL, SK>), gd, dim3(NT), 0, s, OT_SCAN_ARGS);               \
     } while (0)
+#define OT_SCAN_LAUNCH(DT, NT, VL) do { if (skip_frozen) OT_SCAN_LAUNCH2(DT, NT, VL, true); else OT_SCAN_LAUNCH2(DT, NT, VL, false); } while (0)
     if (g.dtype == OT_BF16) {
         if (small) { if (aligned) OT_SCAN_LAUNCH(OT_BF16, 256, true); else OT_SCAN_LAUNCH(OT_BF16, 256, false); }
         else       { if (aligned) OT_SCAN_LAUNCH(OT_BF16, 1024, true); else OT_SCAN_LAUNCH(OT_BF16, 1024, false); }
@@ -486,6 +497,7 @@ int launch_row_scan(const ScanGeometry& g, const void* logits, const BuildWorksp
         if (small) { if (aligned) OT_SCAN_LAUNCH(OT_F32, 256, true); else OT_SCAN_LAUNCH(OT_F32, 256, false); }
         else       { if (aligned) OT_SCAN_LAUNCH(OT_F32, 1024, true); else OT_SCAN_LAUNCH(OT_F32, 1024, false); }
     }
+#undef OT_SCAN_LAUNCH2
 #undef OT_SCAN_LAUNCH
 #undef OT_SCAN_ARGS
     OT_HIP_CHECK(hipGetLastError());
