@@ -171,8 +171,8 @@ OT_API int ot_tree_frontier_mask(const ot_build_params* p, int32_t steps_done,
  *   go_on[b] = 1 if e_sub[b] - E[b] > delta, and then E[b] <- e_sub[b]; else 0.   (E[b] = 0 after begin.)
  * e_sub (double[batch]) and go_on (int32[batch]) are device pointers.  A sequence whose go_on was 0 is
  * frozen: later ot_tree_expand calls do not read its rows and leave its tree and its frontier outputs untouched,
- * later ot_tree_esub
- * calls return go_on = 0 for it, and ot_tree_finalize selects among the layers it had when it stopped.
+ * later ot_tree_esub calls return go_on = 0 for it, and ot_tree_finalize selects among the layers it had when it
+ * stopped.
  * The caller ends the loop when no go_on is set or the maximum depth p->depth is reached.
  * Returns OT_ERR_INVALID_ARG for steps_done outside 1..depth, a NaN delta, or null / misaligned pointers. */
 OT_API int ot_tree_esub(const ot_build_params* p, int32_t steps_done, double delta,
