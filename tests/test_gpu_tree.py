@@ -319,6 +319,7 @@ def test_frontier_masks_of_the_drafting_phase_match_oracle(V, k, n, d, B):
     (900, 4, 100, 7, 4, "f32", 0.004),         # n > 64: the step-by-step form inside the call
     (3000, 16, 256, 5, 3, "bf16", 0.02),       # the widest frontier and k
     (70000, 3, 70, 6, 2, "f32", 0.01),         # rows of three scan parts
+    (200, 16, 64, 26, 2, "f32", 0.002),        # one wavefront wide, but the row table exceeds LDS: step by step as well
 ])
 def test_one_shot_adaptive_build_matches_oracle(V, k, n, dmax, B, dtype, delta):
     """ot_build_tree_adaptive: the stopping rule of Algorithm 1 applied inside the kernel."""
