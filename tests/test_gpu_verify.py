@@ -29,6 +29,7 @@ def _target_rows(tree, n, V, g, agree, dtype):
     (300, 1, 8, 8, 2, "f32", 1.0),             # a chain, accepted whole: A = n + 1
     (300, 3, 200, 3, 1, "f32", 0.5),           # n larger than the tree (n_out < n)
     (2000, 8, 256, 6, 1, "bf16", 0.9),         # maximum n
+    (32000, 8, 60, 10, 16, "bf16", 0.9),       # the 70B batch: 16 sequences, 61 target rows each
 ])
 def test_verify_and_append_match_oracle(V, k, n, d, B, dtype, agree):
     import torch
@@ -107,6 +108,7 @@ def _tree_to_device(api, trees, B, n):
     (32000, 10, 50, 10, 2, "bf16", 0.9, 1.0),      # 7B shape
     (40000, 5, 70, 6, 2, "bf16", 0.95, 0.7),
     (300, 3, 200, 3, 1, "f32", 0.5, 1.5),          # n larger than the tree
+    (32000, 8, 60, 10, 16, "bf16", 0.9, 0.8),      # the 70B batch
 ])
 def test_sampled_verification_matches_oracle(V, k, n, d, B, dtype, agree, T):
     import torch
